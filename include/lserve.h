@@ -1,0 +1,202 @@
+/*
+ * lserve.h -- C ABI of the unified block-sparse attention path of LServe (arxiv 2502.14866)
+ * for AMD MI355X (gfx950).
+ *
+ * Four operations, one GPU, no hidden state:
+ *   lserve_sparse_prefill    block-sparse causal prefill attention (Sec. 3.1, Sec. 3.4)
+ *   lserve_build_page_stats  per-logical-page channel-wise key min / max (Sec. 3.5.2)
+ *   lserve_select_pages      query-centric page scores (Eq. 2), max over logical pages,
+ *                            top-K physical pages under a token budget (Sec. 3.5.2)
+ *   lserve_sparse_decode     paged decode attention over an index table (Sec. 3.6)
+ *
+ * Conventions common to every call
+ *   - "device" pointers are HIP device memory owned by the caller; "host" pointers are ordinary
+ *     host memory.  The library allocates nothing, frees nothing and keeps no state between calls.
+ *     Buffers are borrowed until the work enqueued by the call has completed on `stream`.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Calls validate their
+ *     arguments on the host, enqueue kernels and return; they never synchronise.
+ *   - Return value: LSERVE_OK (0) or a negative LSERVE_ERR_* code.  Nothing is printed, nothing
+ *     aborts.  After LSERVE_ERR_HIP, lserve_last_hip_error() returns the hipError_t value.
+ *   - Device-side data errors (a page id outside the pool, a sequence length of 0 or beyond
+ *     max_pages_per_seq * page_size, a selected page >= the sequence's page count, duplicates in a
+ *     selection) are not detected and give undefined results.
+ *   - All device pointers must be 16-byte aligned.  Element type of Q/K/V/O/pools/stats is IEEE
+ *     binary16 (dtype 0) or bfloat16 (dtype 1); accumulation is fp32.
+ *   - Results are deterministic: the same inputs give bit-identical outputs (fixed reduction
+ *     orders, no floating-point atomics).
+ *
+ * Symbols (paper notation): H query heads, Hkv KV heads, n = H / Hkv, D head dimension (128),
+ * N_P tokens per physical page, N_L tokens per logical page, g = N_P / N_L, L_b current KV length
+ * of sequence b, P_b = ceil(L_b / N_P), K = floor(budget / N_P).
+ */
+#ifndef LSERVE_H
+#define LSERVE_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define LSERVE_OK 0
+#define LSERVE_ERR_INVALID_ARG (-1) /* null / misaligned pointer, non-positive size, bad page sizes, budget < N_P */
+#define LSERVE_ERR_UNSUPPORTED (-2) /* head_dim != 128, unknown dtype, H % Hkv != 0, Hkv > 64, n > 8, g > 8 */
+#define LSERVE_ERR_WORKSPACE (-3)   /* workspace missing or smaller than lserve_workspace_bytes() */
+#define LSERVE_ERR_HIP (-4)         /* a HIP call failed; see lserve_last_hip_error() */
+
+#define LSERVE_DTYPE_FP16 0
+#define LSERVE_DTYPE_BF16 1
+
+/* which_call values for lserve_workspace_bytes() */
+#define LSERVE_CALL_BUILD_PAGE_STATS 0
+#define LSERVE_CALL_SELECT_PAGES 1
+#define LSERVE_CALL_SPARSE_PREFILL 2
+#define LSERVE_CALL_SPARSE_DECODE 3
+
+/*
+ * Attention layer description (Sec. 2.1 for H, Hkv, D; Sec. 3.1 for streaming heads and their
+ * sink / local sizes; Sec. 3.5.2 for N_P and N_L).
+ *
+ * The streaming pattern is tile granular (Sec. 3.1: a tile is kept whole or skipped whole):
+ * s = ceil(sink_tokens / N_P) leading tiles and w = ceil(local_tokens / N_P) trailing tiles,
+ * the query's own tile included, are kept; inside kept tiles only causality masks.  The prefill
+ * mask tile and the decode page are both N_P tokens, so prefill row t and a decode step at
+ * length t + 1 attend the same tokens.
+ */
+typedef struct lserve_attn_desc {
+    int32_t num_q_heads;       /* H */
+    int32_t num_kv_heads;      /* Hkv, H % Hkv == 0, Hkv <= 64, H / Hkv <= 8 */
+    int32_t head_dim;          /* D, must be 128 */
+    int32_t page_size;         /* N_P: 16, 32, 64 or 128; prefill requires 64 */
+    int32_t logical_page_size; /* N_L: divides N_P, N_P / N_L <= 8, N_L >= 1 */
+    int32_t dtype;             /* LSERVE_DTYPE_* */
+    int32_t sink_tokens;       /* >= 0, rounded up to whole tiles */
+    int32_t local_tokens;      /* >= 1, rounded up to whole tiles */
+    const uint8_t *kv_head_is_streaming; /* HOST, [Hkv], 1 = streaming head, 0 = dense / selecting head */
+    float sm_scale;            /* softmax scale; 0 means 1 / sqrt(D) */
+} lserve_attn_desc;
+
+/*
+ * Paged KV cache (Sec. 2.1 "Paged Attention"; Sec. 3.5.2 for the statistics).
+ * Token t of sequence b is slot t % N_P of physical page page_table[b][t / N_P].
+ */
+typedef struct lserve_paged_kv {
+    void *k_pool;              /* device, [num_pages][Hkv][N_P][D] */
+    void *v_pool;              /* device, [num_pages][Hkv][N_P][D] */
+    void *stats;               /* device, [num_pages][Hkv][g][2][D]; [..][0][:] = max, [..][1][:] = min */
+    const int32_t *page_table; /* device, [batch][max_pages_per_seq], physical page ids in [0, num_pages) */
+    const int32_t *seq_lens;   /* device, [batch], 1 <= L_b <= max_pages_per_seq * N_P */
+    int32_t batch;
+    int32_t max_pages_per_seq;
+    int32_t num_pages;
+} lserve_paged_kv;
+
+/*
+ * Key statistics (Sec. 3.5.2; caption of the hierarchical-paging figure): for every non-streaming
+ * KV head, every logical page that overlaps tokens [start_pos[b], L_b) of sequence b and every
+ * channel c, write max and min of K[t][c] over the page's valid tokens t < L_b into kv->stats.
+ * Statistics of logical pages without a valid token are not written.
+ *
+ *   start_pos      device [batch] or NULL (= 0 for every sequence: full rebuild after prefill).
+ *                  After appending one token call with start_pos[b] = L_b - 1.
+ *   max_tail_pages host hint: no sequence has more than this many physical pages overlapping
+ *                  [start_pos, L_b); 0 = unknown (all max_pages_per_seq are visited).  A too small
+ *                  hint leaves the oldest pages of the range stale.
+ * Reads kv->k_pool, page_table, seq_lens; writes kv->stats.  No workspace.
+ */
+int lserve_build_page_stats(const lserve_attn_desc *desc, const lserve_paged_kv *kv,
+                            const int32_t *start_pos, int32_t max_tail_pages, void *stream);
+
+/*
+ * Page selection (Eq. 2 and the paragraph after it; Sec. 3.2 "shorter page tables").
+ * For every sequence b and non-streaming KV head hk:
+ *   logical page score  S_h^l = sum_c max(q_h[c] * kmax^l[c], q_h[c] * kmin^l[c])   (no 1/sqrt(D)),
+ *   group score         = max over the n query heads h of KV head hk,
+ *   physical page score = max over the page's logical pages that hold a valid token,
+ *   selection           = all P_b pages if P_b <= K, else page P_b - 1 (newest token) plus the
+ *                         K - 1 best-scoring other pages, a tie going to the lower page index.
+ * Scores are accumulated in fp32 in a fixed order.
+ *
+ *   q            device [batch][H][D]
+ *   budget_tokens  K = budget_tokens / N_P, must be >= 1
+ *   sel_pages    device [batch][Hkv][K] out: positions of the selected pages inside the sequence
+ *                (indices into page_table[b]), ascending; entries past sel_count are -1.
+ *                Rows of streaming heads are filled with -1.
+ *   sel_count    device [batch][Hkv] out (0 for streaming heads)
+ *   sel_seq_len  device [batch] out: L_b at selection time
+ *   scores_out   device [batch][Hkv][max_pages_per_seq] fp32 or NULL: physical page scores
+ *                (entries p >= P_b and rows of streaming heads are 0)
+ *   workspace    device, >= lserve_workspace_bytes(LSERVE_CALL_SELECT_PAGES, ...)
+ */
+int lserve_select_pages(const lserve_attn_desc *desc, const lserve_paged_kv *kv, const void *q,
+                        int32_t budget_tokens, int32_t *sel_pages, int32_t *sel_count,
+                        int32_t *sel_seq_len, float *scores_out, void *workspace,
+                        size_t workspace_bytes, void *stream);
+
+/*
+ * Block-sparse causal prefill (Eq. 1 under the block mask of Sec. 3.1; Sec. 3.4).
+ * Tokens of all sequences are concatenated.  For the token at position t of its sequence and
+ * query head h (KV head h / n), the allowed keys are the positions u <= t of the same sequence
+ * with, for a streaming head, tile(u) < s or tile(u) > tile(t) - w, tile(x) = x / 64.
+ * out = softmax(scale * q . k_u over allowed u) applied to v_u; tiles with no allowed pair are
+ * never loaded.
+ *
+ *   q            device [total_tokens][H][D]
+ *   k, v         device [total_tokens][Hkv][D]
+ *   cu_seqlens   device [batch + 1], cu_seqlens[0] = 0, cu_seqlens[batch] = total_tokens
+ *   max_seqlen   host: upper bound of the sequence lengths (sizes the launch)
+ *   out          device [total_tokens][H][D]
+ *   lse_out      device [H][total_tokens] fp32 or NULL: natural-log sum of exp of the scaled scores
+ *   workspace    device, >= lserve_workspace_bytes(LSERVE_CALL_SPARSE_PREFILL, ...) (may be 0 bytes)
+ * Requires desc->page_size == 64 (the mask tile).
+ */
+int lserve_sparse_prefill(const lserve_attn_desc *desc, const void *q, const void *k, const void *v,
+                          const int32_t *cu_seqlens, int32_t batch, int32_t total_tokens,
+                          int32_t max_seqlen, void *out, float *lse_out, void *workspace,
+                          size_t workspace_bytes, void *stream);
+
+/*
+ * Paged sparse decode (Eq. 1 over the pages of an index table; Sec. 3.6).
+ * One query token per sequence; its K/V are already in the pool and counted in L_b.
+ * Page list of KV head hk:
+ *   streaming head: pages p < s and pages p > P_b - 1 - w (sink and local pages, each once);
+ *                   its rows of sel_pages / sel_count are ignored;
+ *   selecting head: sel_pages[b][hk][0 .. sel_count) followed by every page
+ *                   p >= ceil(sel_seq_len[b] / N_P), i.e. pages created since the selection
+ *                   (reusable page selection, Sec. 3.5.3).
+ * All n query heads of the group attend the valid tokens (u < L_b) of the listed pages.
+ *
+ *   q            device [batch][H][D]
+ *   sel_pages    device [batch][Hkv][sel_stride], sel_count device [batch][Hkv],
+ *   sel_seq_len  device [batch]; all three may be NULL when every KV head is streaming
+ *   out          device [batch][H][D]
+ *   lse_out      device [batch][H] fp32 or NULL
+ *   workspace    device, >= lserve_workspace_bytes(LSERVE_CALL_SPARSE_DECODE, ...)
+ */
+int lserve_sparse_decode(const lserve_attn_desc *desc, const lserve_paged_kv *kv, const void *q,
+                         const int32_t *sel_pages, const int32_t *sel_count,
+                         const int32_t *sel_seq_len, int32_t sel_stride, void *out, float *lse_out,
+                         void *workspace, size_t workspace_bytes, void *stream);
+
+/*
+ * Bytes of device workspace a call needs (Sec. 3.6 / 3.5.2 calls keep partial results there).
+ *   batch, max_pages_per_seq: as in lserve_paged_kv (ignored for prefill)
+ *   sel_stride_or_budget_pages: K for select, sel_stride for decode (ignored otherwise)
+ *   total_tokens: prefill only
+ * Returns 0 when the call needs none or when desc is invalid.
+ */
+size_t lserve_workspace_bytes(int which_call, const lserve_attn_desc *desc, int32_t batch,
+                              int32_t max_pages_per_seq, int32_t sel_stride_or_budget_pages,
+                              int32_t total_tokens);
+
+/* Human-readable text for a return code (static storage). */
+const char *lserve_strerror(int code);
+
+/* hipError_t of the last failed HIP call on the calling thread (0 if none). */
+int lserve_last_hip_error(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* LSERVE_H */

@@ -1,0 +1,199 @@
+"""ctypes binding of liblserve.so: argument marshalling only, every step runs in the HIP kernels."""
+from __future__ import annotations
+
+import ctypes
+import os
+from dataclasses import dataclass
+from typing import Optional, Sequence
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(_HERE, "liblserve.so")
+_lib = None
+
+LSERVE_CALL_BUILD_PAGE_STATS = 0
+LSERVE_CALL_SELECT_PAGES = 1
+LSERVE_CALL_SPARSE_PREFILL = 2
+LSERVE_CALL_SPARSE_DECODE = 3
+
+EXPORTED_SYMBOLS = (
+    "lserve_build_page_stats",
+    "lserve_select_pages",
+    "lserve_sparse_prefill",
+    "lserve_sparse_decode",
+    "lserve_workspace_bytes",
+    "lserve_strerror",
+    "lserve_last_hip_error",
+)
+
+
+class LserveError(RuntimeError):
+    def __init__(self, code: int, where: str):
+        self.code = code
+        super().__init__(f"{where} failed with code {code}: {lserve_strerror(code)}"
+                         + (f" (hipError_t {lserve_last_hip_error()})" if code == -4 else ""))
+
+
+class _CAttnDesc(ctypes.Structure):
+    _fields_ = [
+        ("num_q_heads", ctypes.c_int32), ("num_kv_heads", ctypes.c_int32), ("head_dim", ctypes.c_int32),
+        ("page_size", ctypes.c_int32), ("logical_page_size", ctypes.c_int32), ("dtype", ctypes.c_int32),
+        ("sink_tokens", ctypes.c_int32), ("local_tokens", ctypes.c_int32),
+        ("kv_head_is_streaming", ctypes.POINTER(ctypes.c_uint8)), ("sm_scale", ctypes.c_float),
+    ]
+
+
+class _CPagedKV(ctypes.Structure):
+    _fields_ = [
+        ("k_pool", ctypes.c_void_p), ("v_pool", ctypes.c_void_p), ("stats", ctypes.c_void_p),
+        ("page_table", ctypes.c_void_p), ("seq_lens", ctypes.c_void_p),
+        ("batch", ctypes.c_int32), ("max_pages_per_seq", ctypes.c_int32), ("num_pages", ctypes.c_int32),
+    ]
+
+
+def library_path() -> str:
+    return _LIB_PATH
+
+
+def load_library():
+    """Load liblserve.so; raises if it has not been built (there is no fallback path)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(_LIB_PATH):
+            raise FileNotFoundError(
+                f"{_LIB_PATH} is missing: build it with `python -m paper_2502_14866_amd.build` "
+                "(or __graft_entry__.build()); there is no CPU fallback")
+        lib = ctypes.CDLL(_LIB_PATH)
+        vp, i32, sz = ctypes.c_void_p, ctypes.c_int32, ctypes.c_size_t
+        dp, kp = ctypes.POINTER(_CAttnDesc), ctypes.POINTER(_CPagedKV)
+        lib.lserve_build_page_stats.argtypes = [dp, kp, vp, i32, vp]
+        lib.lserve_select_pages.argtypes = [dp, kp, vp, i32, vp, vp, vp, vp, vp, sz, vp]
+        lib.lserve_sparse_prefill.argtypes = [dp, vp, vp, vp, vp, i32, i32, i32, vp, vp, vp, sz, vp]
+        lib.lserve_sparse_decode.argtypes = [dp, kp, vp, vp, vp, vp, i32, vp, vp, vp, sz, vp]
+        lib.lserve_workspace_bytes.argtypes = [ctypes.c_int, dp, i32, i32, i32, i32]
+        lib.lserve_workspace_bytes.restype = sz
+        lib.lserve_strerror.argtypes = [ctypes.c_int]
+        lib.lserve_strerror.restype = ctypes.c_char_p
+        lib.lserve_last_hip_error.restype = ctypes.c_int
+        for name in ("lserve_build_page_stats", "lserve_select_pages", "lserve_sparse_prefill",
+                     "lserve_sparse_decode"):
+            getattr(lib, name).restype = ctypes.c_int
+        _lib = lib
+    return _lib
+
+
+@dataclass
+class AttnDesc:
+    """Mirror of lserve_attn_desc."""
+    num_q_heads: int
+    num_kv_heads: int
+    streaming_flags: Sequence[int]
+    head_dim: int = 128
+    page_size: int = 64
+    logical_page_size: int = 16
+    dtype: torch.dtype = torch.float16
+    sink_tokens: int = 128
+    local_tokens: int = 512
+    sm_scale: float = 0.0
+
+    def __post_init__(self):
+        flags = [1 if f else 0 for f in self.streaming_flags]
+        self._flags = (ctypes.c_uint8 * max(1, len(flags)))(*flags)
+        self._c = _CAttnDesc(
+            self.num_q_heads, self.num_kv_heads, self.head_dim, self.page_size, self.logical_page_size,
+            {torch.float16: 0, torch.bfloat16: 1}.get(self.dtype, -1), self.sink_tokens, self.local_tokens,
+            ctypes.cast(self._flags, ctypes.POINTER(ctypes.c_uint8)), float(self.sm_scale))
+
+    def c(self):
+        return ctypes.byref(self._c)
+
+
+@dataclass
+class PagedKV:
+    """Mirror of lserve_paged_kv; keeps the tensors alive."""
+    k_pool: Optional[torch.Tensor]
+    v_pool: Optional[torch.Tensor]
+    stats: Optional[torch.Tensor]
+    page_table: torch.Tensor
+    seq_lens: torch.Tensor
+
+    def c(self):
+        num_pages = 0
+        for t in (self.k_pool, self.v_pool, self.stats):
+            if t is not None:
+                num_pages = t.shape[0]
+        self._c = _CPagedKV(_ptr(self.k_pool), _ptr(self.v_pool), _ptr(self.stats), _ptr(self.page_table),
+                            _ptr(self.seq_lens), self.page_table.shape[0], self.page_table.shape[1], num_pages)
+        return ctypes.byref(self._c)
+
+
+def _ptr(t: Optional[torch.Tensor]):
+    if t is None:
+        return None
+    if not t.is_contiguous():
+        raise ValueError("lserve binding takes contiguous tensors")
+    return ctypes.c_void_p(t.data_ptr())
+
+
+def _stream(stream) -> ctypes.c_void_p:
+    if stream is None:
+        stream = torch.cuda.current_stream()
+    return ctypes.c_void_p(stream.cuda_stream if hasattr(stream, "cuda_stream") else int(stream))
+
+
+def _check(rc: int, where: str) -> None:
+    if rc != 0:
+        raise LserveError(rc, where)
+
+
+def lserve_strerror(code: int) -> str:
+    return load_library().lserve_strerror(int(code)).decode()
+
+
+def lserve_last_hip_error() -> int:
+    return int(load_library().lserve_last_hip_error())
+
+
+def lserve_workspace_bytes(which_call: int, desc: AttnDesc, batch: int = 0, max_pages_per_seq: int = 0,
+                           sel_stride_or_budget_pages: int = 0, total_tokens: int = 0) -> int:
+    return int(load_library().lserve_workspace_bytes(which_call, desc.c(), batch, max_pages_per_seq,
+                                                     sel_stride_or_budget_pages, total_tokens))
+
+
+def lserve_build_page_stats(desc: AttnDesc, kv: PagedKV, start_pos: Optional[torch.Tensor] = None,
+                            max_tail_pages: int = 0, stream=None) -> None:
+    _check(load_library().lserve_build_page_stats(desc.c(), kv.c(), _ptr(start_pos), max_tail_pages,
+                                                  _stream(stream)), "lserve_build_page_stats")
+
+
+def lserve_select_pages(desc: AttnDesc, kv: PagedKV, q: torch.Tensor, budget_tokens: int,
+                        sel_pages: torch.Tensor, sel_count: torch.Tensor, sel_seq_len: torch.Tensor,
+                        scores_out: Optional[torch.Tensor] = None, workspace: Optional[torch.Tensor] = None,
+                        stream=None) -> None:
+    ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    _check(load_library().lserve_select_pages(desc.c(), kv.c(), _ptr(q), budget_tokens, _ptr(sel_pages),
+                                              _ptr(sel_count), _ptr(sel_seq_len), _ptr(scores_out),
+                                              _ptr(workspace), ws_bytes, _stream(stream)), "lserve_select_pages")
+
+
+def lserve_sparse_prefill(desc: AttnDesc, q: torch.Tensor, k: torch.Tensor, v: torch.Tensor,
+                          cu_seqlens: torch.Tensor, max_seqlen: int, out: torch.Tensor,
+                          lse_out: Optional[torch.Tensor] = None, workspace: Optional[torch.Tensor] = None,
+                          stream=None) -> None:
+    ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    _check(load_library().lserve_sparse_prefill(desc.c(), _ptr(q), _ptr(k), _ptr(v), _ptr(cu_seqlens),
+                                                cu_seqlens.shape[0] - 1, q.shape[0], max_seqlen, _ptr(out),
+                                                _ptr(lse_out), _ptr(workspace), ws_bytes, _stream(stream)),
+           "lserve_sparse_prefill")
+
+
+def lserve_sparse_decode(desc: AttnDesc, kv: PagedKV, q: torch.Tensor, sel_pages: Optional[torch.Tensor],
+                         sel_count: Optional[torch.Tensor], sel_seq_len: Optional[torch.Tensor],
+                         out: torch.Tensor, lse_out: Optional[torch.Tensor] = None,
+                         workspace: Optional[torch.Tensor] = None, stream=None) -> None:
+    ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    sel_stride = 0 if sel_pages is None else sel_pages.shape[-1]
+    _check(load_library().lserve_sparse_decode(desc.c(), kv.c(), _ptr(q), _ptr(sel_pages), _ptr(sel_count),
+                                               _ptr(sel_seq_len), sel_stride, _ptr(out), _ptr(lse_out),
+                                               _ptr(workspace), ws_bytes, _stream(stream)), "lserve_sparse_decode")

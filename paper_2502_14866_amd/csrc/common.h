@@ -1,0 +1,117 @@
+// Device-side helpers shared by the gfx950 kernels: 16-bit storage types, wavefront (64 lanes)
+// cross-lane reductions built on DPP, and the launch-parameter block every kernel receives.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace lserve {
+
+constexpr int kWave = 64;       // CDNA wavefront width
+constexpr int kHeadDim = 128;   // D; every kernel is specialised for it
+constexpr int kMaxGroup = 8;    // n = H / Hkv
+constexpr int kMaxLogical = 8;  // g = N_P / N_L
+
+typedef _Float16 half2_t __attribute__((ext_vector_type(2)));
+typedef __bf16 bf162_t __attribute__((ext_vector_type(2)));
+
+struct F16 {};
+struct BF16 {};
+
+template <class T> struct Elem;
+
+// Two 16-bit elements travel in one 32-bit register; element 0 is the low half.
+template <> struct Elem<F16> {
+    static __device__ __forceinline__ float lo(uint32_t u) { return (float)__builtin_bit_cast(half2_t, u)[0]; }
+    static __device__ __forceinline__ float hi(uint32_t u) { return (float)__builtin_bit_cast(half2_t, u)[1]; }
+    // c + a.lo * b.lo + a.hi * b.hi with fp32 accumulation (v_dot2_f32_f16)
+    static __device__ __forceinline__ float dot2(uint32_t a, uint32_t b, float c) {
+        return __builtin_amdgcn_fdot2(__builtin_bit_cast(half2_t, a), __builtin_bit_cast(half2_t, b), c, false);
+    }
+    static __device__ __forceinline__ uint32_t pack(float a, float b) {
+        half2_t h = {(_Float16)a, (_Float16)b};  // round to nearest even
+        return __builtin_bit_cast(uint32_t, h);
+    }
+};
+
+template <> struct Elem<BF16> {
+    static __device__ __forceinline__ float lo(uint32_t u) { return __builtin_bit_cast(float, u << 16); }
+    static __device__ __forceinline__ float hi(uint32_t u) { return __builtin_bit_cast(float, u & 0xffff0000u); }
+    static __device__ __forceinline__ float dot2(uint32_t a, uint32_t b, float c) {
+        return __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf162_t, a), __builtin_bit_cast(bf162_t, b), c, false);
+    }
+    static __device__ __forceinline__ uint32_t pack(float a, float b) {
+        bf162_t h = {(__bf16)a, (__bf16)b};  // round to nearest even
+        return __builtin_bit_cast(uint32_t, h);
+    }
+};
+
+// ---- DPP cross-lane primitives (row = 16 consecutive lanes) ------------------------------------
+
+template <int Ctrl> __device__ __forceinline__ float dpp_f(float x) {
+    return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, x), Ctrl, 0xf, 0xf, true));
+}
+
+constexpr int kDppXor1 = 0xB1;         // quad_perm [1,0,3,2]
+constexpr int kDppXor2 = 0x4E;         // quad_perm [2,3,0,1]
+constexpr int kDppHalfMirror = 0x141;  // lane i <-> 7 - i inside each 8 lanes
+constexpr int kDppMirror = 0x140;      // lane i <-> 15 - i inside each row
+
+// Sum over the 16 lanes of a row; every lane of the row receives the total.
+__device__ __forceinline__ float row16_sum(float x) {
+    x += dpp_f<kDppXor1>(x);
+    x += dpp_f<kDppXor2>(x);
+    x += dpp_f<kDppHalfMirror>(x);
+    x += dpp_f<kDppMirror>(x);
+    return x;
+}
+
+__device__ __forceinline__ float shfl_xor_f(float x, int mask) { return __shfl_xor(x, mask, kWave); }
+
+// Reductions across the four rows of a wave (lanes l, l^16, l^32, l^48 hold peers).
+__device__ __forceinline__ float rows4_sum(float x) {
+    x += shfl_xor_f(x, 16);
+    x += shfl_xor_f(x, 32);
+    return x;
+}
+__device__ __forceinline__ float rows4_max(float x) {
+    x = fmaxf(x, shfl_xor_f(x, 16));
+    x = fmaxf(x, shfl_xor_f(x, 32));
+    return x;
+}
+__device__ __forceinline__ float rows4_min(float x) {
+    x = fminf(x, shfl_xor_f(x, 16));
+    x = fminf(x, shfl_xor_f(x, 32));
+    return x;
+}
+
+__device__ __forceinline__ float wave_max(float x) {
+    x = fmaxf(x, dpp_f<kDppXor1>(x));
+    x = fmaxf(x, dpp_f<kDppXor2>(x));
+    x = fmaxf(x, dpp_f<kDppHalfMirror>(x));
+    x = fmaxf(x, dpp_f<kDppMirror>(x));
+    return rows4_max(x);
+}
+
+__host__ __device__ __forceinline__ int ceil_div(int a, int b) { return (a + b - 1) / b; }
+
+// ---- parameters ----------------------------------------------------------------------------------
+
+struct LayerParams {
+    int H, Hkv, group;       // query heads, KV heads, n = H / Hkv
+    int NP, NL, g;           // physical / logical page size, logical pages per physical page
+    int sink_pages;          // s = ceil(sink_tokens / NP)
+    int local_pages;         // w = ceil(local_tokens / NP)
+    unsigned long long streaming_mask;  // bit hk set = KV head hk is a streaming head
+    float sm_scale_log2;     // softmax scale * log2(e)
+};
+
+struct PagedParams {
+    const void *k_pool, *v_pool;
+    void* stats;
+    const int* page_table;
+    const int* seq_lens;
+    int batch, max_pages, num_pages;
+};
+
+}  // namespace lserve

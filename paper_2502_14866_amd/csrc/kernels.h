@@ -1,0 +1,35 @@
+// Host-visible launchers of the gfx950 kernels.  The C ABI (lserve_api.hip) validates arguments
+// and calls these; each returns the hipError_t of its launch.
+#pragma once
+
+#include "common.h"
+
+namespace lserve {
+
+// Compact list of KV head indices (e.g. the non-streaming heads), passed by value to kernels.
+struct HeadList {
+    int count;
+    unsigned char idx[64];
+};
+
+hipError_t launch_page_stats(int dtype, const LayerParams& lp, const PagedParams& kv, const int* start_pos,
+                             int tail_pages, const HeadList& heads, hipStream_t stream);
+
+hipError_t launch_select_pages(int dtype, const LayerParams& lp, const PagedParams& kv, const void* q,
+                               int budget_pages, int* sel_pages, int* sel_count, int* sel_seq_len,
+                               float* scores, bool scores_is_user_buffer, const HeadList& selecting,
+                               hipStream_t stream);
+
+size_t decode_workspace_bytes(const LayerParams& lp, int batch, int sel_stride);
+
+hipError_t launch_sparse_decode(int dtype, const LayerParams& lp, const PagedParams& kv, const void* q,
+                                const int* sel_pages, const int* sel_count, const int* sel_seq_len,
+                                int sel_stride, void* out, float* lse_out, void* workspace, hipStream_t stream);
+
+size_t prefill_workspace_bytes(const LayerParams& lp, int total_tokens, int batch);
+
+hipError_t launch_sparse_prefill(int dtype, const LayerParams& lp, const void* q, const void* k, const void* v,
+                                 const int* cu_seqlens, int batch, int total_tokens, int max_seqlen, void* out,
+                                 float* lse_out, void* workspace, hipStream_t stream);
+
+}  // namespace lserve

@@ -1,0 +1,206 @@
+// C ABI of the library (see include/lserve.h): host-side argument validation, translation of the
+// public structs into kernel parameter blocks, and launches on the caller's stream.  No device
+// memory is allocated or freed here and no state survives a call.
+#include "../../include/lserve.h"
+
+#include <cmath>
+
+#include "kernels.h"
+
+using namespace lserve;
+
+namespace {
+
+thread_local int g_last_hip_error = 0;
+
+bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+int fail_hip(hipError_t e) {
+    g_last_hip_error = (int)e;
+    return LSERVE_ERR_HIP;
+}
+
+// Validates the layer description and fills the kernel parameter block.
+int make_layer(const lserve_attn_desc* d, LayerParams* lp) {
+    if (!d || !d->kv_head_is_streaming) return LSERVE_ERR_INVALID_ARG;
+    if (d->num_q_heads <= 0 || d->num_kv_heads <= 0 || d->page_size <= 0 || d->logical_page_size <= 0)
+        return LSERVE_ERR_INVALID_ARG;
+    if (d->sink_tokens < 0 || d->local_tokens < 1) return LSERVE_ERR_INVALID_ARG;
+    if (d->page_size % d->logical_page_size != 0) return LSERVE_ERR_INVALID_ARG;
+    if (!(d->sm_scale >= 0.f) || std::isinf(d->sm_scale)) return LSERVE_ERR_INVALID_ARG;
+    if (d->head_dim != kHeadDim) return LSERVE_ERR_UNSUPPORTED;
+    if (d->dtype != LSERVE_DTYPE_FP16 && d->dtype != LSERVE_DTYPE_BF16) return LSERVE_ERR_UNSUPPORTED;
+    if (d->num_q_heads % d->num_kv_heads != 0) return LSERVE_ERR_UNSUPPORTED;
+    if (d->num_kv_heads > 64 || d->num_q_heads / d->num_kv_heads > kMaxGroup) return LSERVE_ERR_UNSUPPORTED;
+    if (d->page_size != 16 && d->page_size != 32 && d->page_size != 64 && d->page_size != 128)
+        return LSERVE_ERR_UNSUPPORTED;
+    if (d->page_size / d->logical_page_size > kMaxLogical) return LSERVE_ERR_UNSUPPORTED;
+    lp->H = d->num_q_heads;
+    lp->Hkv = d->num_kv_heads;
+    lp->group = lp->H / lp->Hkv;
+    lp->NP = d->page_size;
+    lp->NL = d->logical_page_size;
+    lp->g = lp->NP / lp->NL;
+    lp->sink_pages = (d->sink_tokens + lp->NP - 1) / lp->NP;
+    lp->local_pages = (d->local_tokens + lp->NP - 1) / lp->NP;
+    lp->streaming_mask = 0;
+    for (int h = 0; h < lp->Hkv; ++h)
+        if (d->kv_head_is_streaming[h]) lp->streaming_mask |= 1ull << h;
+    const float scale = d->sm_scale > 0.f ? d->sm_scale : 1.0f / std::sqrt((float)kHeadDim);
+    lp->sm_scale_log2 = scale * 1.4426950408889634f;
+    return LSERVE_OK;
+}
+
+int make_paged(const lserve_paged_kv* kv, bool need_k, bool need_v, bool need_stats, PagedParams* pp) {
+    if (!kv || !kv->page_table || !kv->seq_lens) return LSERVE_ERR_INVALID_ARG;
+    if (kv->batch <= 0 || kv->max_pages_per_seq <= 0 || kv->num_pages <= 0) return LSERVE_ERR_INVALID_ARG;
+    if (kv->batch > 65535) return LSERVE_ERR_UNSUPPORTED;
+    if ((need_k && !kv->k_pool) || (need_v && !kv->v_pool) || (need_stats && !kv->stats)) return LSERVE_ERR_INVALID_ARG;
+    if (!aligned16(kv->k_pool) || !aligned16(kv->v_pool) || !aligned16(kv->stats) || !aligned16(kv->page_table) ||
+        !aligned16(kv->seq_lens))
+        return LSERVE_ERR_INVALID_ARG;
+    pp->k_pool = kv->k_pool;
+    pp->v_pool = kv->v_pool;
+    pp->stats = kv->stats;
+    pp->page_table = kv->page_table;
+    pp->seq_lens = kv->seq_lens;
+    pp->batch = kv->batch;
+    pp->max_pages = kv->max_pages_per_seq;
+    pp->num_pages = kv->num_pages;
+    return LSERVE_OK;
+}
+
+HeadList selecting_heads(const LayerParams& lp) {
+    HeadList hl;
+    hl.count = 0;
+    for (int h = 0; h < lp.Hkv; ++h)
+        if (!((lp.streaming_mask >> h) & 1ull)) hl.idx[hl.count++] = (unsigned char)h;
+    return hl;
+}
+
+size_t select_workspace_bytes(const LayerParams& lp, int batch, int max_pages) {
+    return (size_t)batch * lp.Hkv * max_pages * sizeof(float);
+}
+
+}  // namespace
+
+extern "C" {
+
+int lserve_build_page_stats(const lserve_attn_desc* desc, const lserve_paged_kv* kv, const int32_t* start_pos,
+                            int32_t max_tail_pages, void* stream) {
+    LayerParams lp;
+    PagedParams pp;
+    int rc = make_layer(desc, &lp);
+    if (rc) return rc;
+    rc = make_paged(kv, true, false, true, &pp);
+    if (rc) return rc;
+    if (max_tail_pages < 0 || !aligned16(start_pos)) return LSERVE_ERR_INVALID_ARG;
+    const int tail = (max_tail_pages == 0 || max_tail_pages > pp.max_pages) ? pp.max_pages : max_tail_pages;
+    hipError_t e = launch_page_stats(desc->dtype, lp, pp, start_pos, tail, selecting_heads(lp), (hipStream_t)stream);
+    return e == hipSuccess ? LSERVE_OK : fail_hip(e);
+}
+
+int lserve_select_pages(const lserve_attn_desc* desc, const lserve_paged_kv* kv, const void* q, int32_t budget_tokens,
+                        int32_t* sel_pages, int32_t* sel_count, int32_t* sel_seq_len, float* scores_out,
+                        void* workspace, size_t workspace_bytes, void* stream) {
+    LayerParams lp;
+    PagedParams pp;
+    int rc = make_layer(desc, &lp);
+    if (rc) return rc;
+    rc = make_paged(kv, false, false, true, &pp);
+    if (rc) return rc;
+    if (!q || !sel_pages || !sel_count || !sel_seq_len) return LSERVE_ERR_INVALID_ARG;
+    if (!aligned16(q) || !aligned16(sel_pages) || !aligned16(sel_count) || !aligned16(sel_seq_len) ||
+        !aligned16(scores_out) || !aligned16(workspace))
+        return LSERVE_ERR_INVALID_ARG;
+    if (budget_tokens < lp.NP) return LSERVE_ERR_INVALID_ARG;
+    float* scores = scores_out;
+    if (!scores) {
+        if (!workspace || workspace_bytes < select_workspace_bytes(lp, pp.batch, pp.max_pages)) return LSERVE_ERR_WORKSPACE;
+        scores = reinterpret_cast<float*>(workspace);
+    }
+    hipError_t e = launch_select_pages(desc->dtype, lp, pp, q, budget_tokens / lp.NP, sel_pages, sel_count, sel_seq_len,
+                                       scores, scores_out != nullptr, selecting_heads(lp), (hipStream_t)stream);
+    return e == hipSuccess ? LSERVE_OK : fail_hip(e);
+}
+
+int lserve_sparse_prefill(const lserve_attn_desc* desc, const void* q, const void* k, const void* v,
+                          const int32_t* cu_seqlens, int32_t batch, int32_t total_tokens, int32_t max_seqlen, void* out,
+                          float* lse_out, void* workspace, size_t workspace_bytes, void* stream) {
+    LayerParams lp;
+    int rc = make_layer(desc, &lp);
+    if (rc) return rc;
+    if (!q || !k || !v || !cu_seqlens || !out) return LSERVE_ERR_INVALID_ARG;
+    if (batch <= 0 || total_tokens <= 0 || max_seqlen <= 0 || max_seqlen > total_tokens) return LSERVE_ERR_INVALID_ARG;
+    if (batch > 65535) return LSERVE_ERR_UNSUPPORTED;
+    if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(out) || !aligned16(cu_seqlens) ||
+        !aligned16(lse_out) || !aligned16(workspace))
+        return LSERVE_ERR_INVALID_ARG;
+    if (lp.NP != 64) return LSERVE_ERR_UNSUPPORTED;
+    if (!workspace || workspace_bytes < prefill_workspace_bytes(lp, total_tokens, batch)) return LSERVE_ERR_WORKSPACE;
+    hipError_t e = launch_sparse_prefill(desc->dtype, lp, q, k, v, cu_seqlens, batch, total_tokens, max_seqlen, out,
+                                         lse_out, workspace, (hipStream_t)stream);
+    return e == hipSuccess ? LSERVE_OK : fail_hip(e);
+}
+
+int lserve_sparse_decode(const lserve_attn_desc* desc, const lserve_paged_kv* kv, const void* q,
+                         const int32_t* sel_pages, const int32_t* sel_count, const int32_t* sel_seq_len,
+                         int32_t sel_stride, void* out, float* lse_out, void* workspace, size_t workspace_bytes,
+                         void* stream) {
+    LayerParams lp;
+    PagedParams pp;
+    int rc = make_layer(desc, &lp);
+    if (rc) return rc;
+    rc = make_paged(kv, true, true, false, &pp);
+    if (rc) return rc;
+    if (!q || !out) return LSERVE_ERR_INVALID_ARG;
+    const bool any_selecting = selecting_heads(lp).count > 0;
+    if (any_selecting && (!sel_pages || !sel_count || !sel_seq_len || sel_stride <= 0)) return LSERVE_ERR_INVALID_ARG;
+    if (sel_stride < 0) return LSERVE_ERR_INVALID_ARG;
+    if (!aligned16(q) || !aligned16(out) || !aligned16(sel_pages) || !aligned16(sel_count) || !aligned16(sel_seq_len) ||
+        !aligned16(lse_out) || !aligned16(workspace))
+        return LSERVE_ERR_INVALID_ARG;
+    if (!workspace || workspace_bytes < decode_workspace_bytes(lp, pp.batch, sel_stride)) return LSERVE_ERR_WORKSPACE;
+    hipError_t e = launch_sparse_decode(desc->dtype, lp, pp, q, sel_pages, sel_count, sel_seq_len, sel_stride, out,
+                                        lse_out, workspace, (hipStream_t)stream);
+    return e == hipSuccess ? LSERVE_OK : fail_hip(e);
+}
+
+size_t lserve_workspace_bytes(int which_call, const lserve_attn_desc* desc, int32_t batch, int32_t max_pages_per_seq,
+                              int32_t sel_stride_or_budget_pages, int32_t total_tokens) {
+    LayerParams lp;
+    if (make_layer(desc, &lp) != LSERVE_OK) return 0;
+    switch (which_call) {
+        case LSERVE_CALL_SELECT_PAGES:
+            return batch > 0 && max_pages_per_seq > 0 ? select_workspace_bytes(lp, batch, max_pages_per_seq) : 0;
+        case LSERVE_CALL_SPARSE_PREFILL:
+            return batch > 0 && total_tokens > 0 ? prefill_workspace_bytes(lp, total_tokens, batch) : 0;
+        case LSERVE_CALL_SPARSE_DECODE:
+            return batch > 0 && sel_stride_or_budget_pages >= 0
+                       ? decode_workspace_bytes(lp, batch, sel_stride_or_budget_pages)
+                       : 0;
+        default:
+            return 0;
+    }
+}
+
+const char* lserve_strerror(int code) {
+    switch (code) {
+        case LSERVE_OK:
+            return "success";
+        case LSERVE_ERR_INVALID_ARG:
+            return "invalid argument (null or misaligned pointer, non-positive size, bad page sizes or budget)";
+        case LSERVE_ERR_UNSUPPORTED:
+            return "unsupported configuration (head_dim, dtype, head counts or page size)";
+        case LSERVE_ERR_WORKSPACE:
+            return "workspace missing or too small";
+        case LSERVE_ERR_HIP:
+            return "a HIP call failed (see lserve_last_hip_error)";
+        default:
+            return "unknown error code";
+    }
+}
+
+int lserve_last_hip_error(void) { return g_last_hip_error; }
+
+}  // extern "C"

@@ -1,0 +1,273 @@
+// Hierarchical page selector (Sec. 3.5.2): Eq. 2 scores from the per-logical-page key statistics,
+// max over the query heads of a GQA group and over the logical pages of a physical page, then the
+// top-K physical pages per (sequence, KV head).
+//
+// Scoring is a bandwidth-bound scan of the statistics (2 KiB per page and head for N_P = 64,
+// N_L = 16): 16 lanes read the max row and the min row of one logical page with 16-byte loads.
+// Because kmax >= kmin, max(q*kmax, q*kmin) = max(q,0)*kmax + min(q,0)*kmin, so each channel costs
+// two packed dot-product lanes and no compare.  Top-K is a 4-pass radix select on an order-
+// preserving integer image of the fp32 score, followed by an index-ordered compaction, so the
+// output is ascending and ties resolve to the lower page index.
+#include "kernels.h"
+
+namespace lserve {
+
+namespace {
+
+constexpr int kScoreThreads = 256;  // 4 waves, 4 pages per wave (one per 16-lane row)
+constexpr int kPagesPerBlock = 16;
+constexpr int kTopkThreads = 512;
+
+__device__ __forceinline__ unsigned orderable(float s) {
+    unsigned u = __builtin_bit_cast(unsigned, s);
+    return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
+}
+
+template <class T, int N>
+__global__ __launch_bounds__(kScoreThreads) void page_score_kernel(LayerParams lp, PagedParams kv,
+                                                                    const uint4* __restrict__ q,
+                                                                    float* __restrict__ scores, HeadList heads) {
+    const int b = blockIdx.z;
+    const int hk = heads.idx[blockIdx.y];
+    const int lane = threadIdx.x % kWave, wave = threadIdx.x / kWave;
+    const int r = lane / 16, c = lane % 16;
+    const int L = kv.seq_lens[b];
+    const int P = ceil_div(L, lp.NP);
+    const int p = (blockIdx.x * (kScoreThreads / kWave) + wave) * 4 + r;
+    if (p >= kv.max_pages) return;
+    float* dst = scores + ((size_t)b * lp.Hkv + hk) * kv.max_pages + p;
+    if (p >= P) {  // whole row (16 lanes) takes this branch together
+        if (c == 0) *dst = 0.f;
+        return;
+    }
+
+    // positive and negative parts of the group's queries for this lane's 8 channels
+    uint32_t qpos[N][4], qneg[N][4];
+#pragma unroll
+    for (int hh = 0; hh < N; ++hh) {
+        uint4 x = q[((size_t)b * lp.H + hk * N + hh) * (kHeadDim / 8) + c];
+        const uint32_t w[4] = {x.x, x.y, x.z, x.w};
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            float a = Elem<T>::lo(w[i]), d = Elem<T>::hi(w[i]);
+            qpos[hh][i] = Elem<T>::pack(fmaxf(a, 0.f), fmaxf(d, 0.f));
+            qneg[hh][i] = Elem<T>::pack(fminf(a, 0.f), fminf(d, 0.f));
+        }
+    }
+
+    const int phys = kv.page_table[(size_t)b * kv.max_pages + p];
+    const uint4* st = reinterpret_cast<const uint4*>(kv.stats) + ((size_t)phys * lp.Hkv + hk) * lp.g * 2 * (kHeadDim / 8);
+    float best = -INFINITY;
+    for (int j = 0; j < lp.g; ++j) {
+        if (p * lp.NP + j * lp.NL >= L) break;  // logical pages without a valid token
+        uint4 mx = st[(size_t)(j * 2) * (kHeadDim / 8) + c];
+        uint4 mn = st[(size_t)(j * 2 + 1) * (kHeadDim / 8) + c];
+        const uint32_t wx[4] = {mx.x, mx.y, mx.z, mx.w};
+        const uint32_t wn[4] = {mn.x, mn.y, mn.z, mn.w};
+#pragma unroll
+        for (int hh = 0; hh < N; ++hh) {
+            float s = 0.f;
+#pragma unroll
+            for (int i = 0; i < 4; ++i) s = Elem<T>::dot2(qpos[hh][i], wx[i], s);
+#pragma unroll
+            for (int i = 0; i < 4; ++i) s = Elem<T>::dot2(qneg[hh][i], wn[i], s);
+            best = fmaxf(best, row16_sum(s));
+        }
+    }
+    if (c == 0) *dst = best + 0.f;  // +0 canonicalises a negative zero
+}
+
+// Inclusive scan of (a, b) pairs over the block; returns this thread's exclusive prefix and the totals.
+__device__ __forceinline__ void block_exclusive_scan2(int a, int b, int* lds /* 2 * waves */, int& ea, int& eb,
+                                                      int& ta, int& tb) {
+    const int lane = threadIdx.x % kWave, wave = threadIdx.x / kWave, nw = blockDim.x / kWave;
+    int ia = a, ib = b;
+#pragma unroll
+    for (int d = 1; d < kWave; d <<= 1) {
+        int ua = __shfl_up(ia, d, kWave), ub = __shfl_up(ib, d, kWave);
+        if (lane >= d) {
+            ia += ua;
+            ib += ub;
+        }
+    }
+    if (lane == kWave - 1) {
+        lds[wave] = ia;
+        lds[nw + wave] = ib;
+    }
+    __syncthreads();
+    int oa = 0, ob = 0;
+    ta = 0;
+    tb = 0;
+    for (int w = 0; w < nw; ++w) {
+        if (w < wave) {
+            oa += lds[w];
+            ob += lds[nw + w];
+        }
+        ta += lds[w];
+        tb += lds[nw + w];
+    }
+    ea = oa + ia - a;
+    eb = ob + ib - b;
+    __syncthreads();
+}
+
+__global__ __launch_bounds__(kTopkThreads) void topk_pages_kernel(LayerParams lp, PagedParams kv, int K,
+                                                                   const float* __restrict__ scores,
+                                                                   float* __restrict__ user_scores,
+                                                                   int* __restrict__ sel_pages,
+                                                                   int* __restrict__ sel_count,
+                                                                   int* __restrict__ sel_seq_len) {
+    __shared__ int hist[256];
+    __shared__ int scan_lds[2 * kTopkThreads / kWave];
+    __shared__ unsigned s_prefix;
+    __shared__ int s_need;
+
+    const int b = blockIdx.y, hk = blockIdx.x, tid = threadIdx.x;
+    const int L = kv.seq_lens[b];
+    const int P = ceil_div(L, lp.NP);
+    int* out = sel_pages + ((size_t)b * lp.Hkv + hk) * K;
+    if (hk == 0 && tid == 0) sel_seq_len[b] = L;
+
+    if ((lp.streaming_mask >> hk) & 1ull) {  // streaming heads take no selection
+        for (int i = tid; i < K; i += blockDim.x) out[i] = -1;
+        if (user_scores)
+            for (int i = tid; i < kv.max_pages; i += blockDim.x)
+                user_scores[((size_t)b * lp.Hkv + hk) * kv.max_pages + i] = 0.f;
+        if (tid == 0) sel_count[b * lp.Hkv + hk] = 0;
+        return;
+    }
+    if (P <= K) {  // the budget covers the whole context
+        for (int i = tid; i < K; i += blockDim.x) out[i] = i < P ? i : -1;
+        if (tid == 0) sel_count[b * lp.Hkv + hk] = P;
+        return;
+    }
+
+    const float* sc = scores + ((size_t)b * lp.Hkv + hk) * kv.max_pages;
+    const int M = P - 1;  // candidates: every page but the newest, which is always kept
+    int need = K - 1;     // how many candidates to take
+    unsigned threshold = 0xffffffffu;
+    int need_eq = 0;
+    if (need > 0) {
+        // radix select: after the four passes s_prefix is the key of the need-th best candidate
+        if (tid == 0) {
+            s_prefix = 0;
+            s_need = need;
+        }
+        unsigned mask = 0;
+        for (int shift = 24; shift >= 0; shift -= 8) {
+            for (int i = tid; i < 256; i += blockDim.x) hist[i] = 0;
+            __syncthreads();
+            const unsigned prefix = s_prefix;
+            for (int i = tid; i < M; i += blockDim.x) {
+                unsigned key = orderable(sc[i]);
+                if ((key & mask) == prefix) atomicAdd(&hist[(key >> shift) & 255u], 1);
+            }
+            __syncthreads();
+            if (tid < kWave) {
+                // lane l owns buckets 255-4l .. 252-4l; walk from the highest bucket down
+                int h0 = hist[255 - 4 * tid], h1 = hist[254 - 4 * tid], h2 = hist[253 - 4 * tid], h3 = hist[252 - 4 * tid];
+                int tot = h0 + h1 + h2 + h3, inc = tot;
+#pragma unroll
+                for (int d = 1; d < kWave; d <<= 1) {
+                    int u = __shfl_up(inc, d, kWave);
+                    if (tid >= d) inc += u;
+                }
+                const int want = s_need;
+                const int above = inc - tot;  // candidates in higher buckets than this lane's
+                if (above < want && inc >= want) {
+                    int bucket = 255 - 4 * tid, acc = above;
+                    if (acc + h0 < want) {
+                        acc += h0;
+                        --bucket;
+                        if (acc + h1 < want) {
+                            acc += h1;
+                            --bucket;
+                            if (acc + h2 < want) {
+                                acc += h2;
+                                --bucket;
+                            }
+                        }
+                    }
+                    s_prefix = prefix | ((unsigned)bucket << shift);
+                    s_need = want - acc;
+                }
+            }
+            mask |= 0xffu << shift;
+            __syncthreads();
+        }
+        threshold = s_prefix;
+        need_eq = s_need;  // candidates equal to the threshold still to take, lowest indices first
+    }
+
+    // index-ordered compaction: each thread owns a contiguous range of pages
+    const int per = ceil_div(M, (int)blockDim.x);
+    const int i0 = min(M, tid * per), i1 = min(M, i0 + per);
+    int gt = 0, eq = 0;
+    for (int i = i0; i < i1; ++i) {
+        unsigned key = orderable(sc[i]);
+        gt += key > threshold;
+        eq += key == threshold;
+    }
+    int egt, eeq, tgt, teq;
+    block_exclusive_scan2(gt, eq, scan_lds, egt, eeq, tgt, teq);
+    int pos = egt + min(eeq, need_eq);
+    int eq_seen = eeq;
+    for (int i = i0; i < i1; ++i) {
+        unsigned key = orderable(sc[i]);
+        bool take = key > threshold;
+        if (key == threshold) {
+            take = eq_seen < need_eq;
+            ++eq_seen;
+        }
+        if (take && pos < K - 1) out[pos++] = i;  // the bound only matters for non-finite scores
+    }
+    if (tid == 0) {
+        out[K - 1] = P - 1;
+        sel_count[b * lp.Hkv + hk] = K;
+    }
+}
+
+template <class T>
+hipError_t launch_score(const LayerParams& lp, const PagedParams& kv, const void* q, float* scores,
+                        const HeadList& selecting, hipStream_t stream) {
+    dim3 grid(ceil_div(kv.max_pages, kPagesPerBlock), selecting.count, kv.batch);
+    dim3 block(kScoreThreads);
+    const uint4* q4 = reinterpret_cast<const uint4*>(q);
+#define LSERVE_SCORE_CASE(N)                                                                                   \
+    case N:                                                                                                    \
+        hipLaunchKernelGGL((page_score_kernel<T, N>), grid, block, 0, stream, lp, kv, q4, scores, selecting);  \
+        break;
+    switch (lp.group) {
+        LSERVE_SCORE_CASE(1)
+        LSERVE_SCORE_CASE(2)
+        LSERVE_SCORE_CASE(3)
+        LSERVE_SCORE_CASE(4)
+        LSERVE_SCORE_CASE(5)
+        LSERVE_SCORE_CASE(6)
+        LSERVE_SCORE_CASE(7)
+        LSERVE_SCORE_CASE(8)
+        default:
+            return hipErrorInvalidValue;
+    }
+#undef LSERVE_SCORE_CASE
+    return hipGetLastError();
+}
+
+}  // namespace
+
+hipError_t launch_select_pages(int dtype, const LayerParams& lp, const PagedParams& kv, const void* q,
+                               int budget_pages, int* sel_pages, int* sel_count, int* sel_seq_len,
+                               float* scores, bool scores_is_user_buffer, const HeadList& selecting,
+                               hipStream_t stream) {
+    if (selecting.count > 0) {
+        hipError_t e = dtype == 0 ? launch_score<F16>(lp, kv, q, scores, selecting, stream)
+                                  : launch_score<BF16>(lp, kv, q, scores, selecting, stream);
+        if (e != hipSuccess) return e;
+    }
+    dim3 grid(lp.Hkv, kv.batch);
+    hipLaunchKernelGGL(topk_pages_kernel, grid, dim3(kTopkThreads), 0, stream, lp, kv, budget_pages, scores,
+                       scores_is_user_buffer ? scores : nullptr, sel_pages, sel_count, sel_seq_len);
+    return hipGetLastError();
+}
+
+}  // namespace lserve

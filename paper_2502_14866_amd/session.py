@@ -1,0 +1,86 @@
+"""Host-side decode loop with reusable page selection (Sec. 3.5.3).
+
+The selector runs on the first step of every chunk of C decode steps and its index table is
+reused for the other C - 1 steps; every step refreshes the key statistics of the logical page the
+new token fell into and then runs the sparse decode kernel.  This class only owns buffers and
+calls the C-ABI entry points in that order; all arithmetic happens in the HIP kernels.
+"""
+from __future__ import annotations
+
+from typing import Optional, Sequence
+
+import torch
+
+from . import binding as B
+
+
+class DecodeSession:
+    def __init__(self, k_pool: torch.Tensor, v_pool: torch.Tensor, page_table: torch.Tensor,
+                 num_q_heads: int, streaming_flags: Sequence[int], sink_tokens: int, local_tokens: int,
+                 budget_tokens: int, logical_page_size: int = 16, reuse_interval: int = 4,
+                 sm_scale: float = 0.0, want_scores: bool = False, want_lse: bool = False):
+        dev = k_pool.device
+        num_pages, hkv, page_size, head_dim = k_pool.shape
+        batch, max_pages = page_table.shape
+        self.desc = B.AttnDesc(num_q_heads=num_q_heads, num_kv_heads=hkv, streaming_flags=streaming_flags,
+                               head_dim=head_dim, page_size=page_size, logical_page_size=logical_page_size,
+                               dtype=k_pool.dtype, sink_tokens=sink_tokens, local_tokens=local_tokens,
+                               sm_scale=sm_scale)
+        g = page_size // logical_page_size
+        self.stats = torch.zeros((num_pages, hkv, g, 2, head_dim), dtype=k_pool.dtype, device=dev)
+        self.seq_lens = torch.zeros((batch,), dtype=torch.int32, device=dev)
+        self.kv = B.PagedKV(k_pool, v_pool, self.stats, page_table, self.seq_lens)
+        self.budget_tokens = budget_tokens
+        self.reuse_interval = max(1, reuse_interval)
+        K = budget_tokens // page_size
+        self.K = K
+        self.sel_pages = torch.full((batch, hkv, K), -1, dtype=torch.int32, device=dev)
+        self.sel_count = torch.zeros((batch, hkv), dtype=torch.int32, device=dev)
+        self.sel_seq_len = torch.zeros((batch,), dtype=torch.int32, device=dev)
+        self.scores = (torch.zeros((batch, hkv, max_pages), dtype=torch.float32, device=dev)
+                       if want_scores else None)
+        ws_sel = B.lserve_workspace_bytes(B.LSERVE_CALL_SELECT_PAGES, self.desc, batch, max_pages, K, 0)
+        ws_dec = B.lserve_workspace_bytes(B.LSERVE_CALL_SPARSE_DECODE, self.desc, batch, max_pages, K, 0)
+        self.ws_select = torch.empty((max(ws_sel, 16),), dtype=torch.uint8, device=dev)
+        self.ws_decode = torch.empty((max(ws_dec, 16),), dtype=torch.uint8, device=dev)
+        self.out = torch.empty((batch, num_q_heads, head_dim), dtype=k_pool.dtype, device=dev)
+        self.lse = torch.empty((batch, num_q_heads), dtype=torch.float32, device=dev) if want_lse else None
+        self.steps_since_selection: Optional[int] = None
+
+    def set_seq_lens(self, seq_lens: torch.Tensor) -> None:
+        """Point the session at the caller's current lengths (device int32 [batch], not copied)."""
+        self.seq_lens = seq_lens
+        self.kv.seq_lens = seq_lens
+
+    def build_stats_full(self) -> None:
+        """Statistics of every logical page below the current lengths (after prefill)."""
+        B.lserve_build_page_stats(self.desc, self.kv, None, 0)
+
+    def update_stats_tail(self, prev_seq_lens: torch.Tensor, max_new_tokens: int = 1) -> None:
+        """Refresh the logical pages that hold tokens [prev_seq_lens, seq_lens) of every sequence."""
+        np_ = self.desc.page_size
+        tail_pages = 1 if max_new_tokens == 1 else (max_new_tokens + np_ - 1) // np_ + 1
+        B.lserve_build_page_stats(self.desc, self.kv, prev_seq_lens, tail_pages)
+
+    def select(self, q: torch.Tensor) -> None:
+        B.lserve_select_pages(self.desc, self.kv, q, self.budget_tokens, self.sel_pages, self.sel_count,
+                              self.sel_seq_len, self.scores, self.ws_select)
+        self.steps_since_selection = 0
+
+    def decode(self, q: torch.Tensor) -> torch.Tensor:
+        B.lserve_sparse_decode(self.desc, self.kv, q, self.sel_pages, self.sel_count, self.sel_seq_len,
+                               self.out, self.lse, self.ws_decode)
+        return self.out
+
+    def step(self, q: torch.Tensor, seq_lens: torch.Tensor, prev_seq_lens: torch.Tensor) -> torch.Tensor:
+        """One decode step.
+
+        The new token's K/V are already in the pool; `seq_lens` counts it and `prev_seq_lens` is the
+        length before it was appended (both device int32 [batch], 16-byte aligned, not copied).
+        """
+        self.set_seq_lens(seq_lens)
+        self.update_stats_tail(prev_seq_lens, 1)
+        if self.steps_since_selection is None or self.steps_since_selection >= self.reuse_interval:
+            self.select(q)
+        self.steps_since_selection += 1
+        return self.decode(q)

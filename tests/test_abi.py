@@ -1,0 +1,118 @@
+"""The C-ABI library loads, exports every symbol the header declares, and rejects bad arguments
+on the host before touching the GPU (so these run without one)."""
+import ctypes
+import os
+import re
+
+import pytest
+import torch
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def L():
+    import paper_2502_14866_amd as L
+
+    if not os.path.exists(L.library_path()):
+        from paper_2502_14866_amd.build import build_library
+
+        build_library()
+    L.load_library()
+    return L
+
+
+def test_every_declared_symbol_is_exported(L):
+    header = open(os.path.join(ROOT, "include", "lserve.h")).read()
+    declared = set(re.findall(r"^(?:int|size_t|const char \*)\s*(lserve_[a-z_]+)\s*\(", header, flags=re.M))
+    assert {"lserve_build_page_stats", "lserve_select_pages", "lserve_sparse_prefill", "lserve_sparse_decode",
+            "lserve_workspace_bytes", "lserve_strerror", "lserve_last_hip_error"} <= declared
+    lib = ctypes.CDLL(L.library_path())
+    for name in declared:
+        assert hasattr(lib, name), name
+
+
+def test_workspace_sizes_and_error_strings(L):
+    d = L.AttnDesc(32, 8, [1, 1, 1, 1, 0, 0, 0, 0])
+    assert L.lserve_workspace_bytes(L.LSERVE_CALL_SELECT_PAGES, d, 16, 513, 64, 0) == 16 * 8 * 513 * 4
+    assert L.lserve_workspace_bytes(L.LSERVE_CALL_SPARSE_DECODE, d, 16, 513, 64, 0) > 0
+    assert L.lserve_workspace_bytes(L.LSERVE_CALL_SPARSE_PREFILL, d, 1, 0, 0, 65536) >= 8 * 65536 * 128 * 2
+    assert L.lserve_workspace_bytes(L.LSERVE_CALL_BUILD_PAGE_STATS, d, 16, 513, 64, 0) == 0
+    bad = L.AttnDesc(32, 8, [0] * 8, head_dim=64)
+    assert L.lserve_workspace_bytes(L.LSERVE_CALL_SPARSE_DECODE, bad, 16, 513, 64, 0) == 0
+    assert "success" in L.lserve_strerror(0)
+    for code in (-1, -2, -3, -4, -99):
+        assert L.lserve_strerror(code)
+
+
+def _dummy_kv(L, batch=2, max_pages=4, hkv=2):
+    # host tensors are enough: every call below must fail validation before any launch
+    k = torch.zeros((8, hkv, 64, 128), dtype=torch.float16)
+    st = torch.zeros((8, hkv, 4, 2, 128), dtype=torch.float16)
+    pt = torch.zeros((batch, max_pages), dtype=torch.int32)
+    sl = torch.ones((batch + 2,), dtype=torch.int32)[:batch]
+    return L.PagedKV(k, k.clone(), st, pt, sl)
+
+
+def _rc(fn):
+    from paper_2502_14866_amd.binding import LserveError
+
+    try:
+        fn()
+    except LserveError as e:
+        return e.code
+    return 0
+
+
+def test_invalid_arguments_are_rejected_on_the_host(L):
+    kv = _dummy_kv(L)
+    q = torch.zeros((2, 4, 128), dtype=torch.float16)
+    out = torch.zeros_like(q)
+    sel = torch.zeros((2, 2, 4), dtype=torch.int32)
+    cnt = torch.zeros((2, 2), dtype=torch.int32)
+    ssl = torch.zeros((4,), dtype=torch.int32)
+    ws = torch.zeros((1 << 20,), dtype=torch.uint8)
+    good = dict(num_q_heads=4, num_kv_heads=2, streaming_flags=[1, 0])
+    stream = 0
+
+    def desc(**kw):
+        a = dict(good)
+        a.update(kw)
+        return L.AttnDesc(**a)
+
+    assert _rc(lambda: L.lserve_build_page_stats(desc(head_dim=64), kv, None, 0, stream)) == -2
+    assert _rc(lambda: L.lserve_build_page_stats(desc(dtype=torch.float32), kv, None, 0, stream)) == -2
+    assert _rc(lambda: L.lserve_build_page_stats(desc(num_q_heads=5), kv, None, 0, stream)) == -2
+    assert _rc(lambda: L.lserve_build_page_stats(desc(num_q_heads=32), kv, None, 0, stream)) == -2  # n = 16
+    assert _rc(lambda: L.lserve_build_page_stats(desc(page_size=64, logical_page_size=24), kv, None, 0, stream)) == -1
+    assert _rc(lambda: L.lserve_build_page_stats(desc(page_size=48, logical_page_size=16), kv, None, 0, stream)) == -2
+    assert _rc(lambda: L.lserve_build_page_stats(desc(local_tokens=0), kv, None, 0, stream)) == -1
+    assert _rc(lambda: L.lserve_build_page_stats(desc(), kv, None, -1, stream)) == -1
+    nostats = L.PagedKV(kv.k_pool, kv.v_pool, None, kv.page_table, kv.seq_lens)
+    assert _rc(lambda: L.lserve_build_page_stats(desc(), nostats, None, 0, stream)) == -1
+    # selection: budget below one page, missing outputs, workspace too small
+    assert _rc(lambda: L.lserve_select_pages(desc(), kv, q, 32, sel, cnt, ssl, None, ws, stream)) == -1
+    assert _rc(lambda: L.lserve_select_pages(desc(), kv, q, 256, sel, cnt, ssl, None, None, stream)) == -3
+    assert _rc(lambda: L.lserve_select_pages(desc(), kv, q, 256, sel, cnt, ssl, None, ws[:16], stream)) == -3
+    # misaligned pointer
+    assert _rc(lambda: L.lserve_select_pages(desc(), kv, q.view(-1)[1:], 256, sel, cnt, ssl, None, ws, stream)) == -1
+    # decode: selecting head present but no selection given; workspace missing
+    assert _rc(lambda: L.lserve_sparse_decode(desc(), kv, q, None, None, None, out, None, ws, stream)) == -1
+    assert _rc(lambda: L.lserve_sparse_decode(desc(), kv, q, sel, cnt, ssl, out, None, None, stream)) == -3
+    # prefill: page size other than 64, max_seqlen beyond the token count, workspace too small
+    cu = torch.tensor([0, 2, 0, 0], dtype=torch.int32)[:2]
+    assert _rc(lambda: L.lserve_sparse_prefill(desc(page_size=32), q, q[:, :2].contiguous(), q[:, :2].contiguous(), cu, 2, out, None, ws,
+                                               stream)) == -2
+    assert _rc(lambda: L.lserve_sparse_prefill(desc(), q, q[:, :2].contiguous(), q[:, :2].contiguous(), cu, 3, out,
+                                               None, ws, stream)) == -1
+    assert _rc(lambda: L.lserve_sparse_prefill(desc(), q, q[:, :2].contiguous(), q[:, :2].contiguous(), cu, 2, out,
+                                               None, ws[:64], stream)) == -3
+
+
+def test_product_path_does_not_reach_for_the_oracle():
+    pkg = os.path.join(ROOT, "paper_2502_14866_amd")
+    for dirpath, _, files in os.walk(pkg):
+        for f in files:
+            if f.endswith((".py", ".hip", ".h")):
+                text = open(os.path.join(dirpath, f)).read()
+                assert "import oracle" not in text and "from oracle" not in text and "lserve_oracle" not in text

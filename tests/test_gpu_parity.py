@@ -1,0 +1,248 @@
+"""Parity of the HIP path (through the C ABI) against the CPU oracle on the same seeded inputs."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from workloads import Workload, get_config, make_decode_inputs, make_prefill_inputs, scatter_prefill_kv_to_pages
+
+from helpers import small_decode_workload
+from parity import SCORE_REL_TOL, assert_attention_close, assert_lse_close, compare_selection
+
+pytestmark = pytest.mark.gpu
+
+
+def _lib():
+    import paper_2502_14866_amd as L
+
+    L.load_library()
+    return L
+
+
+def _session(L, w, inp, dev, want_scores=True, want_lse=True):
+    from paper_2502_14866_amd.session import DecodeSession
+
+    return DecodeSession(inp.k_pool.to(dev), inp.v_pool.to(dev), inp.page_table.to(dev), w.num_q_heads,
+                         w.streaming_flags(), w.sink_tokens, w.local_tokens, w.budget_tokens,
+                         logical_page_size=w.logical_page_size, reuse_interval=w.reuse_interval,
+                         want_scores=want_scores, want_lse=want_lse)
+
+
+def _check_stats(w, inp, sess, seq_cpu):
+    """Statistics of every non-empty logical page of the non-streaming heads, value for value."""
+    ref = oracle.page_stats(inp.k_pool, inp.page_table, seq_cpu, w.logical_page_size)
+    got = sess.stats.cpu()
+    pt = inp.page_table.numpy()
+    g = w.page_size // w.logical_page_size
+    heads = [h for h in range(w.num_kv_heads) if h not in w.streaming_kv_heads]
+    for b in range(w.batch):
+        L_b = int(seq_cpu[b])
+        P = (L_b + w.page_size - 1) // w.page_size
+        pages = torch.from_numpy(pt[b, :P]).long()
+        full = pages[:P - 1]
+        for hk in heads:
+            assert torch.equal(got[full, hk].float(), ref[full, hk].float()), (b, hk)
+            tail_valid = -(-(L_b - (P - 1) * w.page_size) // w.logical_page_size)
+            assert torch.equal(got[pages[-1], hk, :tail_valid].float(), ref[pages[-1], hk, :tail_valid].float())
+    return ref
+
+
+WORKLOADS = {
+    "tiny_gqa": dict(),
+    "ragged_tail": dict(lengths=(1, 63), decode_steps=3),
+    "mha": dict(num_q_heads=4, num_kv_heads=4, streaming_kv_heads=(1, 3), lengths=(900, 130, 2049), batch=3),
+    "gqa8_bf16": dict(num_q_heads=16, num_kv_heads=2, dtype="bf16", streaming_kv_heads=(1,), lengths=(4100, 700),
+                      budget_tokens=1024),
+    "all_streaming": dict(streaming_kv_heads=(0, 1), lengths=(5000, 200)),
+    "all_dense_page32": dict(streaming_kv_heads=(), page_size=32, logical_page_size=8, lengths=(3000, 1500),
+                             budget_tokens=512),
+    "page128_g8": dict(page_size=128, logical_page_size=16, lengths=(6000, 3000), budget_tokens=1024,
+                       sink_tokens=128, local_tokens=256),
+    "page16_flat": dict(page_size=16, logical_page_size=16, lengths=(700, 333), budget_tokens=128, sink_tokens=16,
+                        local_tokens=64),
+    "group3": dict(num_q_heads=6, num_kv_heads=2, lengths=(1500, 2600), budget_tokens=512),
+}
+
+
+@pytest.mark.parametrize("name", list(WORKLOADS))
+def test_decode_loop_matches_oracle(name):
+    """Statistics, scores, selection (bit-exact sets) and decode output over a short decode loop."""
+    L = _lib()
+    dev = torch.device("cuda:0")
+    kw = dict(WORKLOADS[name])
+    kw.setdefault("decode_steps", 5)
+    kw.setdefault("reuse_interval", 2)
+    w = small_decode_workload(**kw)
+    inp = make_decode_inputs(w)
+    sess = _session(L, w, inp, dev)
+    flags = w.streaming_flags()
+    near_ties = 0
+    sel_ref = cnt_ref = ssl_ref = None
+    prev = inp.prompt_lens.to(dev)
+    for step in range(w.decode_steps):
+        seq_cpu = inp.seq_lens_at(step)
+        seq = seq_cpu.to(dev)
+        q = inp.q[step].to(dev)
+        sess.set_seq_lens(seq)
+        if step == 0:
+            sess.build_stats_full()
+        else:
+            sess.update_stats_tail(prev, 1)
+        stats_ref = _check_stats(w, inp, sess, seq_cpu)
+        if step % w.reuse_interval == 0:
+            sess.select(q)
+            scores_ref, _ = oracle.page_scores(inp.q[step], stats_ref, inp.page_table, seq_cpu, w.page_size)
+            sel_ref, cnt_ref, ssl_ref = oracle.select_pages(scores_ref, seq_cpu, w.page_size, w.budget_tokens)
+            got_scores = sess.scores.cpu().numpy().astype(np.float64)
+            for hk in range(w.num_kv_heads):
+                if flags[hk]:
+                    assert (got_scores[:, hk] == 0).all()
+                else:
+                    np.testing.assert_allclose(got_scores[:, hk], scores_ref[:, hk], rtol=SCORE_REL_TOL, atol=1e-4)
+            near_ties += compare_selection(sess.sel_pages.cpu().numpy(), sess.sel_count.cpu().numpy(), sel_ref,
+                                           cnt_ref, scores_ref, flags)
+            assert np.array_equal(sess.sel_seq_len.cpu().numpy(), ssl_ref)
+        out = sess.decode(q)
+        # the oracle attends the GPU's own selection, so a near-tie cannot leak into this comparison
+        ref, lse_ref = oracle.sparse_decode(inp.q[step], inp.k_pool, inp.v_pool, inp.page_table, seq_cpu,
+                                            sess.sel_pages.cpu().numpy(), sess.sel_count.cpu().numpy(),
+                                            sess.sel_seq_len.cpu().numpy(), flags, w.sink_tokens, w.local_tokens)
+        assert_attention_close(out, ref, f"{name} step {step}")
+        assert_lse_close(sess.lse, lse_ref, f"{name} step {step}")
+        prev = seq
+    print(f"[{name}] near-tie selections: {near_ties}")
+    assert near_ties <= 1
+
+
+def test_decode_ignores_nan_in_slots_past_the_sequence_end():
+    L = _lib()
+    dev = torch.device("cuda:0")
+    w = small_decode_workload(lengths=(70, 130), decode_steps=1, budget_tokens=1024)
+    inp = make_decode_inputs(w)
+    seq_cpu = inp.seq_lens_at(0)
+    for b in range(w.batch):  # poison every slot past the end of the tail page
+        Lb = int(seq_cpu[b])
+        page = int(inp.page_table[b, (Lb - 1) // 64])
+        inp.k_pool[page, :, Lb % 64:] = float("nan")
+        inp.v_pool[page, :, Lb % 64:] = float("nan")
+    sess = _session(L, w, inp, dev)
+    sess.set_seq_lens(seq_cpu.to(dev))
+    sess.build_stats_full()
+    sess.select(inp.q[0].to(dev))
+    out = sess.decode(inp.q[0].to(dev))
+    ref, _ = oracle.sparse_decode(inp.q[0], inp.k_pool, inp.v_pool, inp.page_table, seq_cpu,
+                                  sess.sel_pages.cpu().numpy(), sess.sel_count.cpu().numpy(),
+                                  sess.sel_seq_len.cpu().numpy(), w.streaming_flags(), w.sink_tokens, w.local_tokens)
+    assert_attention_close(out, ref, "nan tail")
+
+
+def test_decode_is_deterministic_and_stale_selection_adds_new_pages():
+    L = _lib()
+    dev = torch.device("cuda:0")
+    w = small_decode_workload(lengths=(1000, 1900), decode_steps=140, budget_tokens=512)
+    inp = make_decode_inputs(w)
+    sess = _session(L, w, inp, dev)
+    sess.set_seq_lens(inp.seq_lens_at(0).to(dev))
+    sess.build_stats_full()
+    sess.select(inp.q[0].to(dev))
+    step = 139  # 139 tokens later: two or three pages are newer than the selection
+    seq_cpu = inp.seq_lens_at(step)
+    sess.set_seq_lens(seq_cpu.to(dev))
+    q = inp.q[step].to(dev)
+    a = sess.decode(q).clone()
+    b = sess.decode(q).clone()
+    assert torch.equal(a, b)
+    ref, _ = oracle.sparse_decode(inp.q[step], inp.k_pool, inp.v_pool, inp.page_table, seq_cpu,
+                                  sess.sel_pages.cpu().numpy(), sess.sel_count.cpu().numpy(),
+                                  sess.sel_seq_len.cpu().numpy(), w.streaming_flags(), w.sink_tokens, w.local_tokens)
+    assert_attention_close(a, ref, "stale selection")
+
+
+def test_planted_needles_are_retrieved_by_the_gpu_selector():
+    L = _lib()
+    dev = torch.device("cuda:0")
+    w = get_config("cfg4", context=16384, batch=2, decode_steps=1)
+    inp = make_decode_inputs(w)
+    sess = _session(L, w, inp, dev)
+    seq_cpu = inp.seq_lens_at(0)
+    sess.set_seq_lens(seq_cpu.to(dev))
+    sess.build_stats_full()
+    sess.select(inp.q[0].to(dev))
+    sel, cnt = sess.sel_pages.cpu().numpy(), sess.sel_count.cpu().numpy()
+    for b in range(w.batch):
+        for hk in range(4, 8):
+            chosen = set(sel[b, hk, :cnt[b, hk]].tolist())
+            for pos in inp.needle_pos[b].tolist():
+                assert pos // 64 in chosen
+
+
+def _prefill(L, w, pin, dev, max_seqlen=None):
+    desc = L.AttnDesc(w.num_q_heads, w.num_kv_heads, w.streaming_flags(), dtype=w.torch_dtype,
+                      sink_tokens=w.sink_tokens, local_tokens=w.local_tokens)
+    q, k, v = pin.q.to(dev), pin.k.to(dev), pin.v.to(dev)
+    cu = pin.cu_seqlens.to(dev)
+    total = q.shape[0]
+    lens = (pin.cu_seqlens[1:] - pin.cu_seqlens[:-1]).tolist()
+    ws = torch.empty((L.lserve_workspace_bytes(L.LSERVE_CALL_SPARSE_PREFILL, desc, len(lens), 0, 0, total),),
+                     dtype=torch.uint8, device=dev)
+    out = torch.full_like(q, float("nan"))
+    lse = torch.empty((w.num_q_heads, total), dtype=torch.float32, device=dev)
+    L.lserve_sparse_prefill(desc, q, k, v, cu, max_seqlen or max(lens), out, lse, ws)
+    torch.cuda.synchronize()
+    return out, lse
+
+
+def _oracle_rows(w, pin, tok, head):
+    return oracle.sparse_prefill_rows(pin.q, pin.k, pin.v, pin.cu_seqlens, w.streaming_flags(), 64, w.sink_tokens,
+                                      w.local_tokens, tok, head)
+
+
+@pytest.mark.parametrize("dtype", ["fp16", "bf16"])
+@pytest.mark.parametrize("lengths", [(1,), (64,), (65, 300), (777, 256, 1000)])
+def test_prefill_matches_oracle_on_every_row(dtype, lengths):
+    L = _lib()
+    dev = torch.device("cuda:0")
+    w = Workload(name="p", batch=len(lengths), num_q_heads=4, num_kv_heads=2, dtype=dtype, streaming_kv_heads=(0,),
+                 sink_tokens=64, local_tokens=192, seed=21)
+    pin = make_prefill_inputs(w, lengths=lengths)
+    out, lse = _prefill(L, w, pin, dev)
+    total = sum(lengths)
+    tok = np.repeat(np.arange(total, dtype=np.int32), w.num_q_heads)
+    head = np.tile(np.arange(w.num_q_heads, dtype=np.int32), total)
+    ref, lse_ref = _oracle_rows(w, pin, tok, head)
+    assert_attention_close(out, ref.reshape(total, w.num_q_heads, -1), f"prefill {dtype} {lengths}")
+    assert_lse_close(lse.t().contiguous(), lse_ref.reshape(total, w.num_q_heads), "prefill lse")
+
+
+def test_cfg1_prefill_then_decode_full_comparison():
+    """Config 1: 2048-token prefill compared on every row, K/V scattered to pages, one decode step."""
+    L = _lib()
+    dev = torch.device("cuda:0")
+    w = get_config("cfg1")
+    pin = make_prefill_inputs(w)
+    out, _ = _prefill(L, w, pin, dev)
+    total = w.prefill_tokens
+    tok = np.repeat(np.arange(total, dtype=np.int32), w.num_q_heads)
+    head = np.tile(np.arange(w.num_q_heads, dtype=np.int32), total)
+    ref, _ = _oracle_rows(w, pin, tok, head)
+    assert_attention_close(out, ref.reshape(total, w.num_q_heads, -1), "cfg1 prefill")
+
+    inp = make_decode_inputs(w)
+    scatter_prefill_kv_to_pages(pin.k, pin.v, pin.cu_seqlens.tolist(), inp.k_pool, inp.v_pool, inp.page_table)
+    sess = _session(L, w, inp, dev)
+    seq_cpu = inp.seq_lens_at(0)  # 2049
+    sess.set_seq_lens(seq_cpu.to(dev))
+    sess.build_stats_full()
+    stats_ref = _check_stats(w, inp, sess, seq_cpu)
+    q = inp.q[0].to(dev)
+    sess.select(q)
+    scores_ref, _ = oracle.page_scores(inp.q[0], stats_ref, inp.page_table, seq_cpu, w.page_size)
+    sel_ref, cnt_ref, _ = oracle.select_pages(scores_ref, seq_cpu, w.page_size, w.budget_tokens)
+    ties = compare_selection(sess.sel_pages.cpu().numpy(), sess.sel_count.cpu().numpy(), sel_ref, cnt_ref,
+                             scores_ref, w.streaming_flags())
+    assert ties == 0
+    dec = sess.decode(q)
+    dref, _ = oracle.sparse_decode(inp.q[0], inp.k_pool, inp.v_pool, inp.page_table, seq_cpu,
+                                   sess.sel_pages.cpu().numpy(), sess.sel_count.cpu().numpy(),
+                                   sess.sel_seq_len.cpu().numpy(), w.streaming_flags(), w.sink_tokens, w.local_tokens)
+    assert_attention_close(dec, dref, "cfg1 decode")
