@@ -1,0 +1,364 @@
+#!/usr/bin/env python3
+"""Benchmark of the LServe sparse-attention hot path on one MI355X.
+
+Workload (N = 1): the decode configuration of the headline metric -- Llama-3-8B shaped layer,
+32 query / 8 KV heads of width 128, fp16, batch 16, every sequence at 32768 tokens of context,
+KV heads 0-3 streaming (128 sink + 512 local tokens), heads 4-7 selecting 64-token pages under a
+4096-token budget with 16-token logical pages, selector rerun every 4 steps, 16-step episodes.
+
+A "step" is one decode step of the whole path for the whole batch: key statistics of the logical
+page the new token fell into, page selection when the step opens a reuse chunk, sparse paged decode.
+All inputs are synthetic, seeded, and resident in HBM before the timed region.  The 16-step episode
+is captured once in a HIP graph and replayed; `value` is batch * steps / wall time.
+
+Extra objects in the JSON line:
+  roofline      sparse decode kernel: algorithmic KV bytes per launch / its mean duration (HIP
+                events around each launch inside an un-captured episode) against 8 TB/s
+  cpu_baseline  the CPU oracle on the host cores for one reuse chunk of the same workload
+  selector, stats, prefill   per-call timings of the other entry points (prefill on the 64K bf16
+                configuration, against the bf16 MFMA peak)
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import re
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0
+MFMA_BF16_PEAK_TFLOPS = 2500.0
+
+
+def parse_args():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=640)
+    ap.add_argument("--warmup", type=int, default=64)
+    ap.add_argument("--workload", default="cfg2", choices=["cfg2", "cfg4", "cfg5"])
+    ap.add_argument("--context", type=int, default=0, help="override the context length (cfg2 / cfg4)")
+    ap.add_argument("--no-graph", action="store_true", help="launch eagerly instead of replaying a HIP graph")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-prefill", action="store_true")
+    ap.add_argument("--prefill-tokens", type=int, default=65536)
+    ap.add_argument("--profile-only", default="", choices=["", "decode", "select", "prefill", "stats"],
+                    help="run only a short loop of one entry point (for rocprofv3)")
+    return ap.parse_args()
+
+
+def decode_bytes_per_launch(w, seq_lens_cpu, sel_count_cpu, sel_seq_len_cpu):
+    """Algorithmic bytes of one sparse decode launch: K and V slabs of the listed pages, q, out, tables."""
+    np_ = w.page_size
+    elt = 2
+    slab = np_ * w.head_dim * elt
+    s = -(-w.sink_tokens // np_)
+    wl = -(-w.local_tokens // np_)
+    flags = w.streaming_flags()
+    pages = 0
+    for b in range(w.batch):
+        P = -(-int(seq_lens_cpu[b]) // np_)
+        for hk in range(w.num_kv_heads):
+            if flags[hk]:
+                head = min(s, P)
+                pages += head + (P - max(head, P - wl))
+            else:
+                pages += int(sel_count_cpu[b, hk]) + max(0, P - -(-int(sel_seq_len_cpu[b]) // np_))
+    kv_bytes = pages * 2 * slab
+    io_bytes = 2 * w.batch * w.num_q_heads * w.head_dim * elt + pages * 8
+    return kv_bytes + io_bytes, pages
+
+
+def read_traffic(workload: str):
+    """HBM bytes per decode launch from the committed rocprofv3 counter summary, if there is one."""
+    path = os.path.join(ROOT, "profiles", f"sparse_decode_{workload}_traffic.txt")
+    if not os.path.exists(path):
+        return None
+    m = re.search(r"^traffic_bytes_per_launch\s*=\s*([0-9.eE+]+)", open(path).read(), flags=re.M)
+    return float(m.group(1)) if m else None
+
+
+def main():
+    args = parse_args()
+    if args.gpus != 1:
+        print(f"bench.py measures one MI355X; --gpus {args.gpus} is not supported (the path has no "
+              "cross-GPU part: it shards by KV head or by sequence with no exchange)", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+
+    import paper_2502_14866_amd as L
+    from paper_2502_14866_amd.session import DecodeSession
+    from workloads import get_config, make_decode_inputs, make_prefill_inputs
+
+    if not os.path.exists(L.library_path()):
+        from paper_2502_14866_amd.build import build_library
+
+        build_library()
+    L.load_library()
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+
+    over = {}
+    if args.context:
+        over["context"] = args.context
+    w = get_config(args.workload, **over)
+    t0 = time.time()
+    inp = make_decode_inputs(w, device=dev)
+    torch.cuda.synchronize()
+    gen_s = time.time() - t0
+    E = w.decode_steps  # episode length
+    C = w.reuse_interval
+    B = w.batch
+
+    sess = DecodeSession(inp.k_pool, inp.v_pool, inp.page_table, w.num_q_heads, w.streaming_flags(),
+                         w.sink_tokens, w.local_tokens, w.budget_tokens, logical_page_size=w.logical_page_size,
+                         reuse_interval=C)
+    # lengths for every episode position, rows padded to 16 bytes; row t = length before step t
+    pad = (B + 3) // 4 * 4
+    len_table = torch.zeros((E + 1, pad), dtype=torch.int32, device=dev)
+    for t in range(E + 1):
+        len_table[t, :B] = inp.prompt_lens + t
+    sess.set_seq_lens(len_table[0, :B])
+    sess.build_stats_full()
+    torch.cuda.synchronize()
+
+    def episode():
+        sess.steps_since_selection = None
+        for t in range(E):
+            sess.step(inp.q[t], len_table[t + 1, :B], len_table[t, :B])
+
+    if args.profile_only:
+        run_profile_only(args, torch, L, sess, inp, len_table, w, dev)
+        return
+
+    episode()  # eager warm-up of every kernel (first-use module load must not land in a capture)
+    torch.cuda.synchronize()
+    graph = None
+    if not args.no_graph:
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            episode()
+        torch.cuda.synchronize()
+
+    def run_steps(n):
+        full, rest = divmod(n, E)
+        for _ in range(full):
+            graph.replay() if graph is not None else episode()
+        if rest:  # a partial episode is launched eagerly
+            sess.steps_since_selection = None
+            for t in range(rest):
+                sess.step(inp.q[t], len_table[t + 1, :B], len_table[t, :B])
+
+    run_steps(args.warmup)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    run_steps(args.steps)
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    tokens_per_s = B * args.steps / elapsed
+
+    # ---- per-kernel timing inside an un-captured episode (HIP events on the launch stream) ----
+    reps = 6
+    dec_ms, sel_ms, st_ms = [], [], []
+    bytes_per_launch, pages_per_launch = [], []
+    for rep in range(reps):
+        sess.steps_since_selection = None
+        for t in range(E):
+            q = inp.q[t]
+            sess.set_seq_lens(len_table[t + 1, :B])
+            ev = [torch.cuda.Event(enable_timing=True) for _ in range(4)]
+            ev[0].record()
+            sess.update_stats_tail(len_table[t, :B], 1)
+            ev[1].record()
+            ran_select = sess.steps_since_selection is None or sess.steps_since_selection >= C
+            if ran_select:
+                sess.select(q)
+            ev[2].record()
+            sess.steps_since_selection += 1
+            sess.decode(q)
+            ev[3].record()
+            torch.cuda.synchronize()
+            st_ms.append(ev[0].elapsed_time(ev[1]))
+            if ran_select:
+                sel_ms.append(ev[1].elapsed_time(ev[2]))
+            dec_ms.append(ev[2].elapsed_time(ev[3]))
+            if rep == 0:
+                nbytes, npages = decode_bytes_per_launch(w, len_table[t + 1, :B].cpu(), sess.sel_count.cpu(),
+                                                         sess.sel_seq_len.cpu())
+                bytes_per_launch.append(nbytes)
+                pages_per_launch.append(npages)
+    mean = lambda xs: sum(xs) / max(1, len(xs))  # noqa: E731
+    dec_mean_ms = mean(dec_ms)
+    alg_bytes = mean(bytes_per_launch)
+    achieved = alg_bytes / (dec_mean_ms * 1e-3) / 1e9
+    traffic = read_traffic(w.name)
+
+    stats_bytes_run = 0
+    flags = w.streaming_flags()
+    n_sel = sum(1 for f in flags if not f)
+    for b in range(B):
+        P = -(-int(inp.prompt_lens[b]) // w.page_size)
+        stats_bytes_run += P * n_sel * (w.page_size // w.logical_page_size) * 2 * w.head_dim * 2
+    sel_mean_ms = mean(sel_ms)
+
+    result = {
+        "metric": "sparse decode tokens/s at 32K context (decode + amortised page selection + stats update)",
+        "value": tokens_per_s,
+        "unit": "tokens/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": elapsed / args.steps * 1e3,
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "f16",
+        "data": "synthetic",
+        "config": {
+            "workload": f"{w.name}: decode only, batch {B}, {w.num_q_heads}/{w.num_kv_heads} heads x {w.head_dim}, "
+                        f"context {int(inp.prompt_lens.max())}, {len(w.streaming_kv_heads)} streaming KV heads "
+                        f"({w.sink_tokens} sink + {w.local_tokens} local), budget {w.budget_tokens}, "
+                        f"N_P {w.page_size}, N_L {w.logical_page_size}, reuse interval {C}, {E}-step episodes",
+            "launch": "eager" if graph is None else "hip graph of one episode",
+            "generate_s": round(gen_s, 2),
+        },
+        "roofline": {
+            "bound": "hbm",
+            "kernel": "sparse_decode_kernel (+ decode_merge_kernel)",
+            "achieved": achieved,
+            "peak": HBM_PEAK_GBS,
+            "unit": "GB/s",
+            "frac": achieved / HBM_PEAK_GBS,
+            "traffic": traffic,
+            "algorithmic_bytes_per_launch": alg_bytes,
+            "pages_per_launch": mean(pages_per_launch),
+            "launch_ms": dec_mean_ms,
+            "launch_ms_min": min(dec_ms),
+        },
+        "selector": {
+            "ms_per_run": sel_mean_ms,
+            "stats_bytes_per_run": stats_bytes_run,
+            "achieved_GBs": stats_bytes_run / (sel_mean_ms * 1e-3) / 1e9 if sel_mean_ms else None,
+            "frac_of_hbm_peak": stats_bytes_run / (sel_mean_ms * 1e-3) / 1e9 / HBM_PEAK_GBS if sel_mean_ms else None,
+        },
+        "stats_tail_update": {"ms_per_call": mean(st_ms)},
+        "whole_path_GBs": (mean(bytes_per_launch) * E + stats_bytes_run * (E // C)) / E
+        / (elapsed / args.steps) / 1e9,
+    }
+
+    if not args.no_cpu_baseline:
+        result["cpu_baseline"] = cpu_baseline(torch, w, inp)
+    if not args.no_prefill:
+        try:
+            result["prefill"] = bench_prefill(torch, L, dev, args.prefill_tokens)
+        except Exception as e:  # the decode line must still be printed
+            result["prefill"] = {"error": repr(e)}
+    print(json.dumps(result))
+
+
+def cpu_baseline(torch, w, inp):
+    """The oracle, as it stands, on one reuse chunk (selector once, C decode steps) of the whole batch."""
+    import oracle
+
+    C = w.reuse_interval
+    k_cpu, v_cpu = inp.k_pool.cpu(), inp.v_pool.cpu()
+    pt = inp.page_table.cpu()
+    q_cpu = inp.q[:C].cpu()
+    flags = w.streaming_flags()
+    prompt = inp.prompt_lens.cpu()
+    t0 = time.perf_counter()
+    stats = None
+    for t in range(C):
+        seq = prompt + (t + 1)
+        if t == 0:
+            # statistics as the decode loop would hold them; the full build is outside the sample
+            stats = oracle.page_stats(k_cpu, pt, seq, w.logical_page_size)
+            t0 = time.perf_counter()
+            scores, _ = oracle.page_scores(q_cpu[0], stats, pt, seq, w.page_size)
+            sel, cnt, ssl = oracle.select_pages(scores, seq, w.page_size, w.budget_tokens)
+        oracle.sparse_decode(q_cpu[t], k_cpu, v_cpu, pt, seq, sel, cnt, ssl, flags, w.sink_tokens, w.local_tokens)
+    dt = time.perf_counter() - t0
+    return {
+        "value": w.batch * C / dt,
+        "unit": "tokens/s",
+        "cores": oracle.num_threads(),
+        "kind": "oracle",
+        "sample": f"one reuse chunk of the same workload: 1 selector run + {C} decode steps, all {w.batch} sequences "
+                  f"({w.batch * C} tokens, {dt:.1f} s)",
+    }
+
+
+def bench_prefill(torch, L, dev, n_tokens):
+    from workloads import get_config, make_prefill_inputs
+
+    w = get_config("cfg3", prefill_tokens=n_tokens)
+    pin = make_prefill_inputs(w, device=dev)
+    desc = L.AttnDesc(w.num_q_heads, w.num_kv_heads, w.streaming_flags(), dtype=w.torch_dtype,
+                      sink_tokens=w.sink_tokens, local_tokens=w.local_tokens)
+    ws = torch.empty((L.lserve_workspace_bytes(L.LSERVE_CALL_SPARSE_PREFILL, desc, 1, 0, 0, n_tokens),),
+                     dtype=torch.uint8, device=dev)
+    out = torch.empty_like(pin.q)
+    call = lambda: L.lserve_sparse_prefill(desc, pin.q, pin.k, pin.v, pin.cu_seqlens, n_tokens, out, None, ws)  # noqa: E731
+    call()
+    torch.cuda.synchronize()
+    reps = 3
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(reps):
+        call()
+    e1.record()
+    torch.cuda.synchronize()
+    ms = e0.elapsed_time(e1) / reps
+    D, T = w.head_dim, 64
+    n = w.group
+    n_dense = sum(1 for f in w.streaming_flags() if not f) * n
+    n_stream = sum(w.streaming_flags()) * n
+    s_t, w_t = -(-w.sink_tokens // T), -(-w.local_tokens // T)
+    nt = -(-n_tokens // T)
+    dense_pairs = n_tokens * (n_tokens + 1) // 2
+    stream_tiles = sum(min(i + 1, w_t) + max(0, min(s_t, i - w_t + 1)) for i in range(nt))
+    flops_dense = 4.0 * D * dense_pairs * n_dense
+    flops_stream = 4.0 * D * stream_tiles * T * T * n_stream  # executed tiles (diagonal tiles counted whole)
+    flops_equiv = 4.0 * D * dense_pairs * (n_dense + n_stream)
+    tf = (flops_dense + flops_stream) / (ms * 1e-3) / 1e12
+    return {
+        "workload": f"cfg3: prefill {n_tokens} tokens, bf16, {w.num_q_heads}/{w.num_kv_heads} heads, "
+                    f"{n_stream} streaming + {n_dense} dense query heads",
+        "ms": ms,
+        "algorithmic_TFLOPs": tf,
+        "dense_equivalent_TFLOPs": flops_equiv / (ms * 1e-3) / 1e12,
+        "roofline": {"bound": "mfma", "achieved": tf, "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
+                     "frac": tf / MFMA_BF16_PEAK_TFLOPS, "traffic": None},
+    }
+
+
+def run_profile_only(args, torch, L, sess, inp, len_table, w, dev):
+    """Short loops of one entry point so that a rocprofv3 run sees only that kernel at its real shape."""
+    B, E = w.batch, w.decode_steps
+    if args.profile_only == "prefill":
+        print(json.dumps(bench_prefill(torch, L, dev, args.prefill_tokens)))
+        return
+    sess.set_seq_lens(len_table[1, :B])
+    sess.update_stats_tail(len_table[0, :B], 1)
+    sess.select(inp.q[0])
+    torch.cuda.synchronize()
+    for i in range(20):
+        t = i % 4
+        sess.set_seq_lens(len_table[t + 1, :B])
+        if args.profile_only == "decode":
+            sess.decode(inp.q[t])
+        elif args.profile_only == "select":
+            sess.select(inp.q[t])
+        else:
+            sess.update_stats_tail(len_table[t, :B], 1)
+    torch.cuda.synchronize()
+    print(json.dumps({"profile_only": args.profile_only, "launches": 20}))
+
+
+if __name__ == "__main__":
+    main()
