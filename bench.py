@@ -6,8 +6,9 @@ Workload (N = 1): the decode configuration of the headline metric -- Llama-3-8B 
 KV heads 0-3 streaming (128 sink + 512 local tokens), heads 4-7 selecting 64-token pages under a
 4096-token budget with 16-token logical pages, selector rerun every 4 steps, 16-step episodes.
 
-A "step" is one decode step of the whole path for the whole batch: key statistics of the logical
-page the new token fell into, page selection when the step opens a reuse chunk, sparse paged decode.
+A "step" is one decode step of the whole path for the whole batch: when the step opens a reuse chunk,
+the key statistics of the logical pages that received tokens since the last selector run and the page
+selection; on every step the sparse paged decode.
 All inputs are synthetic, seeded, and resident in HBM before the timed region.  The 16-step episode
 is captured once in a HIP graph and replayed; `value` is batch * steps / wall time.
 
@@ -128,7 +129,7 @@ def main():
     torch.cuda.synchronize()
 
     def episode():
-        sess.steps_since_selection = None
+        sess.restart()
         for t in range(E):
             sess.step(inp.q[t], len_table[t + 1, :B], len_table[t, :B])
 
@@ -150,7 +151,7 @@ def main():
         for _ in range(full):
             graph.replay() if graph is not None else episode()
         if rest:  # a partial episode is launched eagerly
-            sess.steps_since_selection = None
+            sess.restart()
             for t in range(rest):
                 sess.step(inp.q[t], len_table[t + 1, :B], len_table[t, :B])
 
@@ -167,15 +168,16 @@ def main():
     dec_ms, sel_ms, st_ms = [], [], []
     bytes_per_launch, pages_per_launch = [], []
     for rep in range(reps):
-        sess.steps_since_selection = None
+        sess.restart()
         for t in range(E):
             q = inp.q[t]
             sess.set_seq_lens(len_table[t + 1, :B])
             ev = [torch.cuda.Event(enable_timing=True) for _ in range(4)]
-            ev[0].record()
-            sess.update_stats_tail(len_table[t, :B], 1)
-            ev[1].record()
             ran_select = sess.steps_since_selection is None or sess.steps_since_selection >= C
+            ev[0].record()
+            if ran_select:  # statistics of the tokens appended since the previous selector run
+                sess.update_stats_tail(len_table[max(0, t + 1 - C), :B], min(C, t + 1))
+            ev[1].record()
             if ran_select:
                 sess.select(q)
             ev[2].record()
@@ -183,8 +185,8 @@ def main():
             sess.decode(q)
             ev[3].record()
             torch.cuda.synchronize()
-            st_ms.append(ev[0].elapsed_time(ev[1]))
             if ran_select:
+                st_ms.append(ev[0].elapsed_time(ev[1]))
                 sel_ms.append(ev[1].elapsed_time(ev[2]))
             dec_ms.append(ev[2].elapsed_time(ev[3]))
             if rep == 0:

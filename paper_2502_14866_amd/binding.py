@@ -9,7 +9,8 @@ from typing import Optional, Sequence
 import torch
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-_LIB_PATH = os.path.join(_HERE, "liblserve.so")
+# LSERVE_LIBRARY points at another build of the same library (e.g. an instrumented one)
+_LIB_PATH = os.environ.get("LSERVE_LIBRARY") or os.path.join(_HERE, "liblserve.so")
 _lib = None
 
 LSERVE_CALL_BUILD_PAGE_STATS = 0

@@ -7,11 +7,17 @@
 // (16 lanes per token row), dot products use packed 16-bit dot instructions with fp32
 // accumulation, and the softmax is kept online per wavefront.
 //
-// Decomposition: the page list of one (sequence, KV head) is cut into chunks; one workgroup of
-// four wavefronts walks a chunk page by page, each wavefront taking a quarter of the page's
-// tokens, and prefetches the next page's slabs while it works on the current one.  A chunk's
-// result is either final (single chunk) or a partial (max, sum, unnormalised output) that a small
-// merge kernel combines in chunk order, which keeps the result deterministic.
+// Work distribution: a launch is only a few thousand pages, far too few for the hardware scheduler
+// to even out, so the page lists of all (sequence, KV head) pairs are laid end to end and cut into
+// G equal ranges, G = resident workgroups of the whole chip.  A workgroup resolves the table entries
+// of its pages in one go (one lane per page) and then streams its pages, the next page's slabs in
+// flight while it works on the current one; its four wavefronts each take a quarter of a page's
+// tokens.  A range may cross list boundaries; every (workgroup, list) piece yields either the final
+// result (the list lies inside the range) or a partial (max, sum, unnormalised output) at slot
+// workgroup + list index, which a small merge kernel combines in slot order.  Reduction orders are
+// fixed, so results are deterministic.
+#include <cstdlib>
+
 #include "kernels.h"
 
 namespace lserve {
@@ -20,8 +26,11 @@ namespace {
 
 constexpr int kDecodeThreads = 256;
 constexpr int kDecodeWaves = kDecodeThreads / kWave;
-constexpr int kChunkPages = 8;  // target pages per workgroup
+constexpr int kMaxBlocksPerCU = 4;       // upper bound used to size the workspace
+constexpr int kBlocksPerCU = 2;          // measured best on MI355X: more resident workgroups only queue up in the fabric
 constexpr float kLn2 = 0.6931471805599453f;
+
+// ---- index tables --------------------------------------------------------------------------------
 
 struct PageList {
     int len;          // number of pages attended
@@ -55,179 +64,234 @@ __device__ __forceinline__ int page_of(const PageList& pl, int i) {
     return pl.tail_start + (i - pl.head);
 }
 
-__device__ __forceinline__ int active_chunks(int len, int slots) { return min(slots, ceil_div(len, kChunkPages)); }
+// ---- per-wave online softmax over quarter pages --------------------------------------------------
+//
+// A wave owns NP / 4 consecutive tokens of every page.  Keys and values use different lane maps:
+//   keys  : LPT lanes per token; lane l reads 16-byte chunks LPT * j + l % LPT of token l / LPT, so a
+//           dot product over the 128 channels needs only log2(LPT) cross-lane steps (LPT = 4 for
+//           N_P >= 64: every 4 lanes read 64 contiguous bytes);
+//   values: 16 lanes per token row, lane (r, c) reads chunk c of tokens 4 it + r, so the output
+//           accumulators stay at 8 channels per lane and head.
+// The softmax weights cross from one map to the other through a few hundred bytes of LDS.
 
-template <int ITS> struct Slabs {
-    uint4 k[ITS], v[ITS];
+template <int NP> struct KeyMap {
+    static constexpr int LPT = NP >= 64 ? 4 : (NP == 32 ? 8 : 16);  // lanes per token
+    static constexpr int TPP = kWave / LPT;                          // tokens per pass of the wave
+    static constexpr int PASSES = (NP / 4) / TPP;                    // 2 for N_P = 128, else 1
+    static constexpr int KLOADS = 16 / LPT;                          // 16-byte chunks per lane and token
+    static constexpr int ITS = NP / 16;                              // 16-byte loads per lane and slab
 };
 
-template <int ITS>
-__device__ __forceinline__ void load_slabs(Slabs<ITS>& s, const uint4* kslab, const uint4* vslab, int tok0, int r, int c) {
+template <int NP> struct Slabs {
+    uint4 k[KeyMap<NP>::ITS], v[KeyMap<NP>::ITS];
+};
+
+template <int NP>
+__device__ __forceinline__ void load_k(Slabs<NP>& s, const uint4* kslab, int tok0, int lane) {
+    using M = KeyMap<NP>;
 #pragma unroll
-    for (int it = 0; it < ITS; ++it) s.k[it] = kslab[(size_t)(tok0 + 4 * it + r) * (kHeadDim / 8) + c];
+    for (int ps = 0; ps < M::PASSES; ++ps)
 #pragma unroll
-    for (int it = 0; it < ITS; ++it) s.v[it] = vslab[(size_t)(tok0 + 4 * it + r) * (kHeadDim / 8) + c];
+        for (int j = 0; j < M::KLOADS; ++j)
+            s.k[ps * M::KLOADS + j] =
+                kslab[(size_t)(tok0 + ps * M::TPP + lane / M::LPT) * (kHeadDim / 8) + M::LPT * j + lane % M::LPT];
 }
 
+template <int NP>
+__device__ __forceinline__ void load_v(Slabs<NP>& s, const uint4* vslab, int tok0, int r, int c) {
+#pragma unroll
+    for (int it = 0; it < KeyMap<NP>::ITS; ++it) s.v[it] = vslab[(size_t)(tok0 + 4 * it + r) * (kHeadDim / 8) + c];
+}
+
+template <int N> struct WaveState {
+    float m[N], l[N], o[N][8];
+    __device__ __forceinline__ void reset() {
+#pragma unroll
+        for (int hh = 0; hh < N; ++hh) {
+            m[hh] = -INFINITY;
+            l[hh] = 0.f;
+#pragma unroll
+            for (int i = 0; i < 8; ++i) o[hh][i] = 0.f;
+        }
+    }
+};
+
+constexpr int p_row(int n) { return n <= 4 ? 4 : 8; }  // floats per token row of the weight buffer
+
+// Sum over the LPT lanes that share a token; every one of them receives the total.
+template <int LPT> __device__ __forceinline__ float token_sum(float x) {
+    x += dpp_f<kDppXor1>(x);
+    x += dpp_f<kDppXor2>(x);
+    if (LPT >= 8) x += dpp_f<kDppHalfMirror>(x);
+    if (LPT >= 16) x += dpp_f<kDppMirror>(x);
+    return x;
+}
+
+// Maximum over the wave of a value that is already equal inside every group of four lanes.
+__device__ __forceinline__ float wave_max_of_quads(float x) {
+    x = fmaxf(x, dpp_f<kDppHalfMirror>(x));
+    x = fmaxf(x, dpp_f<kDppMirror>(x));
+    return rows4_max(x);
+}
+
+// One quarter page.  q_lds: [N][16] 16-byte chunks of the group's queries; p_lds: this wave's
+// [NP / 4][p_row(N)] weight buffer.  `valid` = tokens of the page below the sequence length.
 template <class T, int N, int NP>
-__global__ __launch_bounds__(kDecodeThreads) void sparse_decode_kernel(
-    LayerParams lp, PagedParams kv, const uint4* __restrict__ q, const int* __restrict__ sel_pages,
-    const int* __restrict__ sel_count, const int* __restrict__ sel_seq_len, int sel_stride,
-    uint16_t* __restrict__ out, float* __restrict__ lse_out, float* __restrict__ part_o, float* __restrict__ part_ml) {
-    constexpr int ITS = NP / 16;  // 16-byte loads per lane and slab: the wave covers NP / 4 tokens
-    __shared__ float sm_o[kDecodeWaves][N][kHeadDim];
-    __shared__ float sm_m[kDecodeWaves][N], sm_l[kDecodeWaves][N];
+__device__ __forceinline__ void process_quarter_page(WaveState<N>& st, const uint4* q_lds, float* p_lds,
+                                                     Slabs<NP>& cur, int valid, int tok0, int lane,
+                                                     float scale_log2) {
+    using M = KeyMap<NP>;
+    constexpr int PR = p_row(N);
+    const int r = lane / 16;
+    float s[M::PASSES][N];
+#pragma unroll
+    for (int ps = 0; ps < M::PASSES; ++ps)
+#pragma unroll
+        for (int hh = 0; hh < N; ++hh) s[ps][hh] = 0.f;
+#pragma unroll
+    for (int j = 0; j < M::KLOADS; ++j) {
+#pragma unroll
+        for (int hh = 0; hh < N; ++hh) {
+            const uint4 qv = q_lds[hh * 16 + M::LPT * j + lane % M::LPT];
+            const uint32_t qw[4] = {qv.x, qv.y, qv.z, qv.w};
+#pragma unroll
+            for (int ps = 0; ps < M::PASSES; ++ps) {
+                const uint4 kv4 = cur.k[ps * M::KLOADS + j];
+                const uint32_t kw[4] = {kv4.x, kv4.y, kv4.z, kv4.w};
+#pragma unroll
+                for (int i = 0; i < 4; ++i) s[ps][hh] = Elem<T>::dot2(qw[i], kw[i], s[ps][hh]);
+            }
+        }
+    }
+    const bool tail = valid < NP;
+#pragma unroll
+    for (int ps = 0; ps < M::PASSES; ++ps) {
+        const bool dead = tail && tok0 + ps * M::TPP + lane / M::LPT >= valid;
+#pragma unroll
+        for (int hh = 0; hh < N; ++hh) {
+            const float x = token_sum<M::LPT>(s[ps][hh]) * scale_log2;
+            s[ps][hh] = dead ? -INFINITY : x;
+        }
+    }
+#pragma unroll
+    for (int hh = 0; hh < N; ++hh) {
+        float pm = s[0][hh];
+#pragma unroll
+        for (int ps = 1; ps < M::PASSES; ++ps) pm = fmaxf(pm, s[ps][hh]);
+        pm = wave_max_of_quads(pm);
+        if (pm > st.m[hh]) {  // wave-uniform: rescale only when the running maximum moves
+            const float alpha = __builtin_amdgcn_exp2f(st.m[hh] - pm);
+            st.m[hh] = pm;
+            st.l[hh] *= alpha;
+#pragma unroll
+            for (int i = 0; i < 8; ++i) st.o[hh][i] *= alpha;
+        }
+        const float m_safe = st.m[hh] == -INFINITY ? 0.f : st.m[hh];
+#pragma unroll
+        for (int ps = 0; ps < M::PASSES; ++ps) {
+            s[ps][hh] = __builtin_amdgcn_exp2f(s[ps][hh] - m_safe);
+            st.l[hh] += s[ps][hh];  // counted once per lane of the token: divided by LPT at the end
+        }
+    }
+    if (lane % M::LPT == 0) {
+#pragma unroll
+        for (int ps = 0; ps < M::PASSES; ++ps) {
+            float* dst = p_lds + (ps * M::TPP + lane / M::LPT) * PR;
+#pragma unroll
+            for (int hh = 0; hh < N; ++hh) dst[hh] = s[ps][hh];
+        }
+    }
+    __builtin_amdgcn_wave_barrier();
+#pragma unroll
+    for (int it = 0; it < M::ITS; ++it) {
+        uint4 vv = cur.v[it];
+        if (tail && tok0 + 4 * it + r >= valid) vv = make_uint4(0, 0, 0, 0);  // slots past the end may hold anything
+        const uint32_t vw[4] = {vv.x, vv.y, vv.z, vv.w};
+        float pv[PR];
+#pragma unroll
+        for (int x4 = 0; x4 < PR / 4; ++x4) {
+            const float4 t4 = *reinterpret_cast<const float4*>(p_lds + (4 * it + r) * PR + 4 * x4);
+            pv[4 * x4] = t4.x;
+            pv[4 * x4 + 1] = t4.y;
+            pv[4 * x4 + 2] = t4.z;
+            pv[4 * x4 + 3] = t4.w;
+        }
+#pragma unroll
+        for (int hh = 0; hh < N; ++hh) {
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                st.o[hh][2 * i] = __builtin_fmaf(pv[hh], Elem<T>::lo(vw[i]), st.o[hh][2 * i]);
+                st.o[hh][2 * i + 1] = __builtin_fmaf(pv[hh], Elem<T>::hi(vw[i]), st.o[hh][2 * i + 1]);
+            }
+        }
+    }
+    __builtin_amdgcn_wave_barrier();
+}
 
-    const int slot = blockIdx.x, slots = gridDim.x, hk = blockIdx.y, b = blockIdx.z;
-    const int L = kv.seq_lens[b];
-    const PageList pl = make_page_list(lp, b, hk, L, sel_pages, sel_count, sel_seq_len, sel_stride);
-    const int A = active_chunks(pl.len, slots);
-    if (slot >= A) return;
-    const int i0 = (int)((long long)slot * pl.len / A), i1 = (int)((long long)(slot + 1) * pl.len / A);
+// Shared memory of a decode workgroup.
+template <int N, int NP> struct DecodeShared {
+    float o[kDecodeWaves][N][kHeadDim];   // cross-wave merge
+    float m[kDecodeWaves][N], l[kDecodeWaves][N];
+    uint4 q[N * 16];                      // queries of the current group
+    float p[kDecodeWaves][(NP / 4) * p_row(N)];
+};
 
+// Loads the n queries of KV head hk into shared memory.  Called by the whole workgroup.
+template <int N, int NP>
+__device__ __forceinline__ void stage_query(DecodeShared<N, NP>& sm, const uint4* q, int b, int H, int hk) {
+    __syncthreads();  // earlier readers of sm.q are done
+    for (int i = threadIdx.x; i < N * 16; i += kDecodeThreads)
+        sm.q[i] = q[((size_t)b * H + hk * N) * (kHeadDim / 8) + i];
+    __syncthreads();
+}
+
+// Folds the four token rows of every wave, then the four waves of the workgroup, and writes either
+// the final rows (out / lse) or a partial (part_o / part_ml).  Must be called by all 256 threads.
+template <class T, int N, int NP>
+__device__ __forceinline__ void flush_block(WaveState<N>& st, DecodeShared<N, NP>& sm, bool final_result, int H,
+                                            int b, int hk, uint16_t* out, float* lse_out, float* part_o,
+                                            float* part_ml, size_t part_slot) {
     const int lane = threadIdx.x % kWave, wave = threadIdx.x / kWave;
     const int r = lane / 16, c = lane % 16;
-    const int tok0 = wave * (NP / 4);
-
-    uint32_t qreg[N][4];
 #pragma unroll
     for (int hh = 0; hh < N; ++hh) {
-        uint4 x = q[((size_t)b * lp.H + hk * N + hh) * (kHeadDim / 8) + c];
-        qreg[hh][0] = x.x;
-        qreg[hh][1] = x.y;
-        qreg[hh][2] = x.z;
-        qreg[hh][3] = x.w;
-    }
-
-    float m[N], l[N], o[N][8];
+        // every lane of a token added the token's weight: 64 lanes hold LPT copies of the sum
+        float lsum = st.l[hh];
+        lsum += dpp_f<kDppXor1>(lsum);
+        lsum += dpp_f<kDppXor2>(lsum);
+        lsum += dpp_f<kDppHalfMirror>(lsum);
+        lsum += dpp_f<kDppMirror>(lsum);
+        lsum = rows4_sum(lsum) * (1.0f / KeyMap<NP>::LPT);
 #pragma unroll
-    for (int hh = 0; hh < N; ++hh) {
-        m[hh] = -INFINITY;
-        l[hh] = 0.f;
-#pragma unroll
-        for (int i = 0; i < 8; ++i) o[hh][i] = 0.f;
-    }
-
-    const uint4* kpool = reinterpret_cast<const uint4*>(kv.k_pool);
-    const uint4* vpool = reinterpret_cast<const uint4*>(kv.v_pool);
-    const size_t slab = (size_t)NP * (kHeadDim / 8);  // uint4 per (page, head)
-
-    for (int base = i0; base < i1; base += kWave) {
-        // every lane fetches the table entries of one list item; they are broadcast page by page
-        const int cnt = min(kWave, i1 - base);
-        int my_pos = 0, my_phys = 0;
-        if (lane < cnt) {
-            my_pos = page_of(pl, base + lane);
-            my_phys = kv.page_table[(size_t)b * kv.max_pages + my_pos];
-        }
-        Slabs<ITS> cur, nxt;
-        {
-            const int phys = __builtin_amdgcn_readfirstlane(my_phys);
-            const size_t off = ((size_t)phys * lp.Hkv + hk) * slab;
-            load_slabs<ITS>(cur, kpool + off, vpool + off, tok0, r, c);
-        }
-        for (int idx = 0; idx < cnt; ++idx) {
-            if (idx + 1 < cnt) {
-                const int phys = __builtin_amdgcn_readlane(my_phys, idx + 1);
-                const size_t off = ((size_t)phys * lp.Hkv + hk) * slab;
-                load_slabs<ITS>(nxt, kpool + off, vpool + off, tok0, r, c);
-            }
-            const int pos = __builtin_amdgcn_readlane(my_pos, idx);
-            const int valid = L - pos * NP;  // tokens of this page below the sequence length (may exceed NP)
-
-            float s[ITS][N];
-#pragma unroll
-            for (int it = 0; it < ITS; ++it) {
-                const uint32_t kw[4] = {cur.k[it].x, cur.k[it].y, cur.k[it].z, cur.k[it].w};
-#pragma unroll
-                for (int hh = 0; hh < N; ++hh) {
-                    float a = 0.f;
-#pragma unroll
-                    for (int i = 0; i < 4; ++i) a = Elem<T>::dot2(qreg[hh][i], kw[i], a);
-                    s[it][hh] = row16_sum(a) * lp.sm_scale_log2;
-                }
-            }
-            if (valid < NP) {  // tail page: mask the slots past the sequence end, keys and values
-#pragma unroll
-                for (int it = 0; it < ITS; ++it) {
-                    if (tok0 + 4 * it + r >= valid) {
-#pragma unroll
-                        for (int hh = 0; hh < N; ++hh) s[it][hh] = -INFINITY;
-                        cur.v[it] = make_uint4(0, 0, 0, 0);
-                    }
-                }
-            }
-            float p[ITS][N];
-#pragma unroll
-            for (int hh = 0; hh < N; ++hh) {
-                float pm = s[0][hh];
-#pragma unroll
-                for (int it = 1; it < ITS; ++it) pm = fmaxf(pm, s[it][hh]);
-                pm = rows4_max(pm);
-                const float m_new = fmaxf(m[hh], pm);
-                const float m_safe = m_new == -INFINITY ? 0.f : m_new;
-                const float alpha = __builtin_amdgcn_exp2f(m[hh] - m_safe);
-                m[hh] = m_new;
-                float ps = 0.f;
-#pragma unroll
-                for (int it = 0; it < ITS; ++it) {
-                    p[it][hh] = __builtin_amdgcn_exp2f(s[it][hh] - m_safe);
-                    ps += p[it][hh];
-                }
-                l[hh] = l[hh] * alpha + ps;
-#pragma unroll
-                for (int i = 0; i < 8; ++i) o[hh][i] *= alpha;
-            }
-#pragma unroll
-            for (int it = 0; it < ITS; ++it) {
-                const uint32_t vw[4] = {cur.v[it].x, cur.v[it].y, cur.v[it].z, cur.v[it].w};
-#pragma unroll
-                for (int hh = 0; hh < N; ++hh) {
-#pragma unroll
-                    for (int i = 0; i < 4; ++i) {
-                        o[hh][2 * i] = __builtin_fmaf(p[it][hh], Elem<T>::lo(vw[i]), o[hh][2 * i]);
-                        o[hh][2 * i + 1] = __builtin_fmaf(p[it][hh], Elem<T>::hi(vw[i]), o[hh][2 * i + 1]);
-                    }
-                }
-            }
-            cur = nxt;
-        }
-    }
-
-    // fold the four token rows of the wave, then the four waves of the workgroup
-#pragma unroll
-    for (int hh = 0; hh < N; ++hh) {
-        l[hh] = rows4_sum(l[hh]);
-#pragma unroll
-        for (int i = 0; i < 8; ++i) o[hh][i] = rows4_sum(o[hh][i]);
+        for (int i = 0; i < 8; ++i) st.o[hh][i] = rows4_sum(st.o[hh][i]);
         if (r == 0) {
 #pragma unroll
-            for (int i = 0; i < 8; ++i) sm_o[wave][hh][8 * c + i] = o[hh][i];
+            for (int i = 0; i < 8; ++i) sm.o[wave][hh][8 * c + i] = st.o[hh][i];
         }
         if (lane == 0) {
-            sm_m[wave][hh] = m[hh];
-            sm_l[wave][hh] = l[hh];
+            sm.m[wave][hh] = st.m[hh];
+            sm.l[wave][hh] = lsum;
         }
     }
     __syncthreads();
     for (int idx = threadIdx.x; idx < N * kHeadDim; idx += kDecodeThreads) {
         const int hh = idx / kHeadDim, ch = idx % kHeadDim;
-        float M = sm_m[0][hh];
+        float M = sm.m[0][hh];
 #pragma unroll
-        for (int w = 1; w < kDecodeWaves; ++w) M = fmaxf(M, sm_m[w][hh]);
+        for (int w = 1; w < kDecodeWaves; ++w) M = fmaxf(M, sm.m[w][hh]);
         float lt = 0.f, acc = 0.f;
 #pragma unroll
         for (int w = 0; w < kDecodeWaves; ++w) {
-            const float f = __builtin_amdgcn_exp2f(sm_m[w][hh] - M);
-            lt += sm_l[w][hh] * f;
-            acc += sm_o[w][hh][ch] * f;
+            const float f = sm.m[w][hh] == -INFINITY ? 0.f : __builtin_amdgcn_exp2f(sm.m[w][hh] - M);
+            lt += sm.l[w][hh] * f;
+            acc += sm.o[w][hh][ch] * f;
         }
         const int h = hk * N + hh;
-        if (A == 1) {
-            out[((size_t)b * lp.H + h) * kHeadDim + ch] = (uint16_t)(Elem<T>::pack(acc / lt, 0.f) & 0xffffu);
-            if (lse_out && ch == 0) lse_out[b * lp.H + h] = (M + __builtin_amdgcn_logf(lt)) * kLn2;
+        if (final_result) {
+            out[((size_t)b * H + h) * kHeadDim + ch] = (uint16_t)(Elem<T>::pack(acc / lt, 0.f) & 0xffffu);
+            if (lse_out && ch == 0) lse_out[b * H + h] = (M + __builtin_amdgcn_logf(lt)) * kLn2;
         } else {
-            const size_t pi = ((size_t)b * lp.H + h) * slots + slot;
+            const size_t pi = part_slot * N + hh;
             part_o[pi * kHeadDim + ch] = acc;
             if (ch == 0) {
                 part_ml[pi * 2] = M;
@@ -235,60 +299,273 @@ __global__ __launch_bounds__(kDecodeThreads) void sparse_decode_kernel(
             }
         }
     }
+    __syncthreads();
 }
 
-// Combines the partial results of one (sequence, query head) in chunk order.
-template <class T>
-__global__ __launch_bounds__(kHeadDim) void decode_merge_kernel(LayerParams lp, PagedParams kv,
-                                                                const int* __restrict__ sel_pages,
-                                                                const int* __restrict__ sel_count,
-                                                                const int* __restrict__ sel_seq_len, int sel_stride,
-                                                                int slots, uint16_t* __restrict__ out,
-                                                                float* __restrict__ lse_out,
-                                                                const float* __restrict__ part_o,
-                                                                const float* __restrict__ part_ml) {
-    const int h = blockIdx.x, b = blockIdx.y, ch = threadIdx.x;
-    const int hk = h / lp.group;
-    const PageList pl = make_page_list(lp, b, hk, kv.seq_lens[b], sel_pages, sel_count, sel_seq_len, sel_stride);
-    const int A = active_chunks(pl.len, slots);
-    if (A <= 1) return;  // the decode kernel already wrote the final result
-    const size_t p0 = ((size_t)b * lp.H + h) * slots;
-    float M = -INFINITY;
-    for (int cI = 0; cI < A; ++cI) M = fmaxf(M, part_ml[(p0 + cI) * 2]);
-    float lt = 0.f, acc = 0.f;
-    for (int cI = 0; cI < A; ++cI) {
-        const float f = __builtin_amdgcn_exp2f(part_ml[(p0 + cI) * 2] - M);
-        lt += part_ml[(p0 + cI) * 2 + 1] * f;
-        acc += part_o[(p0 + cI) * kHeadDim + ch] * f;
+// ---- balanced kernel over the nominal page space -------------------------------------------------
+//
+// Launch shape and work split must not depend on device data, and a prefix sum over the real list
+// lengths would put two more dependent memory round trips in front of the first K/V load of every
+// workgroup.  The split is therefore done over *nominal* list lengths the host knows: s + w pages
+// for a streaming head, sel_stride + 1 for a dense head (the selection plus one page created since).
+// Nominal entry x of the launch maps to (sequence, KV head, entry) by arithmetic alone.  Entries
+// past a list's real length are skipped; real entries past the nominal length (a selection reused
+// for more than one new page) are handled by the workgroup that owns the list's last nominal entry.
+
+struct DecodePlan {
+    int per_seq;               // nominal entries per sequence
+    int total;                 // batch * per_seq
+    int quot, rem;             // total = G * quot + rem: the first `rem` ranges hold quot + 1 entries
+    unsigned short first[65];  // first nominal entry of KV head hk inside a sequence; first[Hkv] = per_seq
+};
+
+// Range of workgroup j is [range_begin(j), range_begin(j + 1)); no division on the device.
+__device__ __forceinline__ int range_begin(const DecodePlan& plan, int j) { return j * plan.quot + min(j, plan.rem); }
+
+// Workgroup whose range holds nominal entry x.
+__device__ __forceinline__ int range_of(const DecodePlan& plan, int x) {
+    const int big = plan.rem * (plan.quot + 1);
+    return x < big ? x / (plan.quot + 1) : plan.rem + (x - big) / plan.quot;
+}
+
+// KV head of nominal entry y of a sequence.  The loop index is uniform, so the table is read with
+// independent scalar loads instead of a chain of dependent ones.
+__device__ __forceinline__ int head_of_entry(const DecodePlan& plan, int Hkv, int y) {
+    int hk = 0;
+    for (int h = 1; h < Hkv; ++h) hk += y >= (int)plan.first[h];
+    return hk;
+}
+
+template <class T, int N, int NP>
+__global__ __launch_bounds__(kDecodeThreads) void sparse_decode_kernel(
+    LayerParams lp, PagedParams kv, DecodePlan plan, const uint4* __restrict__ q, const int* __restrict__ sel_pages,
+    const int* __restrict__ sel_count, const int* __restrict__ sel_seq_len, int sel_stride,
+    uint16_t* __restrict__ out, float* __restrict__ lse_out, float* __restrict__ part_o, float* __restrict__ part_ml) {
+    __shared__ DecodeShared<N, NP> sm;
+
+    const int blk = blockIdx.x;
+    const int lo = range_begin(plan, blk), hi = range_begin(plan, blk + 1);
+    if (lo >= hi) return;
+
+    const int lane = threadIdx.x % kWave, wave = threadIdx.x / kWave;
+    const int r = lane / 16, c = lane % 16;
+    const int tok0 = wave * (NP / 4);
+    const uint4* kpool = reinterpret_cast<const uint4*>(kv.k_pool);
+    const uint4* vpool = reinterpret_cast<const uint4*>(kv.v_pool);
+    const size_t slab = (size_t)NP * (kHeadDim / 8);  // uint4 per (page, head)
+
+    WaveState<N> st;
+    int cur_list = -1, cur_b = 0, cur_hk = 0;
+
+    for (int base = lo; base < hi; base += kWave) {
+        // one lane per nominal entry: everything that does not depend on another load is requested
+        // at once (lengths, selection entry), then the page table, then the slabs
+        const int cnt = min(kWave, hi - base);
+        int my_list = 0, my_pos = 0, my_phys = 0, my_L = 1, my_extra = 0, my_tail = 0;
+        bool my_valid = false;
+        if (lane < cnt) {
+            const int x = base + lane;
+            const int b = x / plan.per_seq, y = x % plan.per_seq;
+            const int hk = head_of_entry(plan, lp.Hkv, y);
+            const int i = y - plan.first[hk], nominal = plan.first[hk + 1] - plan.first[hk];
+            my_list = b * lp.Hkv + hk;
+            my_L = kv.seq_lens[b];
+            const int P = ceil_div(my_L, NP);
+            int head, tail_start, sel_entry = 0;
+            const bool streaming = (lp.streaming_mask >> hk) & 1ull;
+            if (streaming) {
+                head = min(lp.sink_pages, P);
+                tail_start = max(head, P - lp.local_pages);
+                sel_entry = i;
+            } else {
+                sel_entry = sel_pages[(size_t)my_list * sel_stride + min(i, sel_stride - 1)];
+                head = sel_count[my_list];
+                tail_start = ceil_div(sel_seq_len[b], NP);
+            }
+            const int len = head + max(0, P - tail_start);
+            my_valid = i < len;
+            my_pos = i < head ? sel_entry : tail_start + (i - head);
+            my_tail = tail_start - head;  // position of entry i >= head is my_tail + i
+            if (i == nominal - 1 && len > nominal) my_extra = len - nominal;
+            if (my_valid) my_phys = kv.page_table[(size_t)b * kv.max_pages + my_pos];
+        }
+        unsigned long long todo = __ballot(my_valid);
+        if (todo == 0) continue;
+        Slabs<NP> cur, nxt;
+        {
+            const int idx0 = __builtin_ctzll(todo);
+            const size_t o0 = ((size_t)__builtin_amdgcn_readlane(my_phys, idx0) * lp.Hkv +
+                               __builtin_amdgcn_readlane(my_list, idx0) % lp.Hkv) * slab;
+            load_k<NP>(cur, kpool + o0, tok0, lane);
+            load_v<NP>(cur, vpool + o0, tok0, r, c);
+        }
+        while (todo) {
+            const int idx = __builtin_ctzll(todo);
+            todo &= todo - 1;
+            if (todo) {
+                const int idx1 = __builtin_ctzll(todo);
+                const size_t o1 = ((size_t)__builtin_amdgcn_readlane(my_phys, idx1) * lp.Hkv +
+                                   __builtin_amdgcn_readlane(my_list, idx1) % lp.Hkv) * slab;
+                load_k<NP>(nxt, kpool + o1, tok0, lane);
+                load_v<NP>(nxt, vpool + o1, tok0, r, c);
+            }
+            const int list = __builtin_amdgcn_readlane(my_list, idx);
+            if (list != cur_list) {  // uniform: the range crossed into the next list
+                if (cur_list >= 0) {
+                    const int n0 = cur_b * plan.per_seq + plan.first[cur_hk], n1 = cur_b * plan.per_seq + plan.first[cur_hk + 1];
+                    flush_block<T, N, NP>(st, sm, n0 >= lo && n1 <= hi, lp.H, cur_b, cur_hk, out, lse_out, part_o,
+                                          part_ml, (size_t)blk + cur_list);
+                }
+                cur_list = list;
+                cur_b = list / lp.Hkv;
+                cur_hk = list % lp.Hkv;
+                stage_query<N, NP>(sm, q, cur_b, lp.H, cur_hk);
+                st.reset();
+            }
+            const int L = __builtin_amdgcn_readlane(my_L, idx);
+            const int pos = __builtin_amdgcn_readlane(my_pos, idx);
+            process_quarter_page<T, N, NP>(st, sm.q, sm.p[wave], cur, L - pos * NP, tok0, lane, lp.sm_scale_log2);
+            const int extra = __builtin_amdgcn_readlane(my_extra, idx);
+            if (extra > 0) {  // real entries beyond the nominal length: rare, not prefetched
+                const int nominal = plan.first[cur_hk + 1] - plan.first[cur_hk];
+                const int tail = __builtin_amdgcn_readlane(my_tail, idx);
+                for (int e = 0; e < extra; ++e) {
+                    const int epos = tail + nominal + e;
+                    const int ephys = kv.page_table[(size_t)cur_b * kv.max_pages + epos];
+                    const size_t oe = ((size_t)ephys * lp.Hkv + cur_hk) * slab;
+                    load_k<NP>(cur, kpool + oe, tok0, lane);
+                    load_v<NP>(cur, vpool + oe, tok0, r, c);
+                    process_quarter_page<T, N, NP>(st, sm.q, sm.p[wave], cur, L - epos * NP, tok0, lane, lp.sm_scale_log2);
+                }
+            }
+            cur = nxt;
+        }
     }
+    if (cur_list < 0) return;  // no real entry in this range
+    const int n0 = cur_b * plan.per_seq + plan.first[cur_hk], n1 = cur_b * plan.per_seq + plan.first[cur_hk + 1];
+    flush_block<T, N, NP>(st, sm, n0 >= lo && n1 <= hi, lp.H, cur_b, cur_hk, out, lse_out, part_o, part_ml,
+                          (size_t)blk + cur_list);
+}
+
+// Combines the pieces of every list that was cut by a range boundary, in slot order.
+template <class T, int N>
+__global__ __launch_bounds__(N* kHeadDim) void decode_merge_kernel(
+    LayerParams lp, PagedParams kv, DecodePlan plan, const int* __restrict__ sel_pages,
+    const int* __restrict__ sel_count, const int* __restrict__ sel_seq_len, int sel_stride,
+    uint16_t* __restrict__ out, float* __restrict__ lse_out, const float* __restrict__ part_o,
+    const float* __restrict__ part_ml) {
+    const int hk = blockIdx.x, b = blockIdx.y, list = b * lp.Hkv + hk;
+    const int n0 = b * plan.per_seq + plan.first[hk], n1 = b * plan.per_seq + plan.first[hk + 1];
+    // workgroups whose ranges hold the first and the last nominal entry of the list
+    const int j0 = range_of(plan, n0), j1 = range_of(plan, n1 - 1);
+    if (j0 == j1) return;  // the list lay inside one range: the decode kernel wrote the final rows
+    const int len = make_page_list(lp, b, hk, kv.seq_lens[b], sel_pages, sel_count, sel_seq_len, sel_stride).len;
+    const int hh = threadIdx.x / kHeadDim, ch = threadIdx.x % kHeadDim;
+    // A piece exists iff its first nominal entry is a real entry of the list (ranges between j0 and
+    // j1 are never empty: an empty range implies quot = 0, and then no list spans two ranges).
+    // Pieces are folded in slot order, eight at a time so that their loads are in flight together.
+    constexpr int kBatch = 8;
+    float M = -INFINITY, lt = 0.f, acc = 0.f;
+    for (int jb = j0; jb <= j1; jb += kBatch) {
+        float pm[kBatch], pl[kBatch], po[kBatch];
+#pragma unroll
+        for (int u = 0; u < kBatch; ++u) {
+            const int j = jb + u;
+            const bool real = j <= j1 && max(n0, range_begin(plan, j)) - n0 < len;
+            const size_t pi = ((size_t)(real ? j : j0) + list) * N + hh;
+            pm[u] = real ? part_ml[pi * 2] : -INFINITY;
+            pl[u] = real ? part_ml[pi * 2 + 1] : 0.f;
+            po[u] = real ? part_o[pi * kHeadDim + ch] : 0.f;
+        }
+        float bm = pm[0];
+#pragma unroll
+        for (int u = 1; u < kBatch; ++u) bm = fmaxf(bm, pm[u]);
+        if (bm == -INFINITY) continue;
+        const float m_new = fmaxf(M, bm);
+        const float keep = __builtin_amdgcn_exp2f(M - m_new);  // 0 for the first batch (M = -inf)
+        lt *= keep;
+        acc *= keep;
+#pragma unroll
+        for (int u = 0; u < kBatch; ++u) {
+            const float f = __builtin_amdgcn_exp2f(pm[u] - m_new);
+            lt += pl[u] * f;
+            acc += po[u] * f;
+        }
+        M = m_new;
+    }
+    const int h = hk * N + hh;
     out[((size_t)b * lp.H + h) * kHeadDim + ch] = (uint16_t)(Elem<T>::pack(acc / lt, 0.f) & 0xffffu);
     if (lse_out && ch == 0) lse_out[b * lp.H + h] = (M + __builtin_amdgcn_logf(lt)) * kLn2;
 }
 
-int decode_slots(const LayerParams& lp, int sel_stride) {
-    int longest = 0;
+// ---- host side -----------------------------------------------------------------------------------
+
+int num_compute_units() {
+    static int cus = [] {
+        int dev = 0, n = 0;
+        if (hipGetDevice(&dev) != hipSuccess) return 256;
+        if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n <= 0) return 256;
+        return n;
+    }();
+    return cus;
+}
+
+DecodePlan make_plan(const LayerParams& lp, int batch, int sel_stride, int G) {
+    DecodePlan plan;
+    int acc = 0;
     for (int hk = 0; hk < lp.Hkv; ++hk) {
+        plan.first[hk] = (unsigned short)acc;
         const bool streaming = (lp.streaming_mask >> hk) & 1ull;
-        // dense heads: the selection plus one page created since; longer lists only make chunks longer
-        const int len = streaming ? lp.sink_pages + lp.local_pages : sel_stride + 1;
-        longest = len > longest ? len : longest;
+        acc += streaming ? lp.sink_pages + lp.local_pages : sel_stride + 1;
     }
-    const int slots = (longest + kChunkPages - 1) / kChunkPages;
-    return slots < 1 ? 1 : slots;
+    for (int hk = lp.Hkv; hk <= 64; ++hk) plan.first[hk] = (unsigned short)acc;
+    plan.per_seq = acc;
+    plan.total = batch * acc;
+    plan.quot = plan.total / G;
+    plan.rem = plan.total % G;
+    return plan;
+}
+
+size_t partial_slots(const LayerParams& lp, int batch) {
+    return (size_t)num_compute_units() * kMaxBlocksPerCU + (size_t)batch * lp.Hkv;
+}
+
+template <class T, int N, int NP>
+hipError_t launch_decode_kernels(const LayerParams& lp, const PagedParams& kv, const void* q, const int* sel_pages,
+                                 const int* sel_count, const int* sel_seq_len, int sel_stride, void* out,
+                                 float* lse_out, float* part_o, float* part_ml, hipStream_t stream) {
+    const uint4* q4 = reinterpret_cast<const uint4*>(q);
+    uint16_t* o16 = reinterpret_cast<uint16_t*>(out);
+    static int per_cu = 0;  // resident workgroups per compute unit of this instantiation
+    if (per_cu == 0) {
+        int nb = 0;
+        hipError_t e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&nb, sparse_decode_kernel<T, N, NP>, kDecodeThreads, 0);
+        if (e != hipSuccess) return e;
+        per_cu = nb < 1 ? 1 : (nb > kBlocksPerCU ? kBlocksPerCU : nb);
+        if (const char* e = getenv("LSERVE_DECODE_BLOCKS_PER_CU")) {  // tuning override
+            const int v = atoi(e);
+            if (v >= 1 && v <= nb && v <= kMaxBlocksPerCU) per_cu = v;
+        }
+    }
+    const int G = num_compute_units() * per_cu;
+    const DecodePlan plan = make_plan(lp, kv.batch, sel_stride, G);
+    hipLaunchKernelGGL((sparse_decode_kernel<T, N, NP>), dim3(G), dim3(kDecodeThreads), 0, stream, lp, kv, plan, q4,
+                       sel_pages, sel_count, sel_seq_len, sel_stride, o16, lse_out, part_o, part_ml);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL((decode_merge_kernel<T, N>), dim3(lp.Hkv, kv.batch), dim3(N * kHeadDim), 0, stream, lp, kv, plan,
+                       sel_pages, sel_count, sel_seq_len, sel_stride, o16, lse_out, part_o, part_ml);
+    return hipGetLastError();
 }
 
 template <class T, int N>
 hipError_t launch_decode_np(const LayerParams& lp, const PagedParams& kv, const void* q, const int* sel_pages,
-                            const int* sel_count, const int* sel_seq_len, int sel_stride, void* out,
-                            float* lse_out, float* part_o, float* part_ml, int slots, hipStream_t stream) {
-    dim3 grid(slots, lp.Hkv, kv.batch), block(kDecodeThreads);
-    const uint4* q4 = reinterpret_cast<const uint4*>(q);
-    uint16_t* o16 = reinterpret_cast<uint16_t*>(out);
-#define LSERVE_DECODE_NP(NPV)                                                                                  \
-    case NPV:                                                                                                  \
-        hipLaunchKernelGGL((sparse_decode_kernel<T, N, NPV>), grid, block, 0, stream, lp, kv, q4, sel_pages,   \
-                           sel_count, sel_seq_len, sel_stride, o16, lse_out, part_o, part_ml);                 \
-        break;
+                            const int* sel_count, const int* sel_seq_len, int sel_stride, void* out, float* lse_out,
+                            float* part_o, float* part_ml, hipStream_t stream) {
+#define LSERVE_DECODE_NP(NPV)                                                                                       \
+    case NPV:                                                                                                       \
+        return launch_decode_kernels<T, N, NPV>(lp, kv, q, sel_pages, sel_count, sel_seq_len, sel_stride, out,       \
+                                                lse_out, part_o, part_ml, stream);
     switch (lp.NP) {
         LSERVE_DECODE_NP(16)
         LSERVE_DECODE_NP(32)
@@ -298,22 +575,18 @@ hipError_t launch_decode_np(const LayerParams& lp, const PagedParams& kv, const 
             return hipErrorInvalidValue;
     }
 #undef LSERVE_DECODE_NP
-    return hipGetLastError();
 }
 
 template <class T>
 hipError_t launch_decode(const LayerParams& lp, const PagedParams& kv, const void* q, const int* sel_pages,
                          const int* sel_count, const int* sel_seq_len, int sel_stride, void* out, float* lse_out,
                          void* workspace, hipStream_t stream) {
-    const int slots = decode_slots(lp, sel_stride);
     float* part_o = reinterpret_cast<float*>(workspace);
-    float* part_ml = part_o + (size_t)kv.batch * lp.H * slots * kHeadDim;
-    hipError_t e;
-#define LSERVE_DECODE_N(NV)                                                                                         \
-    case NV:                                                                                                        \
-        e = launch_decode_np<T, NV>(lp, kv, q, sel_pages, sel_count, sel_seq_len, sel_stride, out, lse_out, part_o, \
-                                    part_ml, slots, stream);                                                        \
-        break;
+    float* part_ml = part_o + partial_slots(lp, kv.batch) * lp.group * kHeadDim;
+#define LSERVE_DECODE_N(NV)                                                                                          \
+    case NV:                                                                                                         \
+        return launch_decode_np<T, NV>(lp, kv, q, sel_pages, sel_count, sel_seq_len, sel_stride, out, lse_out,       \
+                                       part_o, part_ml, stream);
     switch (lp.group) {
         LSERVE_DECODE_N(1)
         LSERVE_DECODE_N(2)
@@ -327,21 +600,13 @@ hipError_t launch_decode(const LayerParams& lp, const PagedParams& kv, const voi
             return hipErrorInvalidValue;
     }
 #undef LSERVE_DECODE_N
-    if (e != hipSuccess) return e;
-    if (slots > 1) {
-        hipLaunchKernelGGL(decode_merge_kernel<T>, dim3(lp.H, kv.batch), dim3(kHeadDim), 0, stream, lp, kv, sel_pages,
-                           sel_count, sel_seq_len, sel_stride, slots, reinterpret_cast<uint16_t*>(out), lse_out,
-                           part_o, part_ml);
-        e = hipGetLastError();
-    }
-    return e;
 }
 
 }  // namespace
 
 size_t decode_workspace_bytes(const LayerParams& lp, int batch, int sel_stride) {
-    const int slots = decode_slots(lp, sel_stride);
-    return (size_t)batch * lp.H * slots * (kHeadDim + 2) * sizeof(float);
+    (void)sel_stride;
+    return partial_slots(lp, batch) * lp.group * (kHeadDim + 2) * sizeof(float);
 }
 
 hipError_t launch_sparse_decode(int dtype, const LayerParams& lp, const PagedParams& kv, const void* q,

@@ -1,8 +1,9 @@
 """Host-side decode loop with reusable page selection (Sec. 3.5.3).
 
 The selector runs on the first step of every chunk of C decode steps and its index table is
-reused for the other C - 1 steps; every step refreshes the key statistics of the logical page the
-new token fell into and then runs the sparse decode kernel.  This class only owns buffers and
+reused for the other C - 1 steps.  Right before a selector run the key statistics of the logical
+pages that received tokens since the previous run are refreshed; every step runs the sparse decode
+kernel.  This class only owns buffers and
 calls the C-ABI entry points in that order; all arithmetic happens in the HIP kernels.
 """
 from __future__ import annotations
@@ -46,6 +47,10 @@ class DecodeSession:
         self.out = torch.empty((batch, num_q_heads, head_dim), dtype=k_pool.dtype, device=dev)
         self.lse = torch.empty((batch, num_q_heads), dtype=torch.float32, device=dev) if want_lse else None
         self.steps_since_selection: Optional[int] = None
+        # Key statistics are consumed only by the selector, so the logical pages touched since the
+        # last selector run are refreshed in one call right before the next run.
+        self._stats_from: Optional[torch.Tensor] = None
+        self._stats_tokens = 0
 
     def set_seq_lens(self, seq_lens: torch.Tensor) -> None:
         """Point the session at the caller's current lengths (device int32 [batch], not copied)."""
@@ -76,11 +81,21 @@ class DecodeSession:
         """One decode step.
 
         The new token's K/V are already in the pool; `seq_lens` counts it and `prev_seq_lens` is the
-        length before it was appended (both device int32 [batch], 16-byte aligned, not copied).
+        length before it was appended (both device int32 [batch], 16-byte aligned, not copied, and
+        left unchanged by the caller until the next selector run).
         """
         self.set_seq_lens(seq_lens)
-        self.update_stats_tail(prev_seq_lens, 1)
+        if self._stats_from is None:
+            self._stats_from = prev_seq_lens
+        self._stats_tokens += 1
         if self.steps_since_selection is None or self.steps_since_selection >= self.reuse_interval:
+            self.update_stats_tail(self._stats_from, self._stats_tokens)
+            self._stats_from, self._stats_tokens = seq_lens, 0
             self.select(q)
         self.steps_since_selection += 1
         return self.decode(q)
+
+    def restart(self) -> None:
+        """Forget the selection and the pending statistics range (start of a new episode)."""
+        self.steps_since_selection = None
+        self._stats_from, self._stats_tokens = None, 0

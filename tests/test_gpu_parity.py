@@ -246,3 +246,78 @@ def test_cfg1_prefill_then_decode_full_comparison():
                                    sess.sel_pages.cpu().numpy(), sess.sel_count.cpu().numpy(),
                                    sess.sel_seq_len.cpu().numpy(), w.streaming_flags(), w.sink_tokens, w.local_tokens)
     assert_attention_close(dec, dref, "cfg1 decode")
+
+
+def test_hip_graph_replays_of_a_decode_episode_equal_the_eager_run():
+    """An episode (statistics update, selection every C steps, decode) captured in a HIP graph must
+    reproduce the eager results bit for bit on every replay, with eager work between replays."""
+    L = _lib()
+    from paper_2502_14866_amd.session import DecodeSession
+
+    dev = torch.device("cuda:0")
+    w = small_decode_workload(batch=4, lengths=(3000, 700, 5000, 64), decode_steps=8, reuse_interval=4,
+                              budget_tokens=1024, num_q_heads=8, num_kv_heads=2)
+    inp = make_decode_inputs(w, device=dev)
+    E, B = w.decode_steps, w.batch
+    sess = DecodeSession(inp.k_pool, inp.v_pool, inp.page_table, w.num_q_heads, w.streaming_flags(), w.sink_tokens,
+                         w.local_tokens, w.budget_tokens, reuse_interval=w.reuse_interval)
+    lens = torch.zeros((E + 1, 4), dtype=torch.int32, device=dev)
+    for t in range(E + 1):
+        lens[t, :B] = inp.prompt_lens + t
+    sess.set_seq_lens(lens[0, :B])
+    sess.build_stats_full()
+    outs = torch.zeros((E,) + tuple(sess.out.shape), dtype=sess.out.dtype, device=dev)
+
+    def episode():
+        sess.restart()
+        for t in range(E):
+            sess.step(inp.q[t], lens[t + 1, :B], lens[t, :B])
+            outs[t].copy_(sess.out)
+
+    episode()
+    torch.cuda.synchronize()
+    eager = outs.clone()
+    sel_eager = sess.sel_pages.clone()
+    assert torch.isfinite(eager.float()).all()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        episode()
+    torch.cuda.synchronize()
+    for rep in range(4):
+        outs.fill_(0)
+        sess.sel_pages.fill_(-7)  # eager work between replays; the graph must rebuild all of it
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(outs, eager), f"replay {rep} differs from the eager episode"
+        assert torch.equal(sess.sel_pages, sel_eager)
+
+
+def test_session_step_loop_with_lazy_statistics_matches_oracle():
+    """DecodeSession.step refreshes the statistics only right before a selector run; the selection made
+    then and every step's output must still match the oracle."""
+    L = _lib()
+    dev = torch.device("cuda:0")
+    w = small_decode_workload(batch=3, lengths=(1000, 127, 2500), decode_steps=9, reuse_interval=4,
+                              budget_tokens=512)
+    inp = make_decode_inputs(w)
+    sess = _session(L, w, inp, dev)
+    flags = w.streaming_flags()
+    lens = torch.zeros((w.decode_steps + 1, 4), dtype=torch.int32, device=dev)
+    for t in range(w.decode_steps + 1):
+        lens[t, :w.batch] = inp.prompt_lens.to(dev) + t
+    sess.set_seq_lens(lens[0, :w.batch])
+    sess.build_stats_full()
+    for t in range(w.decode_steps):
+        seq_cpu = inp.seq_lens_at(t)
+        out = sess.step(inp.q[t].to(dev), lens[t + 1, :w.batch], lens[t, :w.batch])
+        if t % w.reuse_interval == 0:
+            stats_ref = _check_stats(w, inp, sess, seq_cpu)
+            scores_ref, _ = oracle.page_scores(inp.q[t], stats_ref, inp.page_table, seq_cpu, w.page_size)
+            sel_ref, cnt_ref, _ = oracle.select_pages(scores_ref, seq_cpu, w.page_size, w.budget_tokens)
+            compare_selection(sess.sel_pages.cpu().numpy(), sess.sel_count.cpu().numpy(), sel_ref, cnt_ref,
+                              scores_ref, flags)
+        ref, _ = oracle.sparse_decode(inp.q[t], inp.k_pool, inp.v_pool, inp.page_table, seq_cpu,
+                                      sess.sel_pages.cpu().numpy(), sess.sel_count.cpu().numpy(),
+                                      sess.sel_seq_len.cpu().numpy(), flags, w.sink_tokens, w.local_tokens)
+        assert_attention_close(out, ref, f"session step {t}")
