@@ -4,8 +4,9 @@
 // the diagonal; streaming heads visit only the sink tiles and the local band, so whole tiles
 // outside the mask are never loaded.  Only the diagonal tile needs element-wise causal masking.
 //
-// Mapping to CDNA4: a workgroup of four wavefronts owns 256 consecutive query rows of one head;
-// wavefront w owns mask tile 4 * block + w (64 rows).  Key tiles are staged through LDS once per
+// Mapping to CDNA4: a workgroup of eight wavefronts owns 256 consecutive query rows of one head;
+// wavefronts 2t and 2t + 1 own the two 32-row halves of mask tile 4 * block + t.  Two wavefronts
+// share each SIMD, so the matrix pipe of one overlaps the softmax arithmetic of the other.  Key tiles are staged through LDS once per
 // workgroup and consumed by all four wavefronts.  Scores are computed transposed,
 //   S^T (keys x queries) = K (keys x d) * Q^T (d x queries)          v_mfma_f32_32x32x16
 // so that a lane owns one query column: the softmax reductions over keys stay inside the lane
@@ -25,7 +26,7 @@ typedef __bf16 bf168_t __attribute__((ext_vector_type(8)));
 typedef float float16_t __attribute__((ext_vector_type(16)));
 
 constexpr int kTile = 64;              // mask tile = key tile = page
-constexpr int kPrefillThreads = 256;   // 4 waves
+constexpr int kPrefillThreads = 512;   // 8 waves: two per SIMD, each owning 32 query rows
 constexpr int kRowsPerBlock = 256;     // 4 mask tiles of queries
 constexpr int kKRowBytes = 256 + 16;   // K tile row (128 x 16 bit) padded against LDS bank conflicts
 constexpr int kVRowBytes = 128 + 16;   // V^T tile row (64 keys x 16 bit) padded
@@ -85,6 +86,16 @@ __device__ __forceinline__ uint4 pack8(const float* p) {
                       Elem<T>::pack(p[6], p[7]));
 }
 
+// Exchange between the two 32-lane halves of a wave (v_permlane32_swap): after the swap the first
+// result holds the lower half of both operands' low lanes, the second the upper halves, so combining
+// them gives every lane op(x[l], x[l ^ 32]).
+__device__ __forceinline__ float halves_max(float x) { return fmaxf(x, __shfl_xor(x, 32, kWave)); }
+__device__ __forceinline__ float halves_sum(float x) { return x + __shfl_xor(x, 32, kWave); }
+
+template <class T> struct Ones;
+template <> struct Ones<F16> { static constexpr uint32_t pair = 0x3c003c00u; };
+template <> struct Ones<BF16> { static constexpr uint32_t pair = 0x3f803f80u; };
+
 template <class T>
 __global__ __launch_bounds__(kPrefillThreads) void sparse_prefill_kernel(
     LayerParams lp, const uint16_t* __restrict__ q, const uint16_t* __restrict__ k, const uint16_t* __restrict__ vt,
@@ -106,10 +117,11 @@ __global__ __launch_bounds__(kPrefillThreads) void sparse_prefill_kernel(
     const int tid = threadIdx.x, lane = tid % kWave, wave = tid / kWave;
     const int n = lane % 32, half = lane / 32;
     const bool streaming = (lp.streaming_mask >> hk) & 1ull;
-    const int iq = qblk * 4 + wave;               // this wave's mask tile
+    const int iq = qblk * 4 + wave / 2;  // this wave's mask tile; the wave owns one half of its rows
+    const int row0 = (wave % 2) * 32;    // first row of the wave inside the mask tile
     const int n_qtiles = ceil_div(len, kTile);
     const int iq_last = min(qblk * 4 + 3, n_qtiles - 1);  // last mask tile of the block that holds rows
-    const bool wave_has_rows = iq < n_qtiles;
+    const bool wave_has_rows = iq * kTile + row0 < len;
 
     // key tiles the block visits: [0, sink_end) and [band_begin, iq_last]
     int sink_end, band_begin;
@@ -122,56 +134,56 @@ __global__ __launch_bounds__(kPrefillThreads) void sparse_prefill_kernel(
     }
     const int n_visit = sink_end + (iq_last - band_begin + 1);
 
-    // ---- Q^T operands: lane (n, half) holds Q[row][16 kk + 8 half .. + 8] for both 32-row blocks
-    uint4 qreg[2][8];
-#pragma unroll
-    for (int qb = 0; qb < 2; ++qb) {
-        const int row = min(iq * kTile + qb * 32 + n, len - 1);
+    // ---- Q^T operand: lane (n, half) holds Q[row][16 kk + 8 half .. + 8]
+    uint4 qreg[8];
+    {
+        const int row = min(iq * kTile + row0 + n, len - 1);
         const uint4* src = reinterpret_cast<const uint4*>(q + ((size_t)(start + row) * lp.H + h) * kHeadDim);
 #pragma unroll
-        for (int kk = 0; kk < 8; ++kk) qreg[qb][kk] = src[kk * 2 + half];
+        for (int kk = 0; kk < 8; ++kk) qreg[kk] = src[kk * 2 + half];
     }
 
-    float16_t acc[4][2];
+    float16_t acc[4];
 #pragma unroll
     for (int db = 0; db < 4; ++db)
 #pragma unroll
-        for (int qb = 0; qb < 2; ++qb)
-#pragma unroll
-            for (int i = 0; i < 16; ++i) acc[db][qb][i] = 0.f;
-    float m[2] = {-INFINITY, -INFINITY}, l[2] = {0.f, 0.f};
+        for (int i = 0; i < 16; ++i) acc[db][i] = 0.f;
+    float m_run = -INFINITY, l_run = 0.f;  // running maximum (scaled, base 2) and sum of this lane's query row
 
-    // ---- staging: each thread moves 4 x 16 B of the K tile and 4 x 16 B of the V^T tile
+    // ---- staging: each thread moves 2 x 16 B of the K tile and 2 x 16 B of the V^T tile
     const uint16_t* kbase = k + ((size_t)start * lp.Hkv + hk) * kHeadDim;
     const uint16_t* vtbase = vt + ((size_t)hk * tiles_total + tile_base(start, b)) * kHeadDim * kTile;
-    uint4 kst[4], vst[4];
-    auto tile_of = [&](int it) { return it < sink_end ? it : band_begin + (it - sink_end); };
-    auto fetch = [&](int jt) {
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            const int chunk = tid + i * kPrefillThreads;  // 1024 chunks of 16 B per tile
-            const int krow = min(jt * kTile + chunk / 16, len - 1);
-            kst[i] = reinterpret_cast<const uint4*>(kbase + (size_t)krow * lp.Hkv * kHeadDim)[chunk % 16];
-            vst[i] = reinterpret_cast<const uint4*>(vtbase + (size_t)jt * kHeadDim * kTile)[chunk];
-        }
-    };
-    auto stash = [&](int stage) {
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            const int chunk = tid + i * kPrefillThreads;
-            *reinterpret_cast<uint4*>(smem + stage * kStageBytes + (chunk / 16) * kKRowBytes + (chunk % 16) * 16) = kst[i];
-            *reinterpret_cast<uint4*>(smem + stage * kStageBytes + kKTileBytes + (chunk / 8) * kVRowBytes + (chunk % 8) * 16) = vst[i];
-        }
-    };
+    static_assert(kTile * 16 == 2 * kPrefillThreads, "each thread stages two chunks per tile");
+    uint4 kst0, kst1, vst0, vst1;
+    const int c0 = tid, c1 = tid + kPrefillThreads;  // 1024 chunks of 16 B per tile
+#define LSERVE_FETCH(JT)                                                                                          \
+    {                                                                                                             \
+        const int jt_ = (JT);                                                                                     \
+        const uint16_t* vsrc_ = vtbase + (size_t)jt_ * kHeadDim * kTile;                                          \
+        kst0 = reinterpret_cast<const uint4*>(kbase + (size_t)min(jt_ * kTile + c0 / 16, len - 1) * lp.Hkv * kHeadDim)[c0 % 16]; \
+        kst1 = reinterpret_cast<const uint4*>(kbase + (size_t)min(jt_ * kTile + c1 / 16, len - 1) * lp.Hkv * kHeadDim)[c1 % 16]; \
+        vst0 = reinterpret_cast<const uint4*>(vsrc_)[c0];                                                         \
+        vst1 = reinterpret_cast<const uint4*>(vsrc_)[c1];                                                         \
+    }
+#define LSERVE_STASH(STAGE)                                                                                       \
+    {                                                                                                             \
+        unsigned char* kd_ = smem + (STAGE) * kStageBytes;                                                        \
+        unsigned char* vd_ = kd_ + kKTileBytes;                                                                   \
+        *reinterpret_cast<uint4*>(kd_ + (c0 / 16) * kKRowBytes + (c0 % 16) * 16) = kst0;                          \
+        *reinterpret_cast<uint4*>(kd_ + (c1 / 16) * kKRowBytes + (c1 % 16) * 16) = kst1;                          \
+        *reinterpret_cast<uint4*>(vd_ + (c0 / 8) * kVRowBytes + (c0 % 8) * 16) = vst0;                            \
+        *reinterpret_cast<uint4*>(vd_ + (c1 / 8) * kVRowBytes + (c1 % 8) * 16) = vst1;                            \
+    }
+    auto tile_of = [sink_end, band_begin](int it) { return it < sink_end ? it : band_begin + (it - sink_end); };
 
-    fetch(tile_of(0));
-    stash(0);
+    LSERVE_FETCH(tile_of(0));
+    LSERVE_STASH(0);
     __syncthreads();
 
     for (int it = 0; it < n_visit; ++it) {
         const int stage = it & 1;
         const int jt = tile_of(it);
-        if (it + 1 < n_visit) fetch(tile_of(it + 1));
+        if (it + 1 < n_visit) LSERVE_FETCH(tile_of(it + 1));
 
         // does this wave's mask tile keep key tile jt?
         bool keep = wave_has_rows && jt <= iq;
@@ -179,106 +191,93 @@ __global__ __launch_bounds__(kPrefillThreads) void sparse_prefill_kernel(
         if (keep) {
             const unsigned char* ks = smem + stage * kStageBytes;
             const unsigned char* vs = ks + kKTileBytes;
-            // S^T for the 64 keys of the tile: [key block][query block]
-            float16_t s[2][2];
+            const bool diagonal = jt == iq;
+            // S^T for the 64 keys of the tile, two blocks of 32 keys
+            float16_t s[2];
 #pragma unroll
             for (int kb = 0; kb < 2; ++kb) {
 #pragma unroll
-                for (int qb = 0; qb < 2; ++qb)
-#pragma unroll
-                    for (int i = 0; i < 16; ++i) s[kb][qb][i] = 0.f;
+                for (int i = 0; i < 16; ++i) s[kb][i] = 0.f;
 #pragma unroll
                 for (int kk = 0; kk < 8; ++kk) {
                     const uint4 a = *reinterpret_cast<const uint4*>(ks + (kb * 32 + n) * kKRowBytes + kk * 32 + half * 16);
-                    s[kb][0] = Mfma<T>::run(a, qreg[0][kk], s[kb][0]);
-                    s[kb][1] = Mfma<T>::run(a, qreg[1][kk], s[kb][1]);
+                    s[kb] = Mfma<T>::run(a, qreg[kk], s[kb]);
                 }
             }
-            const bool diagonal = jt == iq;
-#pragma unroll
-            for (int qb = 0; qb < 2; ++qb) {
-                float mx = -INFINITY;
-#pragma unroll
-                for (int kb = 0; kb < 2; ++kb) {
-#pragma unroll
-                    for (int i = 0; i < 16; ++i) {
-                        float x = s[kb][qb][i] * lp.sm_scale_log2;
-                        if (diagonal) {
-                            const int key = kb * 32 + 8 * (i / 4) + 4 * half + (i % 4);
-                            if (key > qb * 32 + n) x = -INFINITY;
-                        }
-                        s[kb][qb][i] = x;
-                        mx = fmaxf(mx, x);
-                    }
-                }
-                mx = fmaxf(mx, __shfl_xor(mx, 32, kWave));
-                const float m_new = fmaxf(m[qb], mx);
-                const float m_safe = m_new == -INFINITY ? 0.f : m_new;
-                const float alpha = __builtin_amdgcn_exp2f(m[qb] - m_safe);
-                m[qb] = m_new;
-                float ps = 0.f;
+            if (diagonal) {  // causal mask inside the diagonal tile
 #pragma unroll
                 for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
                     for (int i = 0; i < 16; ++i) {
-                        const float p = __builtin_amdgcn_exp2f(s[kb][qb][i] - m_safe);
-                        s[kb][qb][i] = p;
-                        ps += p;
+                        const int key = kb * 32 + 8 * (i / 4) + 4 * half + (i % 4);
+                        if (key > row0 + n) s[kb][i] = -INFINITY;
                     }
-                l[qb] = l[qb] * alpha + ps;
+            }
+            // online softmax of this lane's query row (its keys are split between the two lane halves)
+            float mx = fmaxf(s[0][0], s[1][0]);
+#pragma unroll
+            for (int i = 1; i < 16; ++i) mx = fmaxf(mx, fmaxf(s[0][i], s[1][i]));
+            mx = halves_max(mx) * lp.sm_scale_log2;
+            const float m_new = fmaxf(m_run, mx);
+            if (__any(m_new > m_run)) {  // rescale only when some row's maximum moved
+                const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);  // exp2(-inf) = 0 on the first tile
+                l_run *= alpha;
 #pragma unroll
                 for (int db = 0; db < 4; ++db)
 #pragma unroll
-                    for (int i = 0; i < 16; ++i) acc[db][qb][i] *= alpha;
+                    for (int i = 0; i < 16; ++i) acc[db][i] *= alpha;
+                m_run = m_new;
+            }
+            uint4 pb[2][2];  // P^T packed to 16 bit: [key block][16-key step]
+#pragma unroll
+            for (int kb = 0; kb < 2; ++kb) {
+                float pf[16];
+#pragma unroll
+                for (int i = 0; i < 16; ++i) pf[i] = __builtin_amdgcn_exp2f(__builtin_fmaf(s[kb][i], lp.sm_scale_log2, -m_run));
+                pb[kb][0] = pack8<T>(pf);
+                pb[kb][1] = pack8<T>(pf + 8);
+                // row sum from the rounded weights, the same values the second product uses
+                const uint32_t w[8] = {pb[kb][0].x, pb[kb][0].y, pb[kb][0].z, pb[kb][0].w,
+                                       pb[kb][1].x, pb[kb][1].y, pb[kb][1].z, pb[kb][1].w};
+#pragma unroll
+                for (int u = 0; u < 8; ++u) l_run = Elem<T>::dot2(w[u], Ones<T>::pair, l_run);
             }
             // O^T += V^T * P^T, 16 keys per instruction
 #pragma unroll
-            for (int kb = 0; kb < 2; ++kb) {
+            for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
-                for (int j = 0; j < 2; ++j) {
-                    float pf0[8], pf1[8];
-#pragma unroll
-                    for (int e = 0; e < 8; ++e) {
-                        pf0[e] = s[kb][0][8 * j + e];
-                        pf1[e] = s[kb][1][8 * j + e];
-                    }
-                    const uint4 p0 = pack8<T>(pf0), p1 = pack8<T>(pf1);
+                for (int j = 0; j < 2; ++j)
 #pragma unroll
                     for (int db = 0; db < 4; ++db) {
                         const uint4 a = *reinterpret_cast<const uint4*>(vs + (db * 32 + n) * kVRowBytes +
                                                                         (kb * 32 + j * 16 + half * 8) * 2);
-                        acc[db][0] = Mfma<T>::run(a, p0, acc[db][0]);
-                        acc[db][1] = Mfma<T>::run(a, p1, acc[db][1]);
+                        acc[db] = Mfma<T>::run(a, pb[kb][j], acc[db]);
                     }
-                }
-            }
         }
-        if (it + 1 < n_visit) stash(stage ^ 1);
+        if (it + 1 < n_visit) LSERVE_STASH(stage ^ 1);
         __syncthreads();
     }
+#undef LSERVE_FETCH
+#undef LSERVE_STASH
 
     if (!wave_has_rows) return;
     // ---- epilogue: lane (n, half) holds O^T[d][q] for d = 32 db + 8 (i / 4) + 4 half + i % 4
+    const float lt = halves_sum(l_run);
+    const int row = iq * kTile + row0 + n;
+    if (row >= len) return;
+    const float inv = 1.f / lt;
+    uint16_t* dst = out + ((size_t)(start + row) * lp.H + h) * kHeadDim;
 #pragma unroll
-    for (int qb = 0; qb < 2; ++qb) {
-        const float lt = l[qb] + __shfl_xor(l[qb], 32, kWave);
-        const int row = iq * kTile + qb * 32 + n;
-        if (row >= len) continue;
-        const float inv = 1.f / lt;
-        uint16_t* dst = out + ((size_t)(start + row) * lp.H + h) * kHeadDim;
+    for (int db = 0; db < 4; ++db)
 #pragma unroll
-        for (int db = 0; db < 4; ++db)
-#pragma unroll
-            for (int g4 = 0; g4 < 4; ++g4) {
-                const int d = db * 32 + 8 * g4 + 4 * half;
-                uint2 w;
-                w.x = Elem<T>::pack(acc[db][qb][4 * g4] * inv, acc[db][qb][4 * g4 + 1] * inv);
-                w.y = Elem<T>::pack(acc[db][qb][4 * g4 + 2] * inv, acc[db][qb][4 * g4 + 3] * inv);
-                *reinterpret_cast<uint2*>(dst + d) = w;
-            }
-        if (lse_out && half == 0)
-            lse_out[(size_t)h * total_tokens + start + row] = (m[qb] + __builtin_amdgcn_logf(lt)) * kLn2;
-    }
+        for (int g4 = 0; g4 < 4; ++g4) {
+            const int d = db * 32 + 8 * g4 + 4 * half;
+            uint2 w;
+            w.x = Elem<T>::pack(acc[db][4 * g4] * inv, acc[db][4 * g4 + 1] * inv);
+            w.y = Elem<T>::pack(acc[db][4 * g4 + 2] * inv, acc[db][4 * g4 + 3] * inv);
+            *reinterpret_cast<uint2*>(dst + d) = w;
+        }
+    if (lse_out && half == 0) lse_out[(size_t)h * total_tokens + start + row] = (m_run + __builtin_amdgcn_logf(lt)) * kLn2;
 }
 
 int prefill_tile_slots(int total_tokens, int batch) { return total_tokens / kTile + batch; }
