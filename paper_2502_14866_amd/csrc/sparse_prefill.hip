@@ -92,6 +92,43 @@ __device__ __forceinline__ uint4 pack8(const float* p) {
 __device__ __forceinline__ float halves_max(float x) { return fmaxf(x, __shfl_xor(x, 32, kWave)); }
 __device__ __forceinline__ float halves_sum(float x) { return x + __shfl_xor(x, 32, kWave); }
 
+// Work order of the launch.  Workgroup ids go round-robin over the eight XCDs, each with its own L2.
+// Dense heads come first (heaviest query blocks first), streaming heads after.  When the number of
+// heads of a class divides 8, an XCD serves a single KV head of that class at a time, so the
+// workgroups resident on it (the query heads of one group, neighbouring query blocks) walk the
+// same K / V tiles together and share them in that L2.
+constexpr int kXcds = 8;
+struct HeadClass {
+    int heads;          // KV heads of this class
+    int slices;         // query-block slices per head spread over XCDs (1 when not swizzled)
+    int swizzled;       // 8 % heads == 0
+    int items_per_xcd;  // workgroups of this class per XCD
+    unsigned char kv_head[64];
+};
+struct PrefillSchedule {
+    HeadClass cls[2];  // dense, streaming
+    int qblocks_total; // batch * blocks_per_seq
+};
+
+// Decodes workgroup `li` of XCD `xcd` inside a class.  Returns false for padding workgroups.
+__device__ __forceinline__ bool decode_work(const HeadClass& hc, int n, int qblocks_total, int xcd, int li, int& hk,
+                                            int& hh, int& rank) {
+    int hidx;
+    if (hc.swizzled) {
+        hidx = xcd % hc.heads;
+        const int slice = xcd / hc.heads;
+        hh = li % n;
+        rank = (li / n) * hc.slices + slice;
+    } else {
+        const int t = li * kXcds + xcd;
+        hh = t % n;
+        hidx = (t / n) % hc.heads;
+        rank = t / (n * hc.heads);
+    }
+    hk = hc.kv_head[hidx];
+    return rank < qblocks_total;
+}
+
 template <class T> struct Ones;
 template <> struct Ones<F16> { static constexpr uint32_t pair = 0x3c003c00u; };
 template <> struct Ones<BF16> { static constexpr uint32_t pair = 0x3f803f80u; };
@@ -100,17 +137,25 @@ template <class T>
 __global__ __launch_bounds__(kPrefillThreads) void sparse_prefill_kernel(
     LayerParams lp, const uint16_t* __restrict__ q, const uint16_t* __restrict__ k, const uint16_t* __restrict__ vt,
     const int* __restrict__ cu_seqlens, int batch, int blocks_per_seq, int tiles_total, uint16_t* __restrict__ out,
-    float* __restrict__ lse_out, int total_tokens) {
+    float* __restrict__ lse_out, int total_tokens, PrefillSchedule sched) {
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
     // two stages of (K tile, V^T tile)
     constexpr int kStageBytes = kKTileBytes + kVTileBytes;
 
-    // heaviest query blocks first; heads of one GQA group are neighbours
-    const int h = blockIdx.x % lp.H;
-    const int rest = blockIdx.x / lp.H;
-    const int b = rest % batch;
-    const int qblk = blocks_per_seq - 1 - rest / batch;
-    const int hk = h / lp.group;
+    // heaviest query blocks first; see PrefillSchedule for the XCD-aware order
+    const int xcd = blockIdx.x % kXcds;
+    int li = blockIdx.x / kXcds, hk, hh, rank;
+    bool real;
+    if (li < sched.cls[0].items_per_xcd) {
+        real = decode_work(sched.cls[0], lp.group, sched.qblocks_total, xcd, li, hk, hh, rank);
+    } else {
+        li -= sched.cls[0].items_per_xcd;
+        real = decode_work(sched.cls[1], lp.group, sched.qblocks_total, xcd, li, hk, hh, rank);
+    }
+    if (!real) return;
+    const int h = hk * lp.group + hh;
+    const int b = rank % batch;
+    const int qblk = blocks_per_seq - 1 - rank / batch;
     const int start = cu_seqlens[b], len = cu_seqlens[b + 1] - start;
     if (qblk * kRowsPerBlock >= len) return;
 
@@ -141,6 +186,12 @@ __global__ __launch_bounds__(kPrefillThreads) void sparse_prefill_kernel(
         const uint4* src = reinterpret_cast<const uint4*>(q + ((size_t)(start + row) * lp.H + h) * kHeadDim);
 #pragma unroll
         for (int kk = 0; kk < 8; ++kk) qreg[kk] = src[kk * 2 + half];
+        // Pin the loads here.  Left alone the compiler sinks them to the loop entry, and because the
+        // memory counter completes in order every tile's first product would then wait for that
+        // tile's K / V prefetch.
+#pragma unroll
+        for (int kk = 0; kk < 8; ++kk)
+            asm volatile("" : "+v"(qreg[kk].x), "+v"(qreg[kk].y), "+v"(qreg[kk].z), "+v"(qreg[kk].w));
     }
 
     float16_t acc[4];
@@ -154,36 +205,40 @@ __global__ __launch_bounds__(kPrefillThreads) void sparse_prefill_kernel(
     const uint16_t* kbase = k + ((size_t)start * lp.Hkv + hk) * kHeadDim;
     const uint16_t* vtbase = vt + ((size_t)hk * tiles_total + tile_base(start, b)) * kHeadDim * kTile;
     static_assert(kTile * 16 == 2 * kPrefillThreads, "each thread stages two chunks per tile");
-    uint4 kst0, kst1, vst0, vst1;
+    // Two register sets keep the tiles it + 1 and it + 2 in flight while tile it is consumed from
+    // LDS: one tile of look-ahead does not cover the latency of a load that misses the L2.
+    uint4 ra_k0 = {}, ra_k1 = {}, ra_v0 = {}, ra_v1 = {}, rb_k0 = {}, rb_k1 = {}, rb_v0 = {}, rb_v1 = {};
     const int c0 = tid, c1 = tid + kPrefillThreads;  // 1024 chunks of 16 B per tile
-#define LSERVE_FETCH(JT)                                                                                          \
+#define LSERVE_FETCH(R, JT)                                                                                       \
     {                                                                                                             \
         const int jt_ = (JT);                                                                                     \
         const uint16_t* vsrc_ = vtbase + (size_t)jt_ * kHeadDim * kTile;                                          \
-        kst0 = reinterpret_cast<const uint4*>(kbase + (size_t)min(jt_ * kTile + c0 / 16, len - 1) * lp.Hkv * kHeadDim)[c0 % 16]; \
-        kst1 = reinterpret_cast<const uint4*>(kbase + (size_t)min(jt_ * kTile + c1 / 16, len - 1) * lp.Hkv * kHeadDim)[c1 % 16]; \
-        vst0 = reinterpret_cast<const uint4*>(vsrc_)[c0];                                                         \
-        vst1 = reinterpret_cast<const uint4*>(vsrc_)[c1];                                                         \
+        R##_k0 = reinterpret_cast<const uint4*>(kbase + (size_t)min(jt_ * kTile + c0 / 16, len - 1) * lp.Hkv * kHeadDim)[c0 % 16]; \
+        R##_k1 = reinterpret_cast<const uint4*>(kbase + (size_t)min(jt_ * kTile + c1 / 16, len - 1) * lp.Hkv * kHeadDim)[c1 % 16]; \
+        R##_v0 = reinterpret_cast<const uint4*>(vsrc_)[c0];                                                         \
+        R##_v1 = reinterpret_cast<const uint4*>(vsrc_)[c1];                                                         \
     }
-#define LSERVE_STASH(STAGE)                                                                                       \
+#define LSERVE_STASH(R, STAGE)                                                                                    \
     {                                                                                                             \
         unsigned char* kd_ = smem + (STAGE) * kStageBytes;                                                        \
         unsigned char* vd_ = kd_ + kKTileBytes;                                                                   \
-        *reinterpret_cast<uint4*>(kd_ + (c0 / 16) * kKRowBytes + (c0 % 16) * 16) = kst0;                          \
-        *reinterpret_cast<uint4*>(kd_ + (c1 / 16) * kKRowBytes + (c1 % 16) * 16) = kst1;                          \
-        *reinterpret_cast<uint4*>(vd_ + (c0 / 8) * kVRowBytes + (c0 % 8) * 16) = vst0;                            \
-        *reinterpret_cast<uint4*>(vd_ + (c1 / 8) * kVRowBytes + (c1 % 8) * 16) = vst1;                            \
+        *reinterpret_cast<uint4*>(kd_ + (c0 / 16) * kKRowBytes + (c0 % 16) * 16) = R##_k0;                          \
+        *reinterpret_cast<uint4*>(kd_ + (c1 / 16) * kKRowBytes + (c1 % 16) * 16) = R##_k1;                          \
+        *reinterpret_cast<uint4*>(vd_ + (c0 / 8) * kVRowBytes + (c0 % 8) * 16) = R##_v0;                            \
+        *reinterpret_cast<uint4*>(vd_ + (c1 / 8) * kVRowBytes + (c1 % 8) * 16) = R##_v1;                            \
     }
     auto tile_of = [sink_end, band_begin](int it) { return it < sink_end ? it : band_begin + (it - sink_end); };
 
-    LSERVE_FETCH(tile_of(0));
-    LSERVE_STASH(0);
+    LSERVE_FETCH(ra, tile_of(0));
+    if (n_visit > 1) LSERVE_FETCH(rb, tile_of(1));
+    LSERVE_STASH(ra, 0);
     __syncthreads();
 
     for (int it = 0; it < n_visit; ++it) {
         const int stage = it & 1;
         const int jt = tile_of(it);
-        if (it + 1 < n_visit) LSERVE_FETCH(tile_of(it + 1));
+        // rb holds tile it + 1 (in flight since the previous iteration); start tile it + 2
+        if (it + 2 < n_visit) LSERVE_FETCH(ra, tile_of(it + 2));
 
         // does this wave's mask tile keep key tile jt?
         bool keep = wave_has_rows && jt <= iq;
@@ -192,18 +247,33 @@ __global__ __launch_bounds__(kPrefillThreads) void sparse_prefill_kernel(
             const unsigned char* ks = smem + stage * kStageBytes;
             const unsigned char* vs = ks + kKTileBytes;
             const bool diagonal = jt == iq;
-            // S^T for the 64 keys of the tile, two blocks of 32 keys
+            // S^T for the 64 keys of the tile, two blocks of 32 keys.  All operand reads of a block are
+            // issued before its products so that LDS latency is paid once, and the two blocks'
+            // accumulation chains alternate in the matrix pipe.
             float16_t s[2];
+            uint4 ka[8][2];
 #pragma unroll
-            for (int kb = 0; kb < 2; ++kb) {
+            for (int kk = 0; kk < 8; ++kk)
+#pragma unroll
+                for (int kb = 0; kb < 2; ++kb)
+                    ka[kk][kb] = *reinterpret_cast<const uint4*>(ks + (kb * 32 + n) * kKRowBytes + kk * 32 + half * 16);
+#pragma unroll
+            for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
                 for (int i = 0; i < 16; ++i) s[kb][i] = 0.f;
 #pragma unroll
-                for (int kk = 0; kk < 8; ++kk) {
-                    const uint4 a = *reinterpret_cast<const uint4*>(ks + (kb * 32 + n) * kKRowBytes + kk * 32 + half * 16);
-                    s[kb] = Mfma<T>::run(a, qreg[kk], s[kb]);
-                }
+            for (int kk = 0; kk < 8; ++kk) {
+                s[0] = Mfma<T>::run(ka[kk][0], qreg[kk], s[0]);
+                s[1] = Mfma<T>::run(ka[kk][1], qreg[kk], s[1]);
             }
+            // schedule: operand reads run four ahead of the products that consume them
+            __builtin_amdgcn_sched_group_barrier(0x100, 4, 0);
+#pragma unroll
+            for (int u = 0; u < 12; ++u) {
+                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+                __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+            }
+            __builtin_amdgcn_sched_group_barrier(0x008, 4, 0);
             if (diagonal) {  // causal mask inside the diagonal tile
 #pragma unroll
                 for (int kb = 0; kb < 2; ++kb)
@@ -242,20 +312,25 @@ __global__ __launch_bounds__(kPrefillThreads) void sparse_prefill_kernel(
 #pragma unroll
                 for (int u = 0; u < 8; ++u) l_run = Elem<T>::dot2(w[u], Ones<T>::pair, l_run);
             }
-            // O^T += V^T * P^T, 16 keys per instruction
+            // O^T += V^T * P^T, 16 keys per instruction; operand reads run one step ahead
 #pragma unroll
-            for (int kb = 0; kb < 2; ++kb)
+            for (int step = 0; step < 4; ++step) {
+                const int kb = step / 2, j = step % 2;
+                uint4 va[4];
 #pragma unroll
-                for (int j = 0; j < 2; ++j)
+                for (int db = 0; db < 4; ++db)
+                    va[db] = *reinterpret_cast<const uint4*>(vs + (db * 32 + n) * kVRowBytes +
+                                                             (kb * 32 + j * 16 + half * 8) * 2);
 #pragma unroll
-                    for (int db = 0; db < 4; ++db) {
-                        const uint4 a = *reinterpret_cast<const uint4*>(vs + (db * 32 + n) * kVRowBytes +
-                                                                        (kb * 32 + j * 16 + half * 8) * 2);
-                        acc[db] = Mfma<T>::run(a, pb[kb][j], acc[db]);
-                    }
+                for (int db = 0; db < 4; ++db) acc[db] = Mfma<T>::run(va[db], pb[kb][j], acc[db]);
+            }
         }
-        if (it + 1 < n_visit) LSERVE_STASH(stage ^ 1);
+        if (it + 1 < n_visit) LSERVE_STASH(rb, stage ^ 1);
         __syncthreads();
+        rb_k0 = ra_k0;
+        rb_k1 = ra_k1;
+        rb_v0 = ra_v0;
+        rb_v1 = ra_v1;
     }
 #undef LSERVE_FETCH
 #undef LSERVE_STASH
@@ -302,9 +377,26 @@ hipError_t launch_prefill(const LayerParams& lp, const void* q, const void* k, c
         if (e != hipSuccess) return e;
         attr_done = true;
     }
-    hipLaunchKernelGGL(sparse_prefill_kernel<T>, dim3(blocks_per_seq * batch * lp.H), dim3(kPrefillThreads), lds, stream,
+    PrefillSchedule sched;
+    sched.qblocks_total = blocks_per_seq * batch;
+    for (int c = 0; c < 2; ++c) {
+        HeadClass& hc = sched.cls[c];
+        hc.heads = 0;
+        for (int hk = 0; hk < lp.Hkv; ++hk)
+            if ((int)((lp.streaming_mask >> hk) & 1ull) == c) hc.kv_head[hc.heads++] = (unsigned char)hk;
+        hc.swizzled = hc.heads > 0 && kXcds % hc.heads == 0;
+        hc.slices = hc.swizzled ? kXcds / hc.heads : 1;
+        if (hc.heads == 0)
+            hc.items_per_xcd = 0;
+        else if (hc.swizzled)
+            hc.items_per_xcd = lp.group * ((sched.qblocks_total + hc.slices - 1) / hc.slices);
+        else
+            hc.items_per_xcd = (hc.heads * lp.group * sched.qblocks_total + kXcds - 1) / kXcds;
+    }
+    const int grid = kXcds * (sched.cls[0].items_per_xcd + sched.cls[1].items_per_xcd);
+    hipLaunchKernelGGL(sparse_prefill_kernel<T>, dim3(grid), dim3(kPrefillThreads), lds, stream,
                        lp, reinterpret_cast<const uint16_t*>(q), reinterpret_cast<const uint16_t*>(k), vt, cu_seqlens,
-                       batch, blocks_per_seq, tiles_total, reinterpret_cast<uint16_t*>(out), lse_out, total_tokens);
+                       batch, blocks_per_seq, tiles_total, reinterpret_cast<uint16_t*>(out), lse_out, total_tokens, sched);
     return hipGetLastError();
 }
 
