@@ -205,9 +205,9 @@ __global__ __launch_bounds__(kPrefillThreads) void sparse_prefill_kernel(
     const uint16_t* kbase = k + ((size_t)start * lp.Hkv + hk) * kHeadDim;
     const uint16_t* vtbase = vt + ((size_t)hk * tiles_total + tile_base(start, b)) * kHeadDim * kTile;
     static_assert(kTile * 16 == 2 * kPrefillThreads, "each thread stages two chunks per tile");
-    // Two register sets keep the tiles it + 1 and it + 2 in flight while tile it is consumed from
-    // LDS: one tile of look-ahead does not cover the latency of a load that misses the L2.
-    uint4 ra_k0 = {}, ra_k1 = {}, ra_v0 = {}, ra_v1 = {}, rb_k0 = {}, rb_k1 = {}, rb_v0 = {}, rb_v1 = {};
+    // The next tile travels through registers while the current one is consumed from LDS; with the
+    // XCD-aware work order these loads hit the L2, so one tile of look-ahead covers their latency.
+    uint4 ra_k0 = {}, ra_k1 = {}, ra_v0 = {}, ra_v1 = {};
     const int c0 = tid, c1 = tid + kPrefillThreads;  // 1024 chunks of 16 B per tile
 #define LSERVE_FETCH(R, JT)                                                                                       \
     {                                                                                                             \
@@ -230,15 +230,13 @@ __global__ __launch_bounds__(kPrefillThreads) void sparse_prefill_kernel(
     auto tile_of = [sink_end, band_begin](int it) { return it < sink_end ? it : band_begin + (it - sink_end); };
 
     LSERVE_FETCH(ra, tile_of(0));
-    if (n_visit > 1) LSERVE_FETCH(rb, tile_of(1));
     LSERVE_STASH(ra, 0);
     __syncthreads();
 
     for (int it = 0; it < n_visit; ++it) {
         const int stage = it & 1;
         const int jt = tile_of(it);
-        // rb holds tile it + 1 (in flight since the previous iteration); start tile it + 2
-        if (it + 2 < n_visit) LSERVE_FETCH(ra, tile_of(it + 2));
+        if (it + 1 < n_visit) LSERVE_FETCH(ra, tile_of(it + 1));
 
         // does this wave's mask tile keep key tile jt?
         bool keep = wave_has_rows && jt <= iq;
@@ -286,7 +284,7 @@ __global__ __launch_bounds__(kPrefillThreads) void sparse_prefill_kernel(
             // online softmax of this lane's query row (its keys are split between the two lane halves)
             float mx = fmaxf(s[0][0], s[1][0]);
 #pragma unroll
-            for (int i = 1; i < 16; ++i) mx = fmaxf(mx, fmaxf(s[0][i], s[1][i]));
+            for (int i = 1; i < 16; ++i) mx = __builtin_fmaxf(__builtin_fmaxf(mx, s[0][i]), s[1][i]);  // v_max3_f32
             mx = halves_max(mx) * lp.sm_scale_log2;
             const float m_new = fmaxf(m_run, mx);
             if (__any(m_new > m_run)) {  // rescale only when some row's maximum moved
@@ -325,12 +323,8 @@ __global__ __launch_bounds__(kPrefillThreads) void sparse_prefill_kernel(
                 for (int db = 0; db < 4; ++db) acc[db] = Mfma<T>::run(va[db], pb[kb][j], acc[db]);
             }
         }
-        if (it + 1 < n_visit) LSERVE_STASH(rb, stage ^ 1);
+        if (it + 1 < n_visit) LSERVE_STASH(ra, stage ^ 1);
         __syncthreads();
-        rb_k0 = ra_k0;
-        rb_k1 = ra_k1;
-        rb_v0 = ra_v0;
-        rb_v1 = ra_v1;
     }
 #undef LSERVE_FETCH
 #undef LSERVE_STASH

@@ -21,3 +21,37 @@ def small_decode_workload(**kw):
                 reuse_interval=2, decode_steps=2, lengths=(300, 777), seed=7, pool_slack=0.3)
     base.update(kw)
     return Workload(**base)
+
+
+def sub_problem(inp, seqs):
+    """CPU copy of the sequences `seqs` of a (possibly device-resident, large) decode problem.
+
+    Only the pages those sequences own are gathered into a small pool with a renumbered page table,
+    so that the oracle can check sampled sequences of a full-size run.  Pure indexing and copies.
+    """
+    from workloads import DecodeInputs
+    from dataclasses import replace
+
+    w = inp.workload
+    steps = max(1, w.decode_steps)
+    rows, tables, off = [], [], 0
+    max_pages = inp.page_table.shape[1]
+    for b in seqs:
+        n_pages = (int(inp.prompt_lens[b]) + steps + w.page_size - 1) // w.page_size
+        rows.append(inp.page_table[b, :n_pages].long())
+        t = torch.zeros(max_pages, dtype=torch.int32)
+        t[:n_pages] = torch.arange(off, off + n_pages, dtype=torch.int32)
+        tables.append(t)
+        off += n_pages
+    idx = torch.cat(rows)
+    sel = torch.tensor(list(seqs), dtype=torch.long, device=inp.q.device)
+    return DecodeInputs(
+        workload=replace(w, batch=len(seqs)),
+        k_pool=inp.k_pool[idx].cpu(),
+        v_pool=inp.v_pool[idx].cpu(),
+        page_table=torch.stack(tables),
+        prompt_lens=inp.prompt_lens[sel].cpu(),
+        q=inp.q[:, sel].cpu(),
+        needle_pos=None if inp.needle_pos is None else inp.needle_pos[list(seqs)],
+        k_scale=inp.k_scale,
+    )
