@@ -345,6 +345,13 @@ def run_profile_only(args, torch, L, sess, inp, len_table, w, dev):
     if args.profile_only == "prefill":
         print(json.dumps(bench_prefill(torch, L, dev, args.prefill_tokens)))
         return
+    # a plain copy of known size in the same run calibrates the memory counters (FETCH_SIZE / WRITE_SIZE)
+    cal_src = torch.empty((128 << 20,), dtype=torch.float16, device=dev).normal_()
+    cal_dst = torch.empty_like(cal_src)
+    for _ in range(3):
+        cal_dst.copy_(cal_src)
+    torch.cuda.synchronize()
+    sess.restart()
     sess.set_seq_lens(len_table[1, :B])
     sess.update_stats_tail(len_table[0, :B], 1)
     sess.select(inp.q[0])
@@ -359,7 +366,7 @@ def run_profile_only(args, torch, L, sess, inp, len_table, w, dev):
         else:
             sess.update_stats_tail(len_table[t, :B], 1)
     torch.cuda.synchronize()
-    print(json.dumps({"profile_only": args.profile_only, "launches": 20}))
+    print(json.dumps({"profile_only": args.profile_only, "launches": 20, "calibration_copy_bytes": cal_src.numel() * 2}))
 
 
 if __name__ == "__main__":
