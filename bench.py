@@ -263,35 +263,39 @@ def main():
     print(json.dumps(result))
 
 
-def cpu_baseline(torch, w, inp):
-    """The oracle, as it stands, on one reuse chunk (selector once, C decode steps) of the whole batch."""
+def cpu_baseline(torch, w, inp, episodes=3):
+    """The oracle, as it stands, on whole episodes of the same workload (every sequence, every head).
+
+    Key statistics are built once outside the timed region (the oracle has no incremental update and the
+    GPU path's per-run refresh touches a single logical page per sequence); page scoring, selection every
+    C steps and decode of every step are timed.
+    """
     import oracle
 
-    C = w.reuse_interval
+    C, E = w.reuse_interval, w.decode_steps
     k_cpu, v_cpu = inp.k_pool.cpu(), inp.v_pool.cpu()
     pt = inp.page_table.cpu()
-    q_cpu = inp.q[:C].cpu()
+    q_cpu = inp.q[:E].cpu()
     flags = w.streaming_flags()
     prompt = inp.prompt_lens.cpu()
+    stats = oracle.page_stats(k_cpu, pt, prompt + E, w.logical_page_size)
     t0 = time.perf_counter()
-    stats = None
-    for t in range(C):
-        seq = prompt + (t + 1)
-        if t == 0:
-            # statistics as the decode loop would hold them; the full build is outside the sample
-            stats = oracle.page_stats(k_cpu, pt, seq, w.logical_page_size)
-            t0 = time.perf_counter()
-            scores, _ = oracle.page_scores(q_cpu[0], stats, pt, seq, w.page_size)
-            sel, cnt, ssl = oracle.select_pages(scores, seq, w.page_size, w.budget_tokens)
-        oracle.sparse_decode(q_cpu[t], k_cpu, v_cpu, pt, seq, sel, cnt, ssl, flags, w.sink_tokens, w.local_tokens)
+    for _ in range(episodes):
+        for t in range(E):
+            seq = prompt + (t + 1)
+            if t % C == 0:
+                scores, _ = oracle.page_scores(q_cpu[t], stats, pt, seq, w.page_size)
+                sel, cnt, ssl = oracle.select_pages(scores, seq, w.page_size, w.budget_tokens)
+            oracle.sparse_decode(q_cpu[t], k_cpu, v_cpu, pt, seq, sel, cnt, ssl, flags, w.sink_tokens, w.local_tokens)
     dt = time.perf_counter() - t0
+    tokens = w.batch * E * episodes
     return {
-        "value": w.batch * C / dt,
+        "value": tokens / dt,
         "unit": "tokens/s",
         "cores": oracle.num_threads(),
         "kind": "oracle",
-        "sample": f"one reuse chunk of the same workload: 1 selector run + {C} decode steps, all {w.batch} sequences "
-                  f"({w.batch * C} tokens, {dt:.1f} s)",
+        "sample": f"{episodes} episodes of the same workload: {E // C * episodes} selector runs + {E * episodes} decode "
+                  f"steps, all {w.batch} sequences ({tokens} tokens, {dt:.1f} s); key statistics prepared outside",
     }
 
 
