@@ -145,6 +145,16 @@ __global__ __launch_bounds__(kTopkThreads) void topk_pages_kernel(LayerParams lp
     const float* sc = scores + ((size_t)b * lp.Hkv + hk) * kv.max_pages;
     const int M = P - 1;  // candidates: every page but the newest, which is always kept
     int need = K - 1;     // how many candidates to take
+    // each thread owns a contiguous range of pages; up to kCached keys stay in registers so that the
+    // radix passes and the compaction do not go back to memory
+    constexpr int kCached = 8;
+    const int per = ceil_div(M, (int)blockDim.x);
+    const int i0 = min(M, tid * per), i1 = min(M, i0 + per);
+    const bool cached = per <= kCached;
+    unsigned keys[kCached];
+#pragma unroll
+    for (int u = 0; u < kCached; ++u) keys[u] = (cached && i0 + u < i1) ? orderable(sc[i0 + u]) : 0u;
+
     unsigned threshold = 0xffffffffu;
     int need_eq = 0;
     if (need > 0) {
@@ -158,9 +168,15 @@ __global__ __launch_bounds__(kTopkThreads) void topk_pages_kernel(LayerParams lp
             for (int i = tid; i < 256; i += blockDim.x) hist[i] = 0;
             __syncthreads();
             const unsigned prefix = s_prefix;
-            for (int i = tid; i < M; i += blockDim.x) {
-                unsigned key = orderable(sc[i]);
-                if ((key & mask) == prefix) atomicAdd(&hist[(key >> shift) & 255u], 1);
+            if (cached) {
+#pragma unroll
+                for (int u = 0; u < kCached; ++u)
+                    if (i0 + u < i1 && (keys[u] & mask) == prefix) atomicAdd(&hist[(keys[u] >> shift) & 255u], 1);
+            } else {
+                for (int i = i0; i < i1; ++i) {
+                    const unsigned key = orderable(sc[i]);
+                    if ((key & mask) == prefix) atomicAdd(&hist[(key >> shift) & 255u], 1);
+                }
             }
             __syncthreads();
             if (tid < kWave) {
@@ -199,27 +215,40 @@ __global__ __launch_bounds__(kTopkThreads) void topk_pages_kernel(LayerParams lp
         need_eq = s_need;  // candidates equal to the threshold still to take, lowest indices first
     }
 
-    // index-ordered compaction: each thread owns a contiguous range of pages
-    const int per = ceil_div(M, (int)blockDim.x);
-    const int i0 = min(M, tid * per), i1 = min(M, i0 + per);
+    // index-ordered compaction over the threads' contiguous ranges
     int gt = 0, eq = 0;
-    for (int i = i0; i < i1; ++i) {
-        unsigned key = orderable(sc[i]);
-        gt += key > threshold;
-        eq += key == threshold;
+    if (cached) {
+#pragma unroll
+        for (int u = 0; u < kCached; ++u)
+            if (i0 + u < i1) {
+                gt += keys[u] > threshold;
+                eq += keys[u] == threshold;
+            }
+    } else {
+        for (int i = i0; i < i1; ++i) {
+            const unsigned key = orderable(sc[i]);
+            gt += key > threshold;
+            eq += key == threshold;
+        }
     }
     int egt, eeq, tgt, teq;
     block_exclusive_scan2(gt, eq, scan_lds, egt, eeq, tgt, teq);
     int pos = egt + min(eeq, need_eq);
     int eq_seen = eeq;
-    for (int i = i0; i < i1; ++i) {
-        unsigned key = orderable(sc[i]);
+    auto emit = [&](int i, unsigned key) {
         bool take = key > threshold;
         if (key == threshold) {
             take = eq_seen < need_eq;
             ++eq_seen;
         }
         if (take && pos < K - 1) out[pos++] = i;  // the bound only matters for non-finite scores
+    };
+    if (cached) {
+#pragma unroll
+        for (int u = 0; u < kCached; ++u)
+            if (i0 + u < i1) emit(i0 + u, keys[u]);
+    } else {
+        for (int i = i0; i < i1; ++i) emit(i, orderable(sc[i]));
     }
     if (tid == 0) {
         out[K - 1] = P - 1;
