@@ -248,6 +248,7 @@ __global__ __launch_bounds__(kPrefillThreads) void sparse_prefill_kernel(
             // S^T for the 64 keys of the tile, two blocks of 32 keys.  All operand reads of a block are
             // issued before its products so that LDS latency is paid once, and the two blocks'
             // accumulation chains alternate in the matrix pipe.
+            __builtin_amdgcn_s_setprio(2);  // products first: the other wavefront of the SIMD fills in with softmax work
             float16_t s[2];
             uint4 ka[8][2];
 #pragma unroll
@@ -272,6 +273,7 @@ __global__ __launch_bounds__(kPrefillThreads) void sparse_prefill_kernel(
                 __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
             }
             __builtin_amdgcn_sched_group_barrier(0x008, 4, 0);
+            __builtin_amdgcn_s_setprio(0);
             if (diagonal) {  // causal mask inside the diagonal tile
 #pragma unroll
                 for (int kb = 0; kb < 2; ++kb)
