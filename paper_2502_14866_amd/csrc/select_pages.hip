@@ -17,6 +17,7 @@ namespace {
 constexpr int kScoreThreads = 256;  // 4 waves, 4 pages per wave (one per 16-lane row)
 constexpr int kPagesPerBlock = 16;
 constexpr int kTopkThreads = 512;
+constexpr int kTopkLdsKeys = 8192;  // up to 8192 candidate pages (524288 tokens at N_P = 64) are ranked from LDS
 
 __device__ __forceinline__ unsigned orderable(float s) {
     unsigned u = __builtin_bit_cast(unsigned, s);
@@ -118,6 +119,7 @@ __global__ __launch_bounds__(kTopkThreads) void topk_pages_kernel(LayerParams lp
                                                                    int* __restrict__ sel_count,
                                                                    int* __restrict__ sel_seq_len) {
     __shared__ int hist[256];
+    __shared__ unsigned skeys[kTopkLdsKeys];  // the list's keys, when they fit: every pass then stays in LDS
     __shared__ int scan_lds[2 * kTopkThreads / kWave];
     __shared__ unsigned s_prefix;
     __shared__ int s_need;
@@ -144,17 +146,13 @@ __global__ __launch_bounds__(kTopkThreads) void topk_pages_kernel(LayerParams lp
 
     const float* sc = scores + ((size_t)b * lp.Hkv + hk) * kv.max_pages;
     const int M = P - 1;  // candidates: every page but the newest, which is always kept
+    const bool in_lds = M <= kTopkLdsKeys;
+    if (in_lds) {
+        for (int i = tid; i < M; i += blockDim.x) skeys[i] = orderable(sc[i]);
+        __syncthreads();
+    }
+    auto key_at = [&](int i) { return in_lds ? skeys[i] : orderable(sc[i]); };
     int need = K - 1;     // how many candidates to take
-    // each thread owns a contiguous range of pages; up to kCached keys stay in registers so that the
-    // radix passes and the compaction do not go back to memory
-    constexpr int kCached = 8;
-    const int per = ceil_div(M, (int)blockDim.x);
-    const int i0 = min(M, tid * per), i1 = min(M, i0 + per);
-    const bool cached = per <= kCached;
-    unsigned keys[kCached];
-#pragma unroll
-    for (int u = 0; u < kCached; ++u) keys[u] = (cached && i0 + u < i1) ? orderable(sc[i0 + u]) : 0u;
-
     unsigned threshold = 0xffffffffu;
     int need_eq = 0;
     if (need > 0) {
@@ -168,15 +166,9 @@ __global__ __launch_bounds__(kTopkThreads) void topk_pages_kernel(LayerParams lp
             for (int i = tid; i < 256; i += blockDim.x) hist[i] = 0;
             __syncthreads();
             const unsigned prefix = s_prefix;
-            if (cached) {
-#pragma unroll
-                for (int u = 0; u < kCached; ++u)
-                    if (i0 + u < i1 && (keys[u] & mask) == prefix) atomicAdd(&hist[(keys[u] >> shift) & 255u], 1);
-            } else {
-                for (int i = i0; i < i1; ++i) {
-                    const unsigned key = orderable(sc[i]);
-                    if ((key & mask) == prefix) atomicAdd(&hist[(key >> shift) & 255u], 1);
-                }
+            for (int i = tid; i < M; i += blockDim.x) {
+                unsigned key = key_at(i);
+                if ((key & mask) == prefix) atomicAdd(&hist[(key >> shift) & 255u], 1);
             }
             __syncthreads();
             if (tid < kWave) {
@@ -215,40 +207,27 @@ __global__ __launch_bounds__(kTopkThreads) void topk_pages_kernel(LayerParams lp
         need_eq = s_need;  // candidates equal to the threshold still to take, lowest indices first
     }
 
-    // index-ordered compaction over the threads' contiguous ranges
+    // index-ordered compaction: each thread owns a contiguous range of pages
+    const int per = ceil_div(M, (int)blockDim.x);
+    const int i0 = min(M, tid * per), i1 = min(M, i0 + per);
     int gt = 0, eq = 0;
-    if (cached) {
-#pragma unroll
-        for (int u = 0; u < kCached; ++u)
-            if (i0 + u < i1) {
-                gt += keys[u] > threshold;
-                eq += keys[u] == threshold;
-            }
-    } else {
-        for (int i = i0; i < i1; ++i) {
-            const unsigned key = orderable(sc[i]);
-            gt += key > threshold;
-            eq += key == threshold;
-        }
+    for (int i = i0; i < i1; ++i) {
+        unsigned key = key_at(i);
+        gt += key > threshold;
+        eq += key == threshold;
     }
     int egt, eeq, tgt, teq;
     block_exclusive_scan2(gt, eq, scan_lds, egt, eeq, tgt, teq);
     int pos = egt + min(eeq, need_eq);
     int eq_seen = eeq;
-    auto emit = [&](int i, unsigned key) {
+    for (int i = i0; i < i1; ++i) {
+        unsigned key = key_at(i);
         bool take = key > threshold;
         if (key == threshold) {
             take = eq_seen < need_eq;
             ++eq_seen;
         }
         if (take && pos < K - 1) out[pos++] = i;  // the bound only matters for non-finite scores
-    };
-    if (cached) {
-#pragma unroll
-        for (int u = 0; u < kCached; ++u)
-            if (i0 + u < i1) emit(i0 + u, keys[u]);
-    } else {
-        for (int i = i0; i < i1; ++i) emit(i, orderable(sc[i]));
     }
     if (tid == 0) {
         out[K - 1] = P - 1;
