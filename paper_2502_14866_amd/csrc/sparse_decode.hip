@@ -337,12 +337,13 @@ __device__ __forceinline__ int head_of_entry(const DecodePlan& plan, int Hkv, in
 }
 
 // Folds the pieces of one list, in slot order, eight at a time so that their loads are in flight
-// together.  A piece exists iff its first nominal entry is a real entry of the list (ranges between
-// j0 and j1 are never empty: an empty range implies quot = 0, and then no list spans two ranges).
+// together.  Every range between j0 and j1 wrote a piece (ranges there are never empty: an empty
+// range implies quot = 0, and then no list spans two ranges); a range that held only nominal
+// entries past the list's real length wrote a neutral piece (max = -inf), whose output is skipped.
 template <class T, int N>
-__device__ __forceinline__ void fold_pieces(const DecodePlan& plan, int list, int n0, int len, int j0, int j1, int hh,
-                                            int ch, int H, int b, int hk, uint16_t* out, float* lse_out,
-                                            const float* part_o, const float* part_ml) {
+__device__ __forceinline__ void fold_pieces(int list, int j0, int j1, int hh, int ch, int H, int b, int hk,
+                                            uint16_t* out, float* lse_out, const float* part_o,
+                                            const float* part_ml) {
     constexpr int kBatch = 8;
     float M = -INFINITY, lt = 0.f, acc = 0.f;
     for (int jb = j0; jb <= j1; jb += kBatch) {
@@ -350,7 +351,7 @@ __device__ __forceinline__ void fold_pieces(const DecodePlan& plan, int list, in
 #pragma unroll
         for (int u = 0; u < kBatch; ++u) {
             const int j = jb + u;
-            const bool real = j <= j1 && max(n0, range_begin(plan, j)) - n0 < len;
+            const bool real = j <= j1;
             const size_t pi = ((size_t)(real ? j : j0) + list) * N + hh;
             pm[u] = real ? part_ml[pi * 2] : -INFINITY;
             pl[u] = real ? part_ml[pi * 2 + 1] : 0.f;
@@ -368,7 +369,7 @@ __device__ __forceinline__ void fold_pieces(const DecodePlan& plan, int list, in
         for (int u = 0; u < kBatch; ++u) {
             const float f = __builtin_amdgcn_exp2f(pm[u] - m_new);
             lt += pl[u] * f;
-            acc += po[u] * f;
+            acc += pm[u] == -INFINITY ? 0.f : po[u] * f;  // a neutral piece has no output to read
         }
         M = m_new;
     }
@@ -442,6 +443,17 @@ __global__ __launch_bounds__(kDecodeThreads) void sparse_decode_kernel(
             my_tail = tail_start - head;  // position of entry i >= head is my_tail + i
             if (i == nominal - 1 && len > nominal) my_extra = len - nominal;
             if (my_valid) my_phys = kv.page_table[(size_t)b * kv.max_pages + my_pos];
+            // Validity is monotone in i, so if the first nominal entry of a split list inside this range
+            // is past the real length the range holds nothing of the list: leave a neutral piece so that
+            // the merge kernel needs no lengths.
+            const int n0 = x - i, n1 = n0 + nominal;
+            if (!my_valid && x == max(n0, lo) && !(n0 >= lo && n1 <= hi)) {
+                for (int hh = 0; hh < N; ++hh) {
+                    const size_t pi = ((size_t)blk + my_list) * N + hh;
+                    part_ml[pi * 2] = -INFINITY;
+                    part_ml[pi * 2 + 1] = 0.f;
+                }
+            }
         }
         unsigned long long todo = __ballot(my_valid);
         if (todo == 0) continue;
@@ -499,18 +511,15 @@ __global__ __launch_bounds__(kDecodeThreads) void sparse_decode_kernel(
 // Combines the pieces of every list that was cut by a range boundary, in slot order.
 template <class T, int N>
 __global__ __launch_bounds__(N* kHeadDim) void decode_merge_kernel(
-    LayerParams lp, PagedParams kv, DecodePlan plan, const int* __restrict__ sel_pages,
-    const int* __restrict__ sel_count, const int* __restrict__ sel_seq_len, int sel_stride,
-    uint16_t* __restrict__ out, float* __restrict__ lse_out, const float* __restrict__ part_o,
-    const float* __restrict__ part_ml) {
+    LayerParams lp, DecodePlan plan, uint16_t* __restrict__ out, float* __restrict__ lse_out,
+    const float* __restrict__ part_o, const float* __restrict__ part_ml) {
     const int hk = blockIdx.x, b = blockIdx.y, list = b * lp.Hkv + hk;
     const int n0 = b * plan.per_seq + plan.first[hk], n1 = b * plan.per_seq + plan.first[hk + 1];
     // workgroups whose ranges hold the first and the last nominal entry of the list
     const int j0 = range_of(plan, n0), j1 = range_of(plan, n1 - 1);
     if (j0 == j1) return;  // the list lay inside one range: the decode kernel wrote the final rows
-    const int len = make_page_list(lp, b, hk, kv.seq_lens[b], sel_pages, sel_count, sel_seq_len, sel_stride).len;
-    fold_pieces<T, N>(plan, list, n0, len, j0, j1, threadIdx.x / kHeadDim, threadIdx.x % kHeadDim, lp.H, b, hk, out, lse_out,
-                      part_o, part_ml);
+    fold_pieces<T, N>(list, j0, j1, threadIdx.x / kHeadDim, threadIdx.x % kHeadDim, lp.H, b, hk, out, lse_out, part_o,
+                      part_ml);
 }
 
 // ---- host side -----------------------------------------------------------------------------------
@@ -568,8 +577,8 @@ hipError_t launch_decode_kernels(const LayerParams& lp, const PagedParams& kv, c
                        sel_pages, sel_count, sel_seq_len, sel_stride, o16, lse_out, part_o, part_ml);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
-    hipLaunchKernelGGL((decode_merge_kernel<T, N>), dim3(lp.Hkv, kv.batch), dim3(N * kHeadDim), 0, stream, lp, kv, plan,
-                       sel_pages, sel_count, sel_seq_len, sel_stride, o16, lse_out, part_o, part_ml);
+    hipLaunchKernelGGL((decode_merge_kernel<T, N>), dim3(lp.Hkv, kv.batch), dim3(N * kHeadDim), 0, stream, lp, plan, o16,
+                       lse_out, part_o, part_ml);
     return hipGetLastError();
 }
 
