@@ -13,8 +13,9 @@ All inputs are synthetic, seeded, and resident in HBM before the timed region.  
 is captured once in a HIP graph and replayed; `value` is batch * steps / wall time.
 
 Extra objects in the JSON line:
-  roofline      sparse decode kernel: algorithmic KV bytes per launch / its mean duration (HIP
-                events around each launch inside an un-captured episode) against 8 TB/s
+  roofline      sparse decode launch (decode + merge kernel): algorithmic KV bytes per launch / its mean
+                duration inside the timed loop (HIP events around replays of the episode graph with and
+                without the decode calls) against 8 TB/s
   cpu_baseline  the CPU oracle on the host cores for one reuse chunk of the same workload
   selector, stats, prefill   per-call timings of the other entry points (prefill on the 64K bf16
                 configuration, against the bf16 MFMA peak)
@@ -163,39 +164,53 @@ def main():
     elapsed = time.perf_counter() - t0
     tokens_per_s = B * args.steps / elapsed
 
-    # ---- per-kernel timing inside an un-captured episode (HIP events on the launch stream) ----
-    reps = 6
-    dec_ms, sel_ms, st_ms = [], [], []
-    bytes_per_launch, pages_per_launch = [], []
-    for rep in range(reps):
+    # ---- duration of the decode launches inside the timed loop (HIP events on the launch stream) ----
+    # The same episode is captured once more without its lserve_sparse_decode calls; the difference of
+    # the two replays, both bracketed by events on the stream the kernels run on, is the time the 16
+    # decode launches (decode + merge kernel) take in the very loop that `value` times.
+    def episode_without_decode():
         sess.restart()
         for t in range(E):
-            q = inp.q[t]
-            sess.set_seq_lens(len_table[t + 1, :B])
-            ev = [torch.cuda.Event(enable_timing=True) for _ in range(4)]
-            ran_select = sess.steps_since_selection is None or sess.steps_since_selection >= C
-            ev[0].record()
-            if ran_select:  # statistics of the tokens appended since the previous selector run
-                sess.update_stats_tail(len_table[max(0, t + 1 - C), :B], min(C, t + 1))
-            ev[1].record()
-            if ran_select:
-                sess.select(q)
-            ev[2].record()
-            sess.steps_since_selection += 1
-            sess.decode(q)
-            ev[3].record()
-            torch.cuda.synchronize()
-            if ran_select:
-                st_ms.append(ev[0].elapsed_time(ev[1]))
-                sel_ms.append(ev[1].elapsed_time(ev[2]))
-            dec_ms.append(ev[2].elapsed_time(ev[3]))
-            if rep == 0:
-                nbytes, npages = decode_bytes_per_launch(w, len_table[t + 1, :B].cpu(), sess.sel_count.cpu(),
-                                                         sess.sel_seq_len.cpu())
-                bytes_per_launch.append(nbytes)
-                pages_per_launch.append(npages)
+            sess.step(inp.q[t], len_table[t + 1, :B], len_table[t, :B], run_decode=False)
+
+    def timed(fn, reps):
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        fn()
+        torch.cuda.synchronize()
+        e0.record()
+        for _ in range(reps):
+            fn()
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / reps
+
+    reps = max(4, min(40, args.steps // E))
+    if graph is not None:
+        graph_nd = torch.cuda.CUDAGraph()
+        episode_without_decode()
+        torch.cuda.synchronize()
+        with torch.cuda.graph(graph_nd):
+            episode_without_decode()
+        torch.cuda.synchronize()
+        full_ms = timed(graph.replay, reps)
+        rest_ms = timed(graph_nd.replay, reps)
+    else:
+        full_ms = timed(episode, reps)
+        rest_ms = timed(episode_without_decode, reps)
+    dec_mean_ms = (full_ms - rest_ms) / E
+    sel_runs = E // C
+    sel_mean_ms = rest_ms / sel_runs  # statistics refresh + scoring + top-K of one selector run
+
+    # algorithmic bytes of every decode launch of an episode (needs the selections: one eager episode)
+    bytes_per_launch, pages_per_launch = [], []
+    sess.restart()
+    for t in range(E):
+        sess.step(inp.q[t], len_table[t + 1, :B], len_table[t, :B])
+        nbytes, npages = decode_bytes_per_launch(w, len_table[t + 1, :B].cpu(), sess.sel_count.cpu(),
+                                                 sess.sel_seq_len.cpu())
+        bytes_per_launch.append(nbytes)
+        pages_per_launch.append(npages)
     mean = lambda xs: sum(xs) / max(1, len(xs))  # noqa: E731
-    dec_mean_ms = mean(dec_ms)
     alg_bytes = mean(bytes_per_launch)
     achieved = alg_bytes / (dec_mean_ms * 1e-3) / 1e9
     traffic = read_traffic(w.name)
@@ -206,8 +221,6 @@ def main():
     for b in range(B):
         P = -(-int(inp.prompt_lens[b]) // w.page_size)
         stats_bytes_run += P * n_sel * (w.page_size // w.logical_page_size) * 2 * w.head_dim * 2
-    sel_mean_ms = mean(sel_ms)
-
     result = {
         "metric": "sparse decode tokens/s at 32K context (decode + amortised page selection + stats update)",
         "value": tokens_per_s,
@@ -231,7 +244,7 @@ def main():
         },
         "roofline": {
             "bound": "hbm",
-            "kernel": "sparse_decode_kernel (+ decode_merge_kernel)",
+            "kernel": "sparse_decode_kernel + decode_merge_kernel (one lserve_sparse_decode call)",
             "achieved": achieved,
             "peak": HBM_PEAK_GBS,
             "unit": "GB/s",
@@ -240,17 +253,22 @@ def main():
             "algorithmic_bytes_per_launch": alg_bytes,
             "pages_per_launch": mean(pages_per_launch),
             "launch_ms": dec_mean_ms,
-            "launch_ms_min": min(dec_ms),
+            "episode_ms": full_ms,
+            "episode_without_decode_ms": rest_ms,
         },
         "selector": {
             "ms_per_run": sel_mean_ms,
+            "kernels": "page_stats_kernel (tail refresh) + page_score_kernel + topk_pages_kernel",
             "stats_bytes_per_run": stats_bytes_run,
             "achieved_GBs": stats_bytes_run / (sel_mean_ms * 1e-3) / 1e9 if sel_mean_ms else None,
             "frac_of_hbm_peak": stats_bytes_run / (sel_mean_ms * 1e-3) / 1e9 / HBM_PEAK_GBS if sel_mean_ms else None,
         },
-        "stats_tail_update": {"ms_per_call": mean(st_ms)},
-        "whole_path_GBs": (mean(bytes_per_launch) * E + stats_bytes_run * (E // C)) / E
-        / (elapsed / args.steps) / 1e9,
+        "whole_path": {
+            "algorithmic_bytes_per_step": (mean(bytes_per_launch) * E + stats_bytes_run * (E // C)) / E,
+            "achieved_GBs": (mean(bytes_per_launch) * E + stats_bytes_run * (E // C)) / E / (elapsed / args.steps) / 1e9,
+            "frac_of_hbm_peak": (mean(bytes_per_launch) * E + stats_bytes_run * (E // C)) / E / (elapsed / args.steps) / 1e9
+            / HBM_PEAK_GBS,
+        },
     }
 
     if not args.no_cpu_baseline:

@@ -77,7 +77,8 @@ class DecodeSession:
                                self.out, self.lse, self.ws_decode)
         return self.out
 
-    def step(self, q: torch.Tensor, seq_lens: torch.Tensor, prev_seq_lens: torch.Tensor) -> torch.Tensor:
+    def step(self, q: torch.Tensor, seq_lens: torch.Tensor, prev_seq_lens: torch.Tensor,
+             run_decode: bool = True) -> torch.Tensor:
         """One decode step.
 
         The new token's K/V are already in the pool; `seq_lens` counts it and `prev_seq_lens` is the
@@ -93,7 +94,7 @@ class DecodeSession:
             self._stats_from, self._stats_tokens = seq_lens, 0
             self.select(q)
         self.steps_since_selection += 1
-        return self.decode(q)
+        return self.decode(q) if run_decode else self.out  # run_decode=False: selector side only (timing)
 
     def restart(self) -> None:
         """Forget the selection and the pending statistics range (start of a new episode)."""
