@@ -48,6 +48,7 @@ def parse_args():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-prefill", action="store_true")
     ap.add_argument("--prefill-tokens", type=int, default=65536)
+    ap.add_argument("--no-append", action="store_true", help="skip the KV write-back timing")
     ap.add_argument("--profile-only", default="", choices=["", "decode", "select", "prefill", "stats"],
                     help="run only a short loop of one entry point (for rocprofv3)")
     return ap.parse_args()
@@ -278,6 +279,11 @@ def main():
             result["prefill"] = bench_prefill(torch, L, dev, args.prefill_tokens)
         except Exception as e:  # the decode line must still be printed
             result["prefill"] = {"error": repr(e)}
+    if not args.no_append:
+        try:
+            result["append"] = bench_append(torch, L, dev, args.prefill_tokens, w)
+        except Exception as e:
+            result["append"] = {"error": repr(e)}
     print(json.dumps(result))
 
 
@@ -358,6 +364,69 @@ def bench_prefill(torch, L, dev, n_tokens):
         "dense_equivalent_TFLOPs": flops_equiv / (ms * 1e-3) / 1e12,
         "roofline": {"bound": "mfma", "achieved": tf, "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
                      "frac": tf / MFMA_BF16_PEAK_TFLOPS, "traffic": None},
+    }
+
+
+def bench_append(torch, L, dev, n_tokens, w_dec):
+    """KV write-back with fused statistics: a whole prefill of cfg3's shape into fresh pages, and the
+    one-token-per-sequence append of the decode workload (launch-latency bound)."""
+    from workloads import get_config
+
+    w = get_config("cfg3", prefill_tokens=n_tokens)
+    Hkv, D, NP, g = w.num_kv_heads, w.head_dim, w.page_size, w.page_size // w.logical_page_size
+    dt = w.torch_dtype
+    desc = L.AttnDesc(w.num_q_heads, Hkv, w.streaming_flags(), dtype=dt, page_size=NP,
+                      logical_page_size=w.logical_page_size, sink_tokens=w.sink_tokens, local_tokens=w.local_tokens)
+    pages = -(-n_tokens // NP)
+    gen = torch.Generator(device=dev).manual_seed(7)
+    k_new = torch.randn((n_tokens, Hkv, D), generator=gen, device=dev, dtype=torch.float32).to(dt)
+    v_new = torch.randn((n_tokens, Hkv, D), generator=gen, device=dev, dtype=torch.float32).to(dt)
+    k_pool = torch.empty((pages, Hkv, NP, D), dtype=dt, device=dev)
+    v_pool = torch.empty_like(k_pool)
+    stats = torch.empty((pages, Hkv, g, 2, D), dtype=dt, device=dev)
+    table = torch.randperm(pages, generator=gen, device=dev).to(torch.int32).reshape(1, pages)
+    seq = torch.tensor([n_tokens], dtype=torch.int32, device=dev)
+    kv = L.PagedKV(k_pool, v_pool, stats, table, seq)
+    cu = torch.tensor([0, n_tokens, 0, 0], dtype=torch.int32, device=dev)
+    zero = torch.zeros((4,), dtype=torch.int32, device=dev)
+
+    def timed(call, reps):
+        call()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(reps):
+            call()
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / reps
+
+    ms = timed(lambda: L.lserve_append_kv(desc, kv, k_new, v_new, cu, zero, n_tokens), 5)
+    n_sel = sum(1 for f in w.streaming_flags() if not f)
+    moved = 2 * 2 * n_tokens * Hkv * D * 2 + pages * n_sel * g * 2 * D * 2  # K and V read + written, statistics written
+    # the decode workload's per-step append: one token per sequence into its tail page
+    B = w_dec.batch
+    desc2 = L.AttnDesc(w_dec.num_q_heads, w_dec.num_kv_heads, w_dec.streaming_flags(), dtype=w_dec.torch_dtype,
+                       page_size=w_dec.page_size, logical_page_size=w_dec.logical_page_size,
+                       sink_tokens=w_dec.sink_tokens, local_tokens=w_dec.local_tokens)
+    ctx = 1024
+    pg = ctx // w_dec.page_size + 1
+    k2 = torch.zeros((B * pg, w_dec.num_kv_heads, w_dec.page_size, D), dtype=w_dec.torch_dtype, device=dev)
+    v2 = torch.zeros_like(k2)
+    st2 = torch.zeros((B * pg, w_dec.num_kv_heads, w_dec.page_size // w_dec.logical_page_size, 2, D),
+                      dtype=w_dec.torch_dtype, device=dev)
+    t2 = torch.arange(B * pg, dtype=torch.int32, device=dev).reshape(B, pg)
+    kv2 = L.PagedKV(k2, v2, st2, t2, torch.full((B + 4,), ctx + 1, dtype=torch.int32, device=dev)[:B])
+    kn2 = torch.randn((B + 1, w_dec.num_kv_heads, D), generator=gen, device=dev, dtype=torch.float32).to(w_dec.torch_dtype)
+    cu2 = torch.arange(B + 4, dtype=torch.int32, device=dev)
+    sp2 = torch.full((B + 4,), ctx + 5, dtype=torch.int32, device=dev)
+    us = timed(lambda: L.lserve_append_kv(desc2, kv2, kn2, kn2, cu2, sp2, 1), 200) * 1e3
+    return {
+        "prefill_writeback": {"workload": f"cfg3: {n_tokens} tokens x {Hkv} KV heads into {pages} scattered pages, bf16",
+                              "ms": ms, "algorithmic_bytes": moved, "achieved_GBs": moved / (ms * 1e-3) / 1e9,
+                              "frac_of_hbm_peak": moved / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS},
+        "decode_append_us_per_call": us,
+        "note": "not part of `value`: the decode benchmark reads a pre-written cache",
     }
 
 

@@ -8,6 +8,8 @@
  *   lserve_select_pages      query-centric page scores (Eq. 2), max over logical pages,
  *                            top-K physical pages under a token budget (Sec. 3.5.2)
  *   lserve_sparse_decode     paged decode attention over an index table (Sec. 3.6)
+ * and, around them, lserve_append_kv: write-back of new K/V into the pages with the statistics
+ * updated in the same pass (Sec. 3.2, Sec. 3.5.2).
  *
  * Conventions common to every call
  *   - "device" pointers are HIP device memory owned by the caller; "host" pointers are ordinary
@@ -107,6 +109,30 @@ typedef struct lserve_paged_kv {
  */
 int lserve_build_page_stats(const lserve_attn_desc *desc, const lserve_paged_kv *kv,
                             const int32_t *start_pos, int32_t max_tail_pages, void *stream);
+
+/*
+ * KV write-back with fused statistics (Sec. 3.2: prefill writes K/V back into the paged cache; Sec. 3.5.2
+ * and the caption of the hierarchical-paging figure: the statistics are computed during the context
+ * stage and the previous decoding steps).  Appends n_b = cu_new[b+1] - cu_new[b] tokens to every
+ * sequence: new token j of sequence b is stored at position start_pos[b] + j, i.e. slot
+ * (start_pos[b] + j) % N_P of physical page page_table[b][(start_pos[b] + j) / N_P], for every KV head,
+ * in both pools.  For non-streaming KV heads the max / min rows of every logical page that received a
+ * token are brought up to date without re-reading old keys: a logical page that already held tokens
+ * (positions below start_pos[b]) combines its stored statistics with the new keys, which requires
+ * kv->stats to be current for positions below start_pos[b]; a logical page whose first token is new
+ * is computed from the new keys alone.  kv->seq_lens must be a valid pointer as in every call but is
+ * neither read nor written (the caller bumps the lengths).  kv->stats may be NULL when every KV head is
+ * streaming.
+ *
+ *   k_new, v_new   device [total_new][Hkv][D], tokens of all sequences concatenated
+ *   cu_new         device [batch + 1], cu_new[0] = 0
+ *   start_pos      device [batch]; start_pos[b] + n_b <= max_pages_per_seq * N_P
+ *   max_new_per_seq  host upper bound of n_b (sizes the launch); > 0
+ * Reads page_table, k_new, v_new, stats; writes k_pool, v_pool, stats.  No workspace.
+ */
+int lserve_append_kv(const lserve_attn_desc *desc, const lserve_paged_kv *kv, const void *k_new,
+                     const void *v_new, const int32_t *cu_new, const int32_t *start_pos,
+                     int32_t max_new_per_seq, void *stream);
 
 /*
  * Page selection (Eq. 2 and the paragraph after it; Sec. 3.2 "shorter page tables").

@@ -7,6 +7,7 @@ from .reference import (  # noqa: F401
     build_oracle,
     widen,
     num_threads,
+    append_kv,
     page_stats,
     page_scores,
     select_pages,

@@ -18,6 +18,9 @@
  *                                      K highest pages under the token budget)
  *   - decode over an index table     : Sec. 3.6 (selected pages for dense heads, sink + local
  *                                      pages for streaming heads), Sec. 3.2 ("shorter page table")
+ *   - KV write-back                  : Sec. 3.2 / Sec. 2.1 (new tokens stored at their slots of the
+ *                                      paged cache; statistics afterwards = the definition above
+ *                                      evaluated at the new lengths)
  *
  * Readings taken where the paper is silent (the same ones bind the GPU path):
  *   - the streaming mask is tile granular: s = ceil(sink / T) sink tiles and w = ceil(local / T)
@@ -122,6 +125,35 @@ void oracle_page_stats(const uint16_t *k_pool, const int32_t *page_table, const 
                     size_t base = ((((size_t)page * Hkv + hk) * g + j) * 2) * D;
                     stats[base + c] = bmax;
                     stats[base + D + c] = bmin;
+                }
+            }
+        }
+    }
+}
+
+/* ---- KV write-back (Sec. 3.2; Sec. 2.1 "Paged Attention") -------------------------------- */
+/*
+ * Append n_b = cu_new[b+1] - cu_new[b] tokens to sequence b: new token j takes position
+ * start_pos[b] + j, which is slot (position % NP) of physical page page_table[b][position / NP],
+ * for every KV head, in both pools.  k_new / v_new are [total_new][Hkv][D].  Bit patterns are moved
+ * unchanged.  Statistics are not touched here: the definition of the statistics after an append
+ * is oracle_page_stats at the new lengths.
+ */
+void oracle_append_kv(const uint16_t *k_new, const uint16_t *v_new, const int32_t *cu_new,
+                      const int32_t *start_pos, const int32_t *page_table, int batch, int max_pages,
+                      int Hkv, int D, int NP, uint16_t *k_pool, uint16_t *v_pool)
+{
+    for (int b = 0; b < batch; ++b) {
+        int n = cu_new[b + 1] - cu_new[b];
+        for (int j = 0; j < n; ++j) {
+            int pos = start_pos[b] + j;
+            int page = page_table[(size_t)b * max_pages + pos / NP];
+            for (int hk = 0; hk < Hkv; ++hk) {
+                for (int c = 0; c < D; ++c) {
+                    size_t src = (((size_t)(cu_new[b] + j)) * Hkv + hk) * D + c;
+                    size_t dst = pool_index(page, hk, pos % NP, c, Hkv, NP, D);
+                    k_pool[dst] = k_new[src];
+                    v_pool[dst] = v_new[src];
                 }
             }
         }

@@ -102,6 +102,19 @@ def page_stats(k_pool: torch.Tensor, page_table, seq_lens, logical_page_size: in
     return stats
 
 
+def append_kv(k_new: torch.Tensor, v_new: torch.Tensor, cu_new, start_pos, page_table,
+              k_pool: torch.Tensor, v_pool: torch.Tensor) -> None:
+    """Write new tokens ([total_new, Hkv, D]) into the paged pools in place at positions start_pos[b] + j."""
+    num_pages, Hkv, NP, D = k_pool.shape
+    assert k_pool.is_contiguous() and v_pool.is_contiguous()
+    pt, cu, sp = _i32(page_table), _i32(cu_new), _i32(start_pos)
+    kn, vn, kb, vb = _bits(k_new), _bits(v_new), _bits(k_pool), _bits(v_pool)
+    assert kb.ctypes.data == k_pool.data_ptr() and vb.ctypes.data == v_pool.data_ptr()
+    _load().oracle_append_kv(_p(kn), _p(vn), _p(cu), _p(sp), _p(pt), ctypes.c_int(pt.shape[0]),
+                             ctypes.c_int(pt.shape[1]), ctypes.c_int(Hkv), ctypes.c_int(D),
+                             ctypes.c_int(NP), _p(kb), _p(vb))
+
+
 def page_scores(q: torch.Tensor, stats: torch.Tensor, page_table, seq_lens, page_size: int,
                 want_logical: bool = False) -> Tuple[np.ndarray, Optional[np.ndarray]]:
     """Physical-page scores [B, Hkv, max_pages] (and per-head logical scores [B, H, max_pages, g])."""

@@ -15,6 +15,7 @@ from .binding import (  # noqa: F401
     PagedKV,
     library_path,
     load_library,
+    lserve_append_kv,
     lserve_build_page_stats,
     lserve_last_hip_error,
     lserve_select_pages,

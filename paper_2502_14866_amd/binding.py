@@ -23,6 +23,7 @@ EXPORTED_SYMBOLS = (
     "lserve_select_pages",
     "lserve_sparse_prefill",
     "lserve_sparse_decode",
+    "lserve_append_kv",
     "lserve_workspace_bytes",
     "lserve_strerror",
     "lserve_last_hip_error",
@@ -72,6 +73,8 @@ def load_library():
         lib.lserve_select_pages.argtypes = [dp, kp, vp, i32, vp, vp, vp, vp, vp, sz, vp]
         lib.lserve_sparse_prefill.argtypes = [dp, vp, vp, vp, vp, i32, i32, i32, vp, vp, vp, sz, vp]
         lib.lserve_sparse_decode.argtypes = [dp, kp, vp, vp, vp, vp, i32, vp, vp, vp, sz, vp]
+        lib.lserve_append_kv.argtypes = [dp, kp, vp, vp, vp, vp, i32, vp]
+        lib.lserve_append_kv.restype = ctypes.c_int
         lib.lserve_workspace_bytes.argtypes = [ctypes.c_int, dp, i32, i32, i32, i32]
         lib.lserve_workspace_bytes.restype = sz
         lib.lserve_strerror.argtypes = [ctypes.c_int]
@@ -166,6 +169,12 @@ def lserve_build_page_stats(desc: AttnDesc, kv: PagedKV, start_pos: Optional[tor
                             max_tail_pages: int = 0, stream=None) -> None:
     _check(load_library().lserve_build_page_stats(desc.c(), kv.c(), _ptr(start_pos), max_tail_pages,
                                                   _stream(stream)), "lserve_build_page_stats")
+
+
+def lserve_append_kv(desc: AttnDesc, kv: PagedKV, k_new: torch.Tensor, v_new: torch.Tensor, cu_new: torch.Tensor,
+                     start_pos: torch.Tensor, max_new_per_seq: int, stream=None) -> None:
+    _check(load_library().lserve_append_kv(desc.c(), kv.c(), _ptr(k_new), _ptr(v_new), _ptr(cu_new), _ptr(start_pos),
+                                           max_new_per_seq, _stream(stream)), "lserve_append_kv")
 
 
 def lserve_select_pages(desc: AttnDesc, kv: PagedKV, q: torch.Tensor, budget_tokens: int,

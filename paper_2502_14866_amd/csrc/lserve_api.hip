@@ -100,6 +100,21 @@ int lserve_build_page_stats(const lserve_attn_desc* desc, const lserve_paged_kv*
     return e == hipSuccess ? LSERVE_OK : fail_hip(e);
 }
 
+int lserve_append_kv(const lserve_attn_desc* desc, const lserve_paged_kv* kv, const void* k_new, const void* v_new,
+                     const int32_t* cu_new, const int32_t* start_pos, int32_t max_new_per_seq, void* stream) {
+    LayerParams lp;
+    PagedParams pp;
+    int rc = make_layer(desc, &lp);
+    if (rc) return rc;
+    rc = make_paged(kv, true, true, selecting_heads(lp).count > 0, &pp);
+    if (rc) return rc;
+    if (!k_new || !v_new || !cu_new || !start_pos || max_new_per_seq <= 0) return LSERVE_ERR_INVALID_ARG;
+    if (!aligned16(k_new) || !aligned16(v_new) || !aligned16(cu_new) || !aligned16(start_pos)) return LSERVE_ERR_INVALID_ARG;
+    hipError_t e = launch_append_kv(desc->dtype, lp, pp, k_new, v_new, cu_new, start_pos, max_new_per_seq,
+                                    (hipStream_t)stream);
+    return e == hipSuccess ? LSERVE_OK : fail_hip(e);
+}
+
 int lserve_select_pages(const lserve_attn_desc* desc, const lserve_paged_kv* kv, const void* q, int32_t budget_tokens,
                         int32_t* sel_pages, int32_t* sel_count, int32_t* sel_seq_len, float* scores_out,
                         void* workspace, size_t workspace_bytes, void* stream) {

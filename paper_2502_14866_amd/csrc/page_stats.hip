@@ -60,6 +60,95 @@ __global__ __launch_bounds__(kWave* kMaxLogical) void page_stats_kernel(LayerPar
     }
 }
 
+// KV write-back with the statistics updated in the same pass (Sec. 3.2, Sec. 3.5.2): one workgroup per
+// (physical page touched by the new tokens, KV head, sequence), one wavefront per logical page.  New
+// rows are copied into both pools with 16-byte accesses; for non-streaming heads the wave folds the
+// new keys into max / min rows and, when the logical page already held tokens, combines them with the
+// stored rows instead of re-reading the old keys.
+template <class T>
+__global__ __launch_bounds__(kWave* kMaxLogical) void append_kv_kernel(LayerParams lp, PagedParams kv,
+                                                                        const uint4* __restrict__ k_new,
+                                                                        const uint4* __restrict__ v_new,
+                                                                        const int* __restrict__ cu_new,
+                                                                        const int* __restrict__ start_pos) {
+    const int b = blockIdx.z, hk = blockIdx.y;
+    const int j = threadIdx.x / kWave, lane = threadIdx.x % kWave;
+    const int r = lane / 16, c = lane % 16;
+    const int s = start_pos[b], src0 = cu_new[b];
+    const int e = s + (cu_new[b + 1] - src0);  // new tokens occupy positions [s, e)
+    const int p = s / lp.NP + (int)blockIdx.x;
+    const int lo = p * lp.NP + j * lp.NL, hi = lo + lp.NL;  // this wave's logical page
+    const int t0 = max(lo, s), t1 = min(hi, e);
+    if (t0 >= t1) return;
+    const bool streaming = (lp.streaming_mask >> hk) & 1ull;
+    const int phys = kv.page_table[(size_t)b * kv.max_pages + p];
+    const size_t slab = ((size_t)phys * lp.Hkv + hk) * lp.NP * (kHeadDim / 8);
+    uint4* kdst = reinterpret_cast<uint4*>(const_cast<void*>(kv.k_pool)) + slab;
+    uint4* vdst = reinterpret_cast<uint4*>(const_cast<void*>(kv.v_pool)) + slab;
+
+    float vmax[8], vmin[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+        vmax[i] = -INFINITY;
+        vmin[i] = INFINITY;
+    }
+    for (int t = t0 + r; t < t1; t += 4) {
+        const size_t src = ((size_t)(src0 + t - s) * lp.Hkv + hk) * (kHeadDim / 8) + c;
+        const uint4 x = k_new[src];
+        const uint4 y = v_new[src];
+        const size_t dst = (size_t)(t - p * lp.NP) * (kHeadDim / 8) + c;
+        kdst[dst] = x;
+        vdst[dst] = y;
+        const uint32_t w[4] = {x.x, x.y, x.z, x.w};
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const float a = Elem<T>::lo(w[i]), bb = Elem<T>::hi(w[i]);
+            vmax[2 * i] = fmaxf(vmax[2 * i], a);
+            vmin[2 * i] = fminf(vmin[2 * i], a);
+            vmax[2 * i + 1] = fmaxf(vmax[2 * i + 1], bb);
+            vmin[2 * i + 1] = fminf(vmin[2 * i + 1], bb);
+        }
+    }
+    if (streaming) return;  // streaming heads are never scored
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+        vmax[i] = rows4_max(vmax[i]);
+        vmin[i] = rows4_min(vmin[i]);
+    }
+    if (r == 0) {
+        uint4* st = reinterpret_cast<uint4*>(kv.stats) + ((((size_t)phys * lp.Hkv + hk) * lp.g + j) * 2) * (kHeadDim / 8);
+        if (lo < s) {  // the logical page already held tokens: fold the stored rows in
+            const uint4 om = st[c], on = st[kHeadDim / 8 + c];
+            const uint32_t wm[4] = {om.x, om.y, om.z, om.w}, wn[4] = {on.x, on.y, on.z, on.w};
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                vmax[2 * i] = fmaxf(vmax[2 * i], Elem<T>::lo(wm[i]));
+                vmax[2 * i + 1] = fmaxf(vmax[2 * i + 1], Elem<T>::hi(wm[i]));
+                vmin[2 * i] = fminf(vmin[2 * i], Elem<T>::lo(wn[i]));
+                vmin[2 * i + 1] = fminf(vmin[2 * i + 1], Elem<T>::hi(wn[i]));
+            }
+        }
+        st[c] = make_uint4(Elem<T>::pack(vmax[0], vmax[1]), Elem<T>::pack(vmax[2], vmax[3]),
+                           Elem<T>::pack(vmax[4], vmax[5]), Elem<T>::pack(vmax[6], vmax[7]));
+        st[kHeadDim / 8 + c] = make_uint4(Elem<T>::pack(vmin[0], vmin[1]), Elem<T>::pack(vmin[2], vmin[3]),
+                                          Elem<T>::pack(vmin[4], vmin[5]), Elem<T>::pack(vmin[6], vmin[7]));
+    }
+}
+
+hipError_t launch_append_kv(int dtype, const LayerParams& lp, const PagedParams& kv, const void* k_new, const void* v_new,
+                            const int* cu_new, const int* start_pos, int max_new_per_seq, hipStream_t stream) {
+    // the new tokens of a sequence touch at most ceil(n / N_P) + 1 physical pages
+    dim3 grid((max_new_per_seq + lp.NP - 1) / lp.NP + 1, lp.Hkv, kv.batch);
+    dim3 block(kWave * lp.g);
+    const uint4* k4 = reinterpret_cast<const uint4*>(k_new);
+    const uint4* v4 = reinterpret_cast<const uint4*>(v_new);
+    if (dtype == 0)
+        hipLaunchKernelGGL(append_kv_kernel<F16>, grid, block, 0, stream, lp, kv, k4, v4, cu_new, start_pos);
+    else
+        hipLaunchKernelGGL(append_kv_kernel<BF16>, grid, block, 0, stream, lp, kv, k4, v4, cu_new, start_pos);
+    return hipGetLastError();
+}
+
 hipError_t launch_page_stats(int dtype, const LayerParams& lp, const PagedParams& kv, const int* start_pos,
                              int tail_pages, const HeadList& heads, hipStream_t stream) {
     if (heads.count == 0) return hipSuccess;

@@ -90,6 +90,13 @@ def test_invalid_arguments_are_rejected_on_the_host(L):
     assert _rc(lambda: L.lserve_build_page_stats(desc(), kv, None, -1, stream)) == -1
     nostats = L.PagedKV(kv.k_pool, kv.v_pool, None, kv.page_table, kv.seq_lens)
     assert _rc(lambda: L.lserve_build_page_stats(desc(), nostats, None, 0, stream)) == -1
+    # append: non-positive launch bound, missing statistics with a selecting head, missing source
+    kn = torch.zeros((4, 2, 128), dtype=torch.float16)
+    cu4 = torch.zeros((4,), dtype=torch.int32)
+    assert _rc(lambda: L.lserve_append_kv(desc(), kv, kn, kn, cu4, cu4, 0, stream)) == -1
+    assert _rc(lambda: L.lserve_append_kv(desc(), nostats, kn, kn, cu4, cu4, 1, stream)) == -1
+    assert _rc(lambda: L.lserve_append_kv(desc(), kv, None, kn, cu4, cu4, 1, stream)) == -1
+    assert _rc(lambda: L.lserve_append_kv(desc(head_dim=64), kv, kn, kn, cu4, cu4, 1, stream)) == -2
     # selection: budget below one page, missing outputs, workspace too small
     assert _rc(lambda: L.lserve_select_pages(desc(), kv, q, 32, sel, cnt, ssl, None, ws, stream)) == -1
     assert _rc(lambda: L.lserve_select_pages(desc(), kv, q, 256, sel, cnt, ssl, None, None, stream)) == -3

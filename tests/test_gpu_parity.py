@@ -321,3 +321,121 @@ def test_session_step_loop_with_lazy_statistics_matches_oracle():
                                       sess.sel_pages.cpu().numpy(), sess.sel_count.cpu().numpy(),
                                       sess.sel_seq_len.cpu().numpy(), flags, w.sink_tokens, w.local_tokens)
         assert_attention_close(out, ref, f"session step {t}")
+
+
+# ---- KV write-back with fused statistics (Sec. 3.2, Sec. 3.5.2) ---------------------------------
+
+def _append_case(L, w, dev, start, n_new, seed, k_pool, v_pool, stats, page_table):
+    """One lserve_append_kv call next to the oracle's write-back; returns the oracle's pools."""
+    g = torch.Generator().manual_seed(seed)
+    total = int(sum(n_new))
+    dt = k_pool.dtype
+    k_new = torch.randn((max(total, 1), w.num_kv_heads, 128), generator=g).to(dt)[:total]
+    v_new = torch.randn((max(total, 1), w.num_kv_heads, 128), generator=g).to(dt)[:total]
+    cu = np.concatenate([[0], np.cumsum(n_new)]).astype(np.int32)
+    desc = L.AttnDesc(num_q_heads=w.num_q_heads, num_kv_heads=w.num_kv_heads, streaming_flags=w.streaming_flags(),
+                      head_dim=128, page_size=w.page_size, logical_page_size=w.logical_page_size, dtype=dt,
+                      sink_tokens=w.sink_tokens, local_tokens=w.local_tokens)
+    seq = torch.tensor([s + n for s, n in zip(start, n_new)], dtype=torch.int32, device=dev)
+    kv = L.PagedKV(k_pool, v_pool, stats, page_table, seq)
+    pad = torch.zeros((1, w.num_kv_heads, 128), dtype=dt)
+    L.lserve_append_kv(desc, kv, torch.cat([k_new, pad]).to(dev), torch.cat([v_new, pad]).to(dev),
+                       torch.from_numpy(cu).to(dev), torch.tensor(start, dtype=torch.int32, device=dev),
+                       max(max(n_new), 1))
+    torch.cuda.synchronize()
+    return k_new, v_new, cu
+
+
+@pytest.mark.parametrize("name,kw", [
+    ("gqa_fp16", dict()),
+    ("bf16_page32", dict(dtype="bf16", page_size=32, logical_page_size=8, sink_tokens=32, local_tokens=64,
+                         budget_tokens=128)),
+    ("page128_g8", dict(page_size=128, logical_page_size=16, sink_tokens=128, local_tokens=256, budget_tokens=512)),
+    ("flat16", dict(page_size=16, logical_page_size=16, sink_tokens=16, local_tokens=64, budget_tokens=128)),
+])
+def test_append_writes_pools_bit_exact_and_keeps_statistics_equal_to_a_rebuild(name, kw):
+    L = _lib()
+    dev = torch.device("cuda:0")
+    w = small_decode_workload(batch=3, lengths=(1, 1, 1), **kw)
+    NP = w.page_size
+    max_pages = 12
+    g = torch.Generator().manual_seed(5)
+    page_table = torch.randperm(3 * max_pages, generator=g).to(torch.int32).reshape(3, max_pages)
+    dt = torch.float16 if w.dtype == "fp16" else torch.bfloat16
+    num_pages = 3 * max_pages
+    k_ref = torch.randn((num_pages, w.num_kv_heads, NP, 128), generator=g).to(dt)  # stale contents, as in a reused pool
+    v_ref = torch.randn((num_pages, w.num_kv_heads, NP, 128), generator=g).to(dt)
+    k_dev, v_dev = k_ref.to(dev), v_ref.to(dev)
+    gl = NP // w.logical_page_size
+    stats = torch.full((num_pages, w.num_kv_heads, gl, 2, 128), float("nan"), dtype=dt, device=dev)
+    pt_dev = page_table.to(dev)
+    # a chunked prefill, single-token decode appends, a ragged multi-token append and an empty one
+    rounds = [(3 * NP + 5, NP - 1, 1), (1, 1, 1), (1, 1, 0), (2 * NP, 7, 3), (0, 1, NP + 1), (1, 0, 0)]
+    start = [0, 0, 0]
+    heads = [h for h in range(w.num_kv_heads) if h not in w.streaming_kv_heads]
+    for it, n_new in enumerate(rounds):
+        k_new, v_new, cu = _append_case(L, w, dev, start, list(n_new), 100 + it, k_dev, v_dev, stats, pt_dev)
+        oracle.append_kv(k_new, v_new, cu, np.asarray(start, np.int32), page_table, k_ref, v_ref)
+        start = [s + n for s, n in zip(start, n_new)]
+        assert torch.equal(k_dev.cpu().view(torch.int16), k_ref.view(torch.int16)), (name, it)
+        assert torch.equal(v_dev.cpu().view(torch.int16), v_ref.view(torch.int16)), (name, it)
+        seq = np.asarray(start, np.int32)
+        live = [b for b in range(3) if seq[b] > 0]
+        ref = oracle.page_stats(k_ref, page_table[live], seq[live], w.logical_page_size)
+        got = stats.cpu()
+        for b in live:
+            for lpage in range(-(-int(seq[b]) // w.logical_page_size)):
+                t0 = lpage * w.logical_page_size
+                phys, j = int(page_table[b, t0 // NP]), (t0 % NP) // w.logical_page_size
+                for hk in heads:
+                    assert torch.equal(got[phys, hk, j].float(), ref[phys, hk, j].float()), (name, it, b, lpage, hk)
+
+
+def test_append_then_select_and_decode_match_the_oracle_without_a_statistics_pass():
+    """Prefill write-back and per-step appends keep the statistics current, so the selector runs with no
+    lserve_build_page_stats call at all."""
+    L = _lib()
+    dev = torch.device("cuda:0")
+    w = small_decode_workload(lengths=(700, 1300), decode_steps=6, budget_tokens=512, reuse_interval=2)
+    inp = make_decode_inputs(w)
+    sess = _session(L, w, inp, dev)
+    # the generator's pools hold every token already; fill the device pools through the entry point instead
+    sess.kv.k_pool.zero_()
+    sess.kv.v_pool.zero_()
+    sess.stats.fill_(float("nan"))
+    NP = w.page_size
+    flags = w.streaming_flags()
+
+    def append(start, n_new):
+        ks, vs = [], []
+        for b in range(w.batch):
+            pos = torch.arange(start[b], start[b] + n_new[b])
+            phys = inp.page_table[b].long()[pos // NP]
+            ks.append(inp.k_pool[phys, :, pos % NP])
+            vs.append(inp.v_pool[phys, :, pos % NP])
+        cu = np.concatenate([[0], np.cumsum(n_new)]).astype(np.int32)
+        L.lserve_append_kv(sess.desc, sess.kv, torch.cat(ks).contiguous().to(dev), torch.cat(vs).contiguous().to(dev),
+                           torch.from_numpy(cu).to(dev), torch.tensor(start, dtype=torch.int32, device=dev),
+                           max(n_new))
+
+    have = [0] * w.batch
+    for step in range(w.decode_steps):
+        seq_cpu = inp.seq_lens_at(step)
+        want = [int(x) for x in seq_cpu]
+        append(have, [a - h for a, h in zip(want, have)])  # the prompt in one call, then one token per step
+        have = want
+        sess.set_seq_lens(seq_cpu.to(dev))
+        q = inp.q[step].to(dev)
+        stats_ref = _check_stats(w, inp, sess, seq_cpu)
+        if step % w.reuse_interval == 0:
+            sess.select(q)
+            scores_ref, _ = oracle.page_scores(inp.q[step], stats_ref, inp.page_table, seq_cpu, w.page_size)
+            sel_ref, cnt_ref, ssl_ref = oracle.select_pages(scores_ref, seq_cpu, w.page_size, w.budget_tokens)
+            assert compare_selection(sess.sel_pages.cpu().numpy(), sess.sel_count.cpu().numpy(), sel_ref, cnt_ref,
+                                     scores_ref, flags) <= 1
+        out = sess.decode(q)
+        ref, lse_ref = oracle.sparse_decode(inp.q[step], inp.k_pool, inp.v_pool, inp.page_table, seq_cpu,
+                                            sess.sel_pages.cpu().numpy(), sess.sel_count.cpu().numpy(),
+                                            sess.sel_seq_len.cpu().numpy(), flags, w.sink_tokens, w.local_tokens)
+        assert_attention_close(out, ref, f"append step {step}")
+        assert_lse_close(sess.lse, lse_ref, f"append step {step}")
