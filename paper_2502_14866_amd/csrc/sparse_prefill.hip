@@ -28,10 +28,32 @@ typedef float float16_t __attribute__((ext_vector_type(16)));
 constexpr int kTile = 64;              // mask tile = key tile = page
 constexpr int kPrefillThreads = 512;   // 8 waves: two per SIMD, each owning 32 query rows
 constexpr int kRowsPerBlock = 256;     // 4 mask tiles of queries
-constexpr int kKRowBytes = 256 + 16;   // K tile row (128 x 16 bit) padded against LDS bank conflicts
-constexpr int kVRowBytes = 128 + 16;   // V^T tile row (64 keys x 16 bit) padded
+constexpr int kKRowBytes = 256;        // K tile row: 128 x 16 bit = 16 chunks of 16 B
+constexpr int kVRowBytes = 128;        // V^T tile row: 64 keys x 16 bit = 8 chunks of 16 B
 constexpr int kKTileBytes = kTile * kKRowBytes;
 constexpr int kVTileBytes = kHeadDim * kVRowBytes;
+
+// Tiles reach LDS through direct-to-LDS loads, which place the 64 lanes of an instruction at 64
+// consecutive 16-byte slots, so rows cannot be padded.  Bank conflicts are avoided by permuting the
+// chunks inside a row instead: chunk c of K row r sits at position c ^ (r % 16), chunk c of V^T row d
+// at position c ^ ((d / 2) % 8).  Sixteen consecutive rows then hit sixteen different 16-byte bank
+// groups for any fixed c, which is what the matrix-operand reads (one row per lane) need.
+// The load itself is written in assembly: left to the compiler it is treated as an access that may
+// touch both memory and LDS, and while one is in flight every LDS operand read in the loop waits with
+// lgkmcnt(0), exposing the LDS latency in front of the products.  `lds_base` is the wave-uniform LDS
+// byte address of the 1 KiB destination; lane l lands at lds_base + 16 l.  Completion is tracked by
+// vmcnt only, which dma_wait() drains before the workgroup barrier.
+__device__ __forceinline__ void dma_load16(const void* src, unsigned lds_base) {
+    const unsigned base = __builtin_amdgcn_readfirstlane(lds_base);
+    asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" ::"v"(src), "s"(base) : "memory");
+}
+__device__ __forceinline__ void dma_wait() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
+__device__ __forceinline__ unsigned lds_address(const void* p) {
+    return (unsigned)(size_t)(const __attribute__((address_space(3))) void*)p;
+}
+
+__device__ __forceinline__ int k_chunk_pos(int row, int c) { return c ^ (row % 16); }
+__device__ __forceinline__ int v_chunk_pos(int d, int c) { return c ^ ((d / 2) % 8); }
 constexpr float kLn2 = 0.6931471805599453f;
 
 template <class T> struct Mfma;
@@ -58,7 +80,8 @@ __device__ __forceinline__ int vt_slot(int key) {
     return kb * 32 + (v / 8) * 16 + half * 8 + (v % 8);
 }
 
-// V [total][Hkv][D]  ->  vt [Hkv][tile slot][D][64 key slots]; keys past the sequence end become 0.
+// V [total][Hkv][D]  ->  vt [Hkv][tile slot][D][64 key slots], 16-byte chunks of a row permuted as in
+// LDS; keys past the sequence end become 0.
 template <class T>
 __global__ __launch_bounds__(256) void transpose_v_kernel(const uint16_t* __restrict__ v, uint16_t* __restrict__ vt,
                                                           const int* __restrict__ cu_seqlens, int Hkv,
@@ -76,7 +99,8 @@ __global__ __launch_bounds__(256) void transpose_v_kernel(const uint16_t* __rest
     uint16_t* dst = vt + ((size_t)hk * tiles_total + tile_base(start, b) + jt) * kHeadDim * kTile;
     for (int idx = threadIdx.x; idx < kTile * kHeadDim; idx += 256) {
         const int d = idx / kTile, key = idx % kTile;
-        dst[(size_t)d * kTile + vt_slot(key)] = sm[key][d];
+        const int sl = vt_slot(key);
+        dst[(size_t)d * kTile + v_chunk_pos(d, sl / 8) * 8 + sl % 8] = sm[key][d];  // stored as the LDS tile is laid out
     }
 }
 
@@ -138,9 +162,13 @@ __global__ __launch_bounds__(kPrefillThreads) void sparse_prefill_kernel(
     LayerParams lp, const uint16_t* __restrict__ q, const uint16_t* __restrict__ k, const uint16_t* __restrict__ vt,
     const int* __restrict__ cu_seqlens, int batch, int blocks_per_seq, int tiles_total, uint16_t* __restrict__ out,
     float* __restrict__ lse_out, int total_tokens, PrefillSchedule sched) {
-    extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
-    // two stages of (K tile, V^T tile)
-    constexpr int kStageBytes = kKTileBytes + kVTileBytes;
+    // Two stages of (K tile, V^T tile).  Four separate arrays, and a loop unrolled over the two stages,
+    // so that the compiler can tell the tile being read from the tile being filled and does not wait
+    // for the loads in flight before every operand read.
+    __shared__ __attribute__((aligned(1024))) unsigned char k_lds0[kKTileBytes];
+    __shared__ __attribute__((aligned(1024))) unsigned char k_lds1[kKTileBytes];
+    __shared__ __attribute__((aligned(1024))) unsigned char v_lds0[kVTileBytes];
+    __shared__ __attribute__((aligned(1024))) unsigned char v_lds1[kVTileBytes];
 
     // heaviest query blocks first; see PrefillSchedule for the XCD-aware order
     const int xcd = blockIdx.x % kXcds;
@@ -201,49 +229,40 @@ __global__ __launch_bounds__(kPrefillThreads) void sparse_prefill_kernel(
         for (int i = 0; i < 16; ++i) acc[db][i] = 0.f;
     float m_run = -INFINITY, l_run = 0.f;  // running maximum (scaled, base 2) and sum of this lane's query row
 
-    // ---- staging: each thread moves 2 x 16 B of the K tile and 2 x 16 B of the V^T tile
+    // ---- staging: every wave issues two direct-to-LDS loads of 1 KiB per tile and operand
     const uint16_t* kbase = k + ((size_t)start * lp.Hkv + hk) * kHeadDim;
     const uint16_t* vtbase = vt + ((size_t)hk * tiles_total + tile_base(start, b)) * kHeadDim * kTile;
     static_assert(kTile * 16 == 2 * kPrefillThreads, "each thread stages two chunks per tile");
-    // The next tile travels through registers while the current one is consumed from LDS; with the
-    // XCD-aware work order these loads hit the L2, so one tile of look-ahead covers their latency.
-    uint4 ra_k0 = {}, ra_k1 = {}, ra_v0 = {}, ra_v1 = {};
-    const int c0 = tid, c1 = tid + kPrefillThreads;  // 1024 chunks of 16 B per tile
-#define LSERVE_FETCH(R, JT)                                                                                       \
-    {                                                                                                             \
-        const int jt_ = (JT);                                                                                     \
-        const uint16_t* vsrc_ = vtbase + (size_t)jt_ * kHeadDim * kTile;                                          \
-        R##_k0 = reinterpret_cast<const uint4*>(kbase + (size_t)min(jt_ * kTile + c0 / 16, len - 1) * lp.Hkv * kHeadDim)[c0 % 16]; \
-        R##_k1 = reinterpret_cast<const uint4*>(kbase + (size_t)min(jt_ * kTile + c1 / 16, len - 1) * lp.Hkv * kHeadDim)[c1 % 16]; \
-        R##_v0 = reinterpret_cast<const uint4*>(vsrc_)[c0];                                                         \
-        R##_v1 = reinterpret_cast<const uint4*>(vsrc_)[c1];                                                         \
-    }
-#define LSERVE_STASH(R, STAGE)                                                                                    \
-    {                                                                                                             \
-        unsigned char* kd_ = smem + (STAGE) * kStageBytes;                                                        \
-        unsigned char* vd_ = kd_ + kKTileBytes;                                                                   \
-        *reinterpret_cast<uint4*>(kd_ + (c0 / 16) * kKRowBytes + (c0 % 16) * 16) = R##_k0;                          \
-        *reinterpret_cast<uint4*>(kd_ + (c1 / 16) * kKRowBytes + (c1 % 16) * 16) = R##_k1;                          \
-        *reinterpret_cast<uint4*>(vd_ + (c0 / 8) * kVRowBytes + (c0 % 8) * 16) = R##_v0;                            \
-        *reinterpret_cast<uint4*>(vd_ + (c1 / 8) * kVRowBytes + (c1 % 8) * 16) = R##_v1;                            \
-    }
+    // lane `lane` of load i of this wave fills slot (2 wave + i) * 64 + lane of the tile
+    const int krow0 = wave * 8 + lane / 16;              // K row of load 0 (load 1: + 4, same row % 16 class + 4)
+    auto fetch = [&](unsigned char* kd, unsigned char* vd, int jt) {
+        const uint16_t* vsrc = vtbase + (size_t)jt * kHeadDim * kTile;
+#pragma unroll
+        for (int i = 0; i < 2; ++i) {
+            const int row = krow0 + 4 * i;
+            const uint16_t* ksrc = kbase + (size_t)min(jt * kTile + row, len - 1) * lp.Hkv * kHeadDim +
+                                   k_chunk_pos(row, lane % 16) * 8;  // the permutation is an involution
+            dma_load16(ksrc, lds_address(kd) + (wave * 2 + i) * 1024);
+            dma_load16(vsrc + ((wave * 2 + i) * 64 + lane) * 8, lds_address(vd) + (wave * 2 + i) * 1024);
+        }
+    };
     auto tile_of = [sink_end, band_begin](int it) { return it < sink_end ? it : band_begin + (it - sink_end); };
 
-    LSERVE_FETCH(ra, tile_of(0));
-    LSERVE_STASH(ra, 0);
-    __syncthreads();
+    // loop-invariant operand offsets of this lane inside a tile
+    int koff[8], voff[4];
+#pragma unroll
+    for (int kk = 0; kk < 8; ++kk) koff[kk] = n * kKRowBytes + k_chunk_pos(n, kk * 2 + half) * 16;
+#pragma unroll
+    for (int step = 0; step < 4; ++step) voff[step] = n * kVRowBytes + v_chunk_pos(n, step * 2 + half) * 16;
 
-    for (int it = 0; it < n_visit; ++it) {
-        const int stage = it & 1;
+    auto tile_step = [&](int it, const unsigned char* ks, const unsigned char* vs, unsigned char* kd, unsigned char* vd) {
         const int jt = tile_of(it);
-        if (it + 1 < n_visit) LSERVE_FETCH(ra, tile_of(it + 1));
+        if (it + 1 < n_visit) fetch(kd, vd, tile_of(it + 1));
 
         // does this wave's mask tile keep key tile jt?
         bool keep = wave_has_rows && jt <= iq;
         if (streaming) keep = keep && (jt < lp.sink_pages || jt > iq - lp.local_pages);
         if (keep) {
-            const unsigned char* ks = smem + stage * kStageBytes;
-            const unsigned char* vs = ks + kKTileBytes;
             const bool diagonal = jt == iq;
             // S^T for the 64 keys of the tile, two blocks of 32 keys.  All operand reads of a block are
             // issued before its products so that LDS latency is paid once, and the two blocks'
@@ -255,7 +274,7 @@ __global__ __launch_bounds__(kPrefillThreads) void sparse_prefill_kernel(
             for (int kk = 0; kk < 8; ++kk)
 #pragma unroll
                 for (int kb = 0; kb < 2; ++kb)
-                    ka[kk][kb] = *reinterpret_cast<const uint4*>(ks + (kb * 32 + n) * kKRowBytes + kk * 32 + half * 16);
+                    ka[kk][kb] = *reinterpret_cast<const uint4*>(ks + kb * 32 * kKRowBytes + koff[kk]);
 #pragma unroll
             for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
@@ -319,17 +338,23 @@ __global__ __launch_bounds__(kPrefillThreads) void sparse_prefill_kernel(
                 uint4 va[4];
 #pragma unroll
                 for (int db = 0; db < 4; ++db)
-                    va[db] = *reinterpret_cast<const uint4*>(vs + (db * 32 + n) * kVRowBytes +
-                                                             (kb * 32 + j * 16 + half * 8) * 2);
+                    va[db] = *reinterpret_cast<const uint4*>(vs + db * 32 * kVRowBytes + voff[step]);
 #pragma unroll
                 for (int db = 0; db < 4; ++db) acc[db] = Mfma<T>::run(va[db], pb[kb][j], acc[db]);
             }
         }
-        if (it + 1 < n_visit) LSERVE_STASH(ra, stage ^ 1);
-        __syncthreads();
+        dma_wait();
+        __syncthreads();  // the next tile has landed and this one is free
+    };
+
+    fetch(k_lds0, v_lds0, tile_of(0));
+    dma_wait();
+    __syncthreads();
+    for (int it = 0; it < n_visit; it += 2) {
+        tile_step(it, k_lds0, v_lds0, k_lds1, v_lds1);
+        if (it + 1 >= n_visit) break;
+        tile_step(it + 1, k_lds1, v_lds1, k_lds0, v_lds0);
     }
-#undef LSERVE_FETCH
-#undef LSERVE_STASH
 
     if (!wave_has_rows) return;
     // ---- epilogue: lane (n, half) holds O^T[d][q] for d = 32 db + 8 (i / 4) + 4 half + i % 4
@@ -365,14 +390,6 @@ hipError_t launch_prefill(const LayerParams& lp, const void* q, const void* k, c
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     const int blocks_per_seq = (max_seqlen + kRowsPerBlock - 1) / kRowsPerBlock;
-    const size_t lds = 2 * (size_t)(kKTileBytes + kVTileBytes);
-    static bool attr_done = false;  // one flag per element type (this function is a template)
-    if (!attr_done) {
-        e = hipFuncSetAttribute(reinterpret_cast<const void*>(&sparse_prefill_kernel<T>),
-                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-        if (e != hipSuccess) return e;
-        attr_done = true;
-    }
     PrefillSchedule sched;
     sched.qblocks_total = blocks_per_seq * batch;
     for (int c = 0; c < 2; ++c) {
@@ -390,7 +407,7 @@ hipError_t launch_prefill(const LayerParams& lp, const void* q, const void* k, c
             hc.items_per_xcd = (hc.heads * lp.group * sched.qblocks_total + kXcds - 1) / kXcds;
     }
     const int grid = kXcds * (sched.cls[0].items_per_xcd + sched.cls[1].items_per_xcd);
-    hipLaunchKernelGGL(sparse_prefill_kernel<T>, dim3(grid), dim3(kPrefillThreads), lds, stream,
+    hipLaunchKernelGGL(sparse_prefill_kernel<T>, dim3(grid), dim3(kPrefillThreads), 0, stream,
                        lp, reinterpret_cast<const uint16_t*>(q), reinterpret_cast<const uint16_t*>(k), vt, cu_seqlens,
                        batch, blocks_per_seq, tiles_total, reinterpret_cast<uint16_t*>(out), lse_out, total_tokens, sched);
     return hipGetLastError();
