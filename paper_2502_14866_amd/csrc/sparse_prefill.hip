@@ -17,6 +17,12 @@
 // order matches the accumulator layout, so every LDS operand read is one 16-byte access.
 #include "kernels.h"
 
+#ifndef LSERVE_PRIO_MODE
+#define LSERVE_PRIO_MODE 0
+#endif
+#ifndef LSERVE_AHEAD
+#define LSERVE_AHEAD 4
+#endif
 namespace lserve {
 
 namespace {
@@ -43,9 +49,14 @@ constexpr int kVTileBytes = kHeadDim * kVRowBytes;
 // lgkmcnt(0), exposing the LDS latency in front of the products.  `lds_base` is the wave-uniform LDS
 // byte address of the 1 KiB destination; lane l lands at lds_base + 16 l.  Completion is tracked by
 // vmcnt only, which dma_wait() drains before the workgroup barrier.
-__device__ __forceinline__ void dma_load16(const void* src, unsigned lds_base) {
-    const unsigned base = __builtin_amdgcn_readfirstlane(lds_base);
-    asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" ::"v"(src), "s"(base) : "memory");
+// The source address is a wave-uniform 64-bit base (scalar registers) plus a 32-bit lane offset.
+__device__ __forceinline__ void dma_load16(unsigned long long src_base, unsigned lane_offset, unsigned lds_base) {
+    asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1" ::"v"(lane_offset), "s"(src_base), "s"(lds_base) : "memory");
+}
+// Tells the compiler that a value every lane agrees on can live in scalar registers.
+__device__ __forceinline__ unsigned long long uniform64(unsigned long long x) {
+    return ((unsigned long long)(unsigned)__builtin_amdgcn_readfirstlane((unsigned)(x >> 32)) << 32) |
+           (unsigned)__builtin_amdgcn_readfirstlane((unsigned)x);
 }
 __device__ __forceinline__ void dma_wait() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
 __device__ __forceinline__ unsigned lds_address(const void* p) {
@@ -233,17 +244,34 @@ __global__ __launch_bounds__(kPrefillThreads) void sparse_prefill_kernel(
     const uint16_t* kbase = k + ((size_t)start * lp.Hkv + hk) * kHeadDim;
     const uint16_t* vtbase = vt + ((size_t)hk * tiles_total + tile_base(start, b)) * kHeadDim * kTile;
     static_assert(kTile * 16 == 2 * kPrefillThreads, "each thread stages two chunks per tile");
-    // lane `lane` of load i of this wave fills slot (2 wave + i) * 64 + lane of the tile
-    const int krow0 = wave * 8 + lane / 16;              // K row of load 0 (load 1: + 4, same row % 16 class + 4)
+    // lane `lane` of load i of this wave fills slot (2 wave + i) * 64 + lane of the tile.  Addresses are a
+    // wave-uniform 64-bit tile base (scalar arithmetic) plus a 32-bit lane offset that does not depend
+    // on the tile, except in the ragged last tile of a sequence where rows past the end are clamped.
+    const unsigned k_row_bytes = (unsigned)__builtin_amdgcn_readfirstlane(lp.Hkv * kHeadDim * 2);
+    const int krow0 = wave * 8 + lane / 16;  // K row of load 0; load 1 takes row + 4
+    unsigned kofs[2], vofs[2];
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+        kofs[i] = (unsigned)(krow0 + 4 * i) * k_row_bytes + k_chunk_pos(krow0 + 4 * i, lane % 16) * 16;  // an involution
+        vofs[i] = ((wave * 2 + i) * 64 + lane) * 16;
+    }
+    const unsigned lds_wave = (unsigned)__builtin_amdgcn_readfirstlane(wave * 2048);
+    const unsigned long long kbase_u = uniform64((unsigned long long)kbase), vtbase_u = uniform64((unsigned long long)vtbase);
+    const int len_u = __builtin_amdgcn_readfirstlane(len);
     auto fetch = [&](unsigned char* kd, unsigned char* vd, int jt) {
-        const uint16_t* vsrc = vtbase + (size_t)jt * kHeadDim * kTile;
+        jt = __builtin_amdgcn_readfirstlane(jt);
+        const unsigned long long ktile = kbase_u + (unsigned long long)jt * (kTile * k_row_bytes);
+        const unsigned long long vtile = vtbase_u + (unsigned long long)jt * (kHeadDim * kTile * 2);
+        const int rows_left = len_u - jt * kTile;
 #pragma unroll
         for (int i = 0; i < 2; ++i) {
-            const int row = krow0 + 4 * i;
-            const uint16_t* ksrc = kbase + (size_t)min(jt * kTile + row, len - 1) * lp.Hkv * kHeadDim +
-                                   k_chunk_pos(row, lane % 16) * 8;  // the permutation is an involution
-            dma_load16(ksrc, lds_address(kd) + (wave * 2 + i) * 1024);
-            dma_load16(vsrc + ((wave * 2 + i) * 64 + lane) * 8, lds_address(vd) + (wave * 2 + i) * 1024);
+            unsigned ko = kofs[i];
+            if (rows_left < kTile) {
+                const int row = krow0 + 4 * i;
+                ko = (unsigned)min(row, rows_left - 1) * k_row_bytes + k_chunk_pos(row, lane % 16) * 16;
+            }
+            dma_load16(ktile, ko, __builtin_amdgcn_readfirstlane(lds_address(kd) + lds_wave + i * 1024));
+            dma_load16(vtile, vofs[i], __builtin_amdgcn_readfirstlane(lds_address(vd) + lds_wave + i * 1024));
         }
     };
     auto tile_of = [sink_end, band_begin](int it) { return it < sink_end ? it : band_begin + (it - sink_end); };
@@ -255,10 +283,20 @@ __global__ __launch_bounds__(kPrefillThreads) void sparse_prefill_kernel(
 #pragma unroll
     for (int step = 0; step < 4; ++step) voff[step] = n * kVRowBytes + v_chunk_pos(n, step * 2 + half) * 16;
 
+#ifdef LSERVE_TRACE
+    const bool tracing = blockIdx.x == LSERVE_TRACE && lse_out != nullptr;
+    unsigned long long* tbuf = reinterpret_cast<unsigned long long*>(lse_out + (size_t)lp.H * total_tokens);
+    if (tracing && tid == 0) { tbuf[0] = hk; tbuf[1] = hh; tbuf[2] = qblk; tbuf[3] = n_visit; }
+#define LSERVE_STAMP(K) if (tracing && it >= 64 && it < 80 && lane == 0) tbuf[8 + ((it - 64) * 8 + wave) * 8 + (K)] = __builtin_readcyclecounter();
+#else
+#define LSERVE_STAMP(K)
+#endif
     auto tile_step = [&](int it, const unsigned char* ks, const unsigned char* vs, unsigned char* kd, unsigned char* vd) {
         const int jt = tile_of(it);
+        LSERVE_STAMP(0)
         if (it + 1 < n_visit) fetch(kd, vd, tile_of(it + 1));
 
+        LSERVE_STAMP(1)
         // does this wave's mask tile keep key tile jt?
         bool keep = wave_has_rows && jt <= iq;
         if (streaming) keep = keep && (jt < lp.sink_pages || jt > iq - lp.local_pages);
@@ -267,7 +305,9 @@ __global__ __launch_bounds__(kPrefillThreads) void sparse_prefill_kernel(
             // S^T for the 64 keys of the tile, two blocks of 32 keys.  All operand reads of a block are
             // issued before its products so that LDS latency is paid once, and the two blocks'
             // accumulation chains alternate in the matrix pipe.
+#if LSERVE_PRIO_MODE == 0
             __builtin_amdgcn_s_setprio(2);  // products first: the other wavefront of the SIMD fills in with softmax work
+#endif
             float16_t s[2];
             uint4 ka[8][2];
 #pragma unroll
@@ -285,14 +325,17 @@ __global__ __launch_bounds__(kPrefillThreads) void sparse_prefill_kernel(
                 s[1] = Mfma<T>::run(ka[kk][1], qreg[kk], s[1]);
             }
             // schedule: operand reads run four ahead of the products that consume them
-            __builtin_amdgcn_sched_group_barrier(0x100, 4, 0);
+            __builtin_amdgcn_sched_group_barrier(0x100, LSERVE_AHEAD, 0);
 #pragma unroll
-            for (int u = 0; u < 12; ++u) {
+            for (int u = 0; u < 16 - LSERVE_AHEAD; ++u) {
                 __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
                 __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
             }
-            __builtin_amdgcn_sched_group_barrier(0x008, 4, 0);
+            __builtin_amdgcn_sched_group_barrier(0x008, LSERVE_AHEAD, 0);
+#if LSERVE_PRIO_MODE == 0
             __builtin_amdgcn_s_setprio(0);
+#endif
+            LSERVE_STAMP(2)
             if (diagonal) {  // causal mask inside the diagonal tile
 #pragma unroll
                 for (int kb = 0; kb < 2; ++kb)
@@ -317,6 +360,7 @@ __global__ __launch_bounds__(kPrefillThreads) void sparse_prefill_kernel(
                     for (int i = 0; i < 16; ++i) acc[db][i] *= alpha;
                 m_run = m_new;
             }
+            LSERVE_STAMP(3)
             uint4 pb[2][2];  // P^T packed to 16 bit: [key block][16-key step]
 #pragma unroll
             for (int kb = 0; kb < 2; ++kb) {
@@ -343,10 +387,20 @@ __global__ __launch_bounds__(kPrefillThreads) void sparse_prefill_kernel(
                 for (int db = 0; db < 4; ++db) acc[db] = Mfma<T>::run(va[db], pb[kb][j], acc[db]);
             }
         }
+        LSERVE_STAMP(4)
         dma_wait();
+        LSERVE_STAMP(5)
         __syncthreads();  // the next tile has landed and this one is free
+        LSERVE_STAMP(6)
     };
 
+#if LSERVE_PRIO_MODE == 1
+    if (wave < 4) __builtin_amdgcn_s_setprio(3);
+#elif LSERVE_PRIO_MODE == 2
+    if (wave % 2 == 0) __builtin_amdgcn_s_setprio(3);
+#elif LSERVE_PRIO_MODE == 3
+    if (wave >= 4) __builtin_amdgcn_s_setprio(3);
+#endif
     fetch(k_lds0, v_lds0, tile_of(0));
     dma_wait();
     __syncthreads();
@@ -356,6 +410,9 @@ __global__ __launch_bounds__(kPrefillThreads) void sparse_prefill_kernel(
         tile_step(it + 1, k_lds1, v_lds1, k_lds0, v_lds0);
     }
 
+#ifdef LSERVE_TRACE
+    if (tracing) return;
+#endif
     if (!wave_has_rows) return;
     // ---- epilogue: lane (n, half) holds O^T[d][q] for d = 32 db + 8 (i / 4) + 4 half + i % 4
     const float lt = halves_sum(l_run);
