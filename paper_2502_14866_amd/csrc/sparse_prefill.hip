@@ -6,8 +6,9 @@
 //
 // Mapping to CDNA4: a workgroup of eight wavefronts owns 256 consecutive query rows of one head;
 // wavefronts 2t and 2t + 1 own the two 32-row halves of mask tile 4 * block + t.  Two wavefronts
-// share each SIMD, so the matrix pipe of one overlaps the softmax arithmetic of the other.  Key tiles are staged through LDS once per
-// workgroup and consumed by all four wavefronts.  Scores are computed transposed,
+// share each SIMD, so the matrix pipe of one overlaps the softmax arithmetic of the other.  K and
+// V^T tiles are brought into LDS once per workgroup by direct-to-LDS loads, double buffered, and
+// consumed by all eight wavefronts.  Scores are computed transposed,
 //   S^T (keys x queries) = K (keys x d) * Q^T (d x queries)          v_mfma_f32_32x32x16
 // so that a lane owns one query column: the softmax reductions over keys stay inside the lane
 // (plus one exchange between the two lane halves), and the exponentiated tile is already in the
@@ -17,12 +18,6 @@
 // order matches the accumulator layout, so every LDS operand read is one 16-byte access.
 #include "kernels.h"
 
-#ifndef LSERVE_PRIO_MODE
-#define LSERVE_PRIO_MODE 0
-#endif
-#ifndef LSERVE_AHEAD
-#define LSERVE_AHEAD 4
-#endif
 namespace lserve {
 
 namespace {
@@ -31,11 +26,15 @@ typedef _Float16 half8_t __attribute__((ext_vector_type(8)));
 typedef __bf16 bf168_t __attribute__((ext_vector_type(8)));
 typedef float float16_t __attribute__((ext_vector_type(16)));
 
-constexpr int kTile = 64;              // mask tile = key tile = page
-constexpr int kPrefillThreads = 512;   // 8 waves: two per SIMD, each owning 32 query rows
-constexpr int kRowsPerBlock = 256;     // 4 mask tiles of queries
-constexpr int kKRowBytes = 256;        // K tile row: 128 x 16 bit = 16 chunks of 16 B
-constexpr int kVRowBytes = 128;        // V^T tile row: 64 keys x 16 bit = 8 chunks of 16 B
+constexpr int kTile = 64;                          // mask tile = key tile = page
+constexpr int kPrefillWaves = 8;                   // two per SIMD, each owning 32 query rows
+constexpr int kPrefillThreads = kPrefillWaves * kWave;
+constexpr int kTilesPerBlock = kPrefillWaves / 2;  // mask tiles of queries per workgroup
+constexpr int kRowsPerBlock = kTilesPerBlock * kTile;
+constexpr int kDmaLoads = 16 / kPrefillWaves;      // 1 KiB loads per wave, tile and operand
+constexpr int kAhead = 4;                          // operand reads in flight ahead of the score products
+constexpr int kKRowBytes = 256;                    // K tile row: 128 x 16 bit = 16 chunks of 16 B
+constexpr int kVRowBytes = 128;                    // V^T tile row: 64 keys x 16 bit = 8 chunks of 16 B
 constexpr int kKTileBytes = kTile * kKRowBytes;
 constexpr int kVTileBytes = kHeadDim * kVRowBytes;
 
@@ -44,12 +43,15 @@ constexpr int kVTileBytes = kHeadDim * kVRowBytes;
 // chunks inside a row instead: chunk c of K row r sits at position c ^ (r % 16), chunk c of V^T row d
 // at position c ^ ((d / 2) % 8).  Sixteen consecutive rows then hit sixteen different 16-byte bank
 // groups for any fixed c, which is what the matrix-operand reads (one row per lane) need.
+__device__ __forceinline__ int k_chunk_pos(int row, int c) { return c ^ (row % 16); }
+__device__ __forceinline__ int v_chunk_pos(int d, int c) { return c ^ ((d / 2) % 8); }
+
 // The load itself is written in assembly: left to the compiler it is treated as an access that may
 // touch both memory and LDS, and while one is in flight every LDS operand read in the loop waits with
-// lgkmcnt(0), exposing the LDS latency in front of the products.  `lds_base` is the wave-uniform LDS
-// byte address of the 1 KiB destination; lane l lands at lds_base + 16 l.  Completion is tracked by
+// lgkmcnt(0), exposing the LDS latency in front of the products.  The source address is a wave-uniform
+// 64-bit base (scalar registers) plus a 32-bit lane offset; `lds_base` is the wave-uniform LDS byte
+// address of the 1 KiB destination and lane l lands at lds_base + 16 l.  Completion is tracked by
 // vmcnt only, which dma_wait() drains before the workgroup barrier.
-// The source address is a wave-uniform 64-bit base (scalar registers) plus a 32-bit lane offset.
 __device__ __forceinline__ void dma_load16(unsigned long long src_base, unsigned lane_offset, unsigned lds_base) {
     asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1" ::"v"(lane_offset), "s"(src_base), "s"(lds_base) : "memory");
 }
@@ -63,8 +65,6 @@ __device__ __forceinline__ unsigned lds_address(const void* p) {
     return (unsigned)(size_t)(const __attribute__((address_space(3))) void*)p;
 }
 
-__device__ __forceinline__ int k_chunk_pos(int row, int c) { return c ^ (row % 16); }
-__device__ __forceinline__ int v_chunk_pos(int d, int c) { return c ^ ((d / 2) % 8); }
 constexpr float kLn2 = 0.6931471805599453f;
 
 template <class T> struct Mfma;
@@ -121,9 +121,7 @@ __device__ __forceinline__ uint4 pack8(const float* p) {
                       Elem<T>::pack(p[6], p[7]));
 }
 
-// Exchange between the two 32-lane halves of a wave (v_permlane32_swap): after the swap the first
-// result holds the lower half of both operands' low lanes, the second the upper halves, so combining
-// them gives every lane op(x[l], x[l ^ 32]).
+// Combine a value with the one held by the same lane of the other 32-lane half of the wave.
 __device__ __forceinline__ float halves_max(float x) { return fmaxf(x, __shfl_xor(x, 32, kWave)); }
 __device__ __forceinline__ float halves_sum(float x) { return x + __shfl_xor(x, 32, kWave); }
 
@@ -169,7 +167,7 @@ template <> struct Ones<F16> { static constexpr uint32_t pair = 0x3c003c00u; };
 template <> struct Ones<BF16> { static constexpr uint32_t pair = 0x3f803f80u; };
 
 template <class T>
-__global__ __launch_bounds__(kPrefillThreads) void sparse_prefill_kernel(
+__global__ __launch_bounds__(kPrefillThreads, 512 / kPrefillThreads) void sparse_prefill_kernel(
     LayerParams lp, const uint16_t* __restrict__ q, const uint16_t* __restrict__ k, const uint16_t* __restrict__ vt,
     const int* __restrict__ cu_seqlens, int batch, int blocks_per_seq, int tiles_total, uint16_t* __restrict__ out,
     float* __restrict__ lse_out, int total_tokens, PrefillSchedule sched) {
@@ -201,16 +199,16 @@ __global__ __launch_bounds__(kPrefillThreads) void sparse_prefill_kernel(
     const int tid = threadIdx.x, lane = tid % kWave, wave = tid / kWave;
     const int n = lane % 32, half = lane / 32;
     const bool streaming = (lp.streaming_mask >> hk) & 1ull;
-    const int iq = qblk * 4 + wave / 2;  // this wave's mask tile; the wave owns one half of its rows
+    const int iq = qblk * kTilesPerBlock + wave / 2;  // this wave's mask tile; the wave owns one half of its rows
     const int row0 = (wave % 2) * 32;    // first row of the wave inside the mask tile
     const int n_qtiles = ceil_div(len, kTile);
-    const int iq_last = min(qblk * 4 + 3, n_qtiles - 1);  // last mask tile of the block that holds rows
+    const int iq_last = min(qblk * kTilesPerBlock + kTilesPerBlock - 1, n_qtiles - 1);  // last mask tile of the block that holds rows
     const bool wave_has_rows = iq * kTile + row0 < len;
 
     // key tiles the block visits: [0, sink_end) and [band_begin, iq_last]
     int sink_end, band_begin;
     if (streaming) {
-        band_begin = max(0, qblk * 4 - lp.local_pages + 1);
+        band_begin = max(0, qblk * kTilesPerBlock - lp.local_pages + 1);
         sink_end = min(lp.sink_pages, band_begin);
     } else {
         band_begin = 0;
@@ -243,19 +241,18 @@ __global__ __launch_bounds__(kPrefillThreads) void sparse_prefill_kernel(
     // ---- staging: every wave issues two direct-to-LDS loads of 1 KiB per tile and operand
     const uint16_t* kbase = k + ((size_t)start * lp.Hkv + hk) * kHeadDim;
     const uint16_t* vtbase = vt + ((size_t)hk * tiles_total + tile_base(start, b)) * kHeadDim * kTile;
-    static_assert(kTile * 16 == 2 * kPrefillThreads, "each thread stages two chunks per tile");
     // lane `lane` of load i of this wave fills slot (2 wave + i) * 64 + lane of the tile.  Addresses are a
     // wave-uniform 64-bit tile base (scalar arithmetic) plus a 32-bit lane offset that does not depend
     // on the tile, except in the ragged last tile of a sequence where rows past the end are clamped.
     const unsigned k_row_bytes = (unsigned)__builtin_amdgcn_readfirstlane(lp.Hkv * kHeadDim * 2);
-    const int krow0 = wave * 8 + lane / 16;  // K row of load 0; load 1 takes row + 4
-    unsigned kofs[2], vofs[2];
+    const int krow0 = wave * (4 * kDmaLoads) + lane / 16;  // K row of load 0; load i takes row + 4 i
+    unsigned kofs[kDmaLoads], vofs[kDmaLoads];
 #pragma unroll
-    for (int i = 0; i < 2; ++i) {
+    for (int i = 0; i < kDmaLoads; ++i) {
         kofs[i] = (unsigned)(krow0 + 4 * i) * k_row_bytes + k_chunk_pos(krow0 + 4 * i, lane % 16) * 16;  // an involution
-        vofs[i] = ((wave * 2 + i) * 64 + lane) * 16;
+        vofs[i] = ((wave * kDmaLoads + i) * 64 + lane) * 16;
     }
-    const unsigned lds_wave = (unsigned)__builtin_amdgcn_readfirstlane(wave * 2048);
+    const unsigned lds_wave = (unsigned)__builtin_amdgcn_readfirstlane(wave * kDmaLoads * 1024);
     const unsigned long long kbase_u = uniform64((unsigned long long)kbase), vtbase_u = uniform64((unsigned long long)vtbase);
     const int len_u = __builtin_amdgcn_readfirstlane(len);
     auto fetch = [&](unsigned char* kd, unsigned char* vd, int jt) {
@@ -264,7 +261,7 @@ __global__ __launch_bounds__(kPrefillThreads) void sparse_prefill_kernel(
         const unsigned long long vtile = vtbase_u + (unsigned long long)jt * (kHeadDim * kTile * 2);
         const int rows_left = len_u - jt * kTile;
 #pragma unroll
-        for (int i = 0; i < 2; ++i) {
+        for (int i = 0; i < kDmaLoads; ++i) {
             unsigned ko = kofs[i];
             if (rows_left < kTile) {
                 const int row = krow0 + 4 * i;
@@ -283,20 +280,9 @@ __global__ __launch_bounds__(kPrefillThreads) void sparse_prefill_kernel(
 #pragma unroll
     for (int step = 0; step < 4; ++step) voff[step] = n * kVRowBytes + v_chunk_pos(n, step * 2 + half) * 16;
 
-#ifdef LSERVE_TRACE
-    const bool tracing = blockIdx.x == LSERVE_TRACE && lse_out != nullptr;
-    unsigned long long* tbuf = reinterpret_cast<unsigned long long*>(lse_out + (size_t)lp.H * total_tokens);
-    if (tracing && tid == 0) { tbuf[0] = hk; tbuf[1] = hh; tbuf[2] = qblk; tbuf[3] = n_visit; }
-#define LSERVE_STAMP(K) if (tracing && it >= 64 && it < 80 && lane == 0) tbuf[8 + ((it - 64) * 8 + wave) * 8 + (K)] = __builtin_readcyclecounter();
-#else
-#define LSERVE_STAMP(K)
-#endif
     auto tile_step = [&](int it, const unsigned char* ks, const unsigned char* vs, unsigned char* kd, unsigned char* vd) {
         const int jt = tile_of(it);
-        LSERVE_STAMP(0)
         if (it + 1 < n_visit) fetch(kd, vd, tile_of(it + 1));
-
-        LSERVE_STAMP(1)
         // does this wave's mask tile keep key tile jt?
         bool keep = wave_has_rows && jt <= iq;
         if (streaming) keep = keep && (jt < lp.sink_pages || jt > iq - lp.local_pages);
@@ -305,9 +291,7 @@ __global__ __launch_bounds__(kPrefillThreads) void sparse_prefill_kernel(
             // S^T for the 64 keys of the tile, two blocks of 32 keys.  All operand reads of a block are
             // issued before its products so that LDS latency is paid once, and the two blocks'
             // accumulation chains alternate in the matrix pipe.
-#if LSERVE_PRIO_MODE == 0
             __builtin_amdgcn_s_setprio(2);  // products first: the other wavefront of the SIMD fills in with softmax work
-#endif
             float16_t s[2];
             uint4 ka[8][2];
 #pragma unroll
@@ -325,17 +309,14 @@ __global__ __launch_bounds__(kPrefillThreads) void sparse_prefill_kernel(
                 s[1] = Mfma<T>::run(ka[kk][1], qreg[kk], s[1]);
             }
             // schedule: operand reads run four ahead of the products that consume them
-            __builtin_amdgcn_sched_group_barrier(0x100, LSERVE_AHEAD, 0);
+            __builtin_amdgcn_sched_group_barrier(0x100, kAhead, 0);
 #pragma unroll
-            for (int u = 0; u < 16 - LSERVE_AHEAD; ++u) {
+            for (int u = 0; u < 16 - kAhead; ++u) {
                 __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
                 __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
             }
-            __builtin_amdgcn_sched_group_barrier(0x008, LSERVE_AHEAD, 0);
-#if LSERVE_PRIO_MODE == 0
+            __builtin_amdgcn_sched_group_barrier(0x008, kAhead, 0);
             __builtin_amdgcn_s_setprio(0);
-#endif
-            LSERVE_STAMP(2)
             if (diagonal) {  // causal mask inside the diagonal tile
 #pragma unroll
                 for (int kb = 0; kb < 2; ++kb)
@@ -360,7 +341,6 @@ __global__ __launch_bounds__(kPrefillThreads) void sparse_prefill_kernel(
                     for (int i = 0; i < 16; ++i) acc[db][i] *= alpha;
                 m_run = m_new;
             }
-            LSERVE_STAMP(3)
             uint4 pb[2][2];  // P^T packed to 16 bit: [key block][16-key step]
 #pragma unroll
             for (int kb = 0; kb < 2; ++kb) {
@@ -387,20 +367,10 @@ __global__ __launch_bounds__(kPrefillThreads) void sparse_prefill_kernel(
                 for (int db = 0; db < 4; ++db) acc[db] = Mfma<T>::run(va[db], pb[kb][j], acc[db]);
             }
         }
-        LSERVE_STAMP(4)
         dma_wait();
-        LSERVE_STAMP(5)
         __syncthreads();  // the next tile has landed and this one is free
-        LSERVE_STAMP(6)
     };
 
-#if LSERVE_PRIO_MODE == 1
-    if (wave < 4) __builtin_amdgcn_s_setprio(3);
-#elif LSERVE_PRIO_MODE == 2
-    if (wave % 2 == 0) __builtin_amdgcn_s_setprio(3);
-#elif LSERVE_PRIO_MODE == 3
-    if (wave >= 4) __builtin_amdgcn_s_setprio(3);
-#endif
     fetch(k_lds0, v_lds0, tile_of(0));
     dma_wait();
     __syncthreads();
@@ -410,9 +380,6 @@ __global__ __launch_bounds__(kPrefillThreads) void sparse_prefill_kernel(
         tile_step(it + 1, k_lds1, v_lds1, k_lds0, v_lds0);
     }
 
-#ifdef LSERVE_TRACE
-    if (tracing) return;
-#endif
     if (!wave_has_rows) return;
     // ---- epilogue: lane (n, half) holds O^T[d][q] for d = 32 db + 8 (i / 4) + 4 half + i % 4
     const float lt = halves_sum(l_run);
