@@ -259,7 +259,7 @@ def main():
         },
         "selector": {
             "ms_per_run": sel_mean_ms,
-            "kernels": "page_stats_kernel (tail refresh) + page_score_kernel + topk_pages_kernel",
+            "kernels": "page_score_kernel (rebuilds the stale tail statistics itself) + topk_pages_kernel",
             "stats_bytes_per_run": stats_bytes_run,
             "achieved_GBs": stats_bytes_run / (sel_mean_ms * 1e-3) / 1e9 if sel_mean_ms else None,
             "frac_of_hbm_peak": stats_bytes_run / (sel_mean_ms * 1e-3) / 1e9 / HBM_PEAK_GBS if sel_mean_ms else None,

@@ -146,6 +146,12 @@ int lserve_append_kv(const lserve_attn_desc *desc, const lserve_paged_kv *kv, co
  *
  *   q            device [batch][H][D]
  *   budget_tokens  K = budget_tokens / N_P, must be >= 1
+ *   stats_valid_len  device [batch] or NULL.  NULL: kv->stats is current for every token below L_b.
+ *                Otherwise kv->stats is current only for tokens below stats_valid_len[b] (<= L_b):
+ *                the logical pages that hold tokens [stats_valid_len[b], L_b) are recomputed from
+ *                kv->k_pool inside this call (Sec. 3.5.2: statistics of the tokens decoded since the
+ *                last selection), used for the scores and written back to kv->stats, which saves the
+ *                separate lserve_build_page_stats launch in a decode loop.  Needs kv->k_pool.
  *   sel_pages    device [batch][Hkv][K] out: positions of the selected pages inside the sequence
  *                (indices into page_table[b]), ascending; entries past sel_count are -1.
  *                Rows of streaming heads are filled with -1.
@@ -156,8 +162,8 @@ int lserve_append_kv(const lserve_attn_desc *desc, const lserve_paged_kv *kv, co
  *   workspace    device, >= lserve_workspace_bytes(LSERVE_CALL_SELECT_PAGES, ...)
  */
 int lserve_select_pages(const lserve_attn_desc *desc, const lserve_paged_kv *kv, const void *q,
-                        int32_t budget_tokens, int32_t *sel_pages, int32_t *sel_count,
-                        int32_t *sel_seq_len, float *scores_out, void *workspace,
+                        int32_t budget_tokens, const int32_t *stats_valid_len, int32_t *sel_pages,
+                        int32_t *sel_count, int32_t *sel_seq_len, float *scores_out, void *workspace,
                         size_t workspace_bytes, void *stream);
 
 /*

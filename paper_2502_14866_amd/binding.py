@@ -70,7 +70,7 @@ def load_library():
         vp, i32, sz = ctypes.c_void_p, ctypes.c_int32, ctypes.c_size_t
         dp, kp = ctypes.POINTER(_CAttnDesc), ctypes.POINTER(_CPagedKV)
         lib.lserve_build_page_stats.argtypes = [dp, kp, vp, i32, vp]
-        lib.lserve_select_pages.argtypes = [dp, kp, vp, i32, vp, vp, vp, vp, vp, sz, vp]
+        lib.lserve_select_pages.argtypes = [dp, kp, vp, i32, vp, vp, vp, vp, vp, vp, sz, vp]
         lib.lserve_sparse_prefill.argtypes = [dp, vp, vp, vp, vp, i32, i32, i32, vp, vp, vp, sz, vp]
         lib.lserve_sparse_decode.argtypes = [dp, kp, vp, vp, vp, vp, i32, vp, vp, vp, sz, vp]
         lib.lserve_append_kv.argtypes = [dp, kp, vp, vp, vp, vp, i32, vp]
@@ -180,9 +180,10 @@ def lserve_append_kv(desc: AttnDesc, kv: PagedKV, k_new: torch.Tensor, v_new: to
 def lserve_select_pages(desc: AttnDesc, kv: PagedKV, q: torch.Tensor, budget_tokens: int,
                         sel_pages: torch.Tensor, sel_count: torch.Tensor, sel_seq_len: torch.Tensor,
                         scores_out: Optional[torch.Tensor] = None, workspace: Optional[torch.Tensor] = None,
-                        stream=None) -> None:
+                        stream=None, stats_valid_len: Optional[torch.Tensor] = None) -> None:
     ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
-    _check(load_library().lserve_select_pages(desc.c(), kv.c(), _ptr(q), budget_tokens, _ptr(sel_pages),
+    _check(load_library().lserve_select_pages(desc.c(), kv.c(), _ptr(q), budget_tokens, _ptr(stats_valid_len),
+                                              _ptr(sel_pages),
                                               _ptr(sel_count), _ptr(sel_seq_len), _ptr(scores_out),
                                               _ptr(workspace), ws_bytes, _stream(stream)), "lserve_select_pages")
 

@@ -19,7 +19,7 @@ hipError_t launch_append_kv(int dtype, const LayerParams& lp, const PagedParams&
                             const int* cu_new, const int* start_pos, int max_new_per_seq, hipStream_t stream);
 
 hipError_t launch_select_pages(int dtype, const LayerParams& lp, const PagedParams& kv, const void* q,
-                               int budget_pages, int* sel_pages, int* sel_count, int* sel_seq_len,
+                               const int* stats_valid_len, int budget_pages, int* sel_pages, int* sel_count, int* sel_seq_len,
                                float* scores, bool scores_is_user_buffer, const HeadList& selecting,
                                hipStream_t stream);
 

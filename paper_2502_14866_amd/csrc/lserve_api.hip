@@ -116,16 +116,16 @@ int lserve_append_kv(const lserve_attn_desc* desc, const lserve_paged_kv* kv, co
 }
 
 int lserve_select_pages(const lserve_attn_desc* desc, const lserve_paged_kv* kv, const void* q, int32_t budget_tokens,
-                        int32_t* sel_pages, int32_t* sel_count, int32_t* sel_seq_len, float* scores_out,
-                        void* workspace, size_t workspace_bytes, void* stream) {
+                        const int32_t* stats_valid_len, int32_t* sel_pages, int32_t* sel_count, int32_t* sel_seq_len,
+                        float* scores_out, void* workspace, size_t workspace_bytes, void* stream) {
     LayerParams lp;
     PagedParams pp;
     int rc = make_layer(desc, &lp);
     if (rc) return rc;
-    rc = make_paged(kv, false, false, true, &pp);
+    rc = make_paged(kv, stats_valid_len != nullptr, false, true, &pp);
     if (rc) return rc;
     if (!q || !sel_pages || !sel_count || !sel_seq_len) return LSERVE_ERR_INVALID_ARG;
-    if (!aligned16(q) || !aligned16(sel_pages) || !aligned16(sel_count) || !aligned16(sel_seq_len) ||
+    if (!aligned16(q) || !aligned16(stats_valid_len) || !aligned16(sel_pages) || !aligned16(sel_count) || !aligned16(sel_seq_len) ||
         !aligned16(scores_out) || !aligned16(workspace))
         return LSERVE_ERR_INVALID_ARG;
     if (budget_tokens < lp.NP) return LSERVE_ERR_INVALID_ARG;
@@ -134,8 +134,8 @@ int lserve_select_pages(const lserve_attn_desc* desc, const lserve_paged_kv* kv,
         if (!workspace || workspace_bytes < select_workspace_bytes(lp, pp.batch, pp.max_pages)) return LSERVE_ERR_WORKSPACE;
         scores = reinterpret_cast<float*>(workspace);
     }
-    hipError_t e = launch_select_pages(desc->dtype, lp, pp, q, budget_tokens / lp.NP, sel_pages, sel_count, sel_seq_len,
-                                       scores, scores_out != nullptr, selecting_heads(lp), (hipStream_t)stream);
+    hipError_t e = launch_select_pages(desc->dtype, lp, pp, q, stats_valid_len, budget_tokens / lp.NP, sel_pages, sel_count,
+                                       sel_seq_len, scores, scores_out != nullptr, selecting_heads(lp), (hipStream_t)stream);
     return e == hipSuccess ? LSERVE_OK : fail_hip(e);
 }
 

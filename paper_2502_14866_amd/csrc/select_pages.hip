@@ -27,6 +27,7 @@ __device__ __forceinline__ unsigned orderable(float s) {
 template <class T, int N>
 __global__ __launch_bounds__(kScoreThreads) void page_score_kernel(LayerParams lp, PagedParams kv,
                                                                     const uint4* __restrict__ q,
+                                                                    const int* __restrict__ stats_valid_len,
                                                                     float* __restrict__ scores, HeadList heads) {
     const int b = blockIdx.z;
     const int hk = heads.idx[blockIdx.y];
@@ -57,12 +58,52 @@ __global__ __launch_bounds__(kScoreThreads) void page_score_kernel(LayerParams l
     }
 
     const int phys = kv.page_table[(size_t)b * kv.max_pages + p];
-    const uint4* st = reinterpret_cast<const uint4*>(kv.stats) + ((size_t)phys * lp.Hkv + hk) * lp.g * 2 * (kHeadDim / 8);
+    uint4* st = reinterpret_cast<uint4*>(kv.stats) + ((size_t)phys * lp.Hkv + hk) * lp.g * 2 * (kHeadDim / 8);
+    const int fresh_below = stats_valid_len ? stats_valid_len[b] : L;  // stored statistics cover tokens below this
     float best = -INFINITY;
     for (int j = 0; j < lp.g; ++j) {
-        if (p * lp.NP + j * lp.NL >= L) break;  // logical pages without a valid token
-        uint4 mx = st[(size_t)(j * 2) * (kHeadDim / 8) + c];
-        uint4 mn = st[(size_t)(j * 2 + 1) * (kHeadDim / 8) + c];
+        const int lo = p * lp.NP + j * lp.NL;
+        if (lo >= L) break;  // logical pages without a valid token
+        uint4 mx, mn;
+        if (min(lo + lp.NL, L) > fresh_below) {
+            // tokens arrived since the statistics were last brought up to date: rebuild this logical
+            // page's rows from its keys (lane c owns channels 8c .. 8c+7), use them and store them
+            const uint4* keys = reinterpret_cast<const uint4*>(kv.k_pool) +
+                                (((size_t)phys * lp.Hkv + hk) * lp.NP + (lo - p * lp.NP)) * (kHeadDim / 8) + c;
+            float vmax[8], vmin[8];
+#pragma unroll
+            for (int i = 0; i < 8; ++i) {
+                vmax[i] = -INFINITY;
+                vmin[i] = INFINITY;
+            }
+            const int cnt = min(lp.NL, L - lo);
+            for (int t0 = 0; t0 < cnt; t0 += 8) {  // eight rows requested together
+                uint4 x[8];
+#pragma unroll
+                for (int u = 0; u < 8; ++u) x[u] = keys[(size_t)min(t0 + u, cnt - 1) * (kHeadDim / 8)];  // a repeated row changes nothing
+#pragma unroll
+                for (int u = 0; u < 8; ++u) {
+                    const uint32_t w[4] = {x[u].x, x[u].y, x[u].z, x[u].w};
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) {
+                        const float a = Elem<T>::lo(w[i]), d = Elem<T>::hi(w[i]);
+                        vmax[2 * i] = fmaxf(vmax[2 * i], a);
+                        vmin[2 * i] = fminf(vmin[2 * i], a);
+                        vmax[2 * i + 1] = fmaxf(vmax[2 * i + 1], d);
+                        vmin[2 * i + 1] = fminf(vmin[2 * i + 1], d);
+                    }
+                }
+            }
+            mx = make_uint4(Elem<T>::pack(vmax[0], vmax[1]), Elem<T>::pack(vmax[2], vmax[3]),
+                            Elem<T>::pack(vmax[4], vmax[5]), Elem<T>::pack(vmax[6], vmax[7]));
+            mn = make_uint4(Elem<T>::pack(vmin[0], vmin[1]), Elem<T>::pack(vmin[2], vmin[3]),
+                            Elem<T>::pack(vmin[4], vmin[5]), Elem<T>::pack(vmin[6], vmin[7]));
+            st[(size_t)(j * 2) * (kHeadDim / 8) + c] = mx;
+            st[(size_t)(j * 2 + 1) * (kHeadDim / 8) + c] = mn;
+        } else {
+            mx = st[(size_t)(j * 2) * (kHeadDim / 8) + c];
+            mn = st[(size_t)(j * 2 + 1) * (kHeadDim / 8) + c];
+        }
         const uint32_t wx[4] = {mx.x, mx.y, mx.z, mx.w};
         const uint32_t wn[4] = {mn.x, mn.y, mn.z, mn.w};
 #pragma unroll
@@ -236,14 +277,15 @@ __global__ __launch_bounds__(kTopkThreads) void topk_pages_kernel(LayerParams lp
 }
 
 template <class T>
-hipError_t launch_score(const LayerParams& lp, const PagedParams& kv, const void* q, float* scores,
-                        const HeadList& selecting, hipStream_t stream) {
+hipError_t launch_score(const LayerParams& lp, const PagedParams& kv, const void* q, const int* stats_valid_len,
+                        float* scores, const HeadList& selecting, hipStream_t stream) {
     dim3 grid(ceil_div(kv.max_pages, kPagesPerBlock), selecting.count, kv.batch);
     dim3 block(kScoreThreads);
     const uint4* q4 = reinterpret_cast<const uint4*>(q);
 #define LSERVE_SCORE_CASE(N)                                                                                   \
     case N:                                                                                                    \
-        hipLaunchKernelGGL((page_score_kernel<T, N>), grid, block, 0, stream, lp, kv, q4, scores, selecting);  \
+        hipLaunchKernelGGL((page_score_kernel<T, N>), grid, block, 0, stream, lp, kv, q4, stats_valid_len, scores, \
+                           selecting);                                                                     \
         break;
     switch (lp.group) {
         LSERVE_SCORE_CASE(1)
@@ -264,12 +306,12 @@ hipError_t launch_score(const LayerParams& lp, const PagedParams& kv, const void
 }  // namespace
 
 hipError_t launch_select_pages(int dtype, const LayerParams& lp, const PagedParams& kv, const void* q,
-                               int budget_pages, int* sel_pages, int* sel_count, int* sel_seq_len,
+                               const int* stats_valid_len, int budget_pages, int* sel_pages, int* sel_count, int* sel_seq_len,
                                float* scores, bool scores_is_user_buffer, const HeadList& selecting,
                                hipStream_t stream) {
     if (selecting.count > 0) {
-        hipError_t e = dtype == 0 ? launch_score<F16>(lp, kv, q, scores, selecting, stream)
-                                  : launch_score<BF16>(lp, kv, q, scores, selecting, stream);
+        hipError_t e = dtype == 0 ? launch_score<F16>(lp, kv, q, stats_valid_len, scores, selecting, stream)
+                                  : launch_score<BF16>(lp, kv, q, stats_valid_len, scores, selecting, stream);
         if (e != hipSuccess) return e;
     }
     dim3 grid(lp.Hkv, kv.batch);

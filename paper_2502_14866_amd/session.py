@@ -1,9 +1,9 @@
 """Host-side decode loop with reusable page selection (Sec. 3.5.3).
 
 The selector runs on the first step of every chunk of C decode steps and its index table is
-reused for the other C - 1 steps.  Right before a selector run the key statistics of the logical
-pages that received tokens since the previous run are refreshed; every step runs the sparse decode
-kernel.  This class only owns buffers and
+reused for the other C - 1 steps.  The key statistics of the logical pages that received tokens since
+the previous run are refreshed by the selector run itself (inside the scoring kernel) or, optionally,
+by a separate launch right before it; every step runs the sparse decode kernel.  This class only owns buffers and
 calls the C-ABI entry points in that order; all arithmetic happens in the HIP kernels.
 """
 from __future__ import annotations
@@ -19,7 +19,8 @@ class DecodeSession:
     def __init__(self, k_pool: torch.Tensor, v_pool: torch.Tensor, page_table: torch.Tensor,
                  num_q_heads: int, streaming_flags: Sequence[int], sink_tokens: int, local_tokens: int,
                  budget_tokens: int, logical_page_size: int = 16, reuse_interval: int = 4,
-                 sm_scale: float = 0.0, want_scores: bool = False, want_lse: bool = False):
+                 sm_scale: float = 0.0, want_scores: bool = False, want_lse: bool = False,
+                 fused_stats: bool = True):
         dev = k_pool.device
         num_pages, hkv, page_size, head_dim = k_pool.shape
         batch, max_pages = page_table.shape
@@ -47,6 +48,8 @@ class DecodeSession:
         self.out = torch.empty((batch, num_q_heads, head_dim), dtype=k_pool.dtype, device=dev)
         self.lse = torch.empty((batch, num_q_heads), dtype=torch.float32, device=dev) if want_lse else None
         self.steps_since_selection: Optional[int] = None
+        # True: the selector rebuilds the stale logical pages itself; False: a separate statistics launch
+        self.fused_stats = fused_stats
         # Key statistics are consumed only by the selector, so the logical pages touched since the
         # last selector run are refreshed in one call right before the next run.
         self._stats_from: Optional[torch.Tensor] = None
@@ -67,9 +70,11 @@ class DecodeSession:
         tail_pages = 1 if max_new_tokens == 1 else (max_new_tokens + np_ - 1) // np_ + 1
         B.lserve_build_page_stats(self.desc, self.kv, prev_seq_lens, tail_pages)
 
-    def select(self, q: torch.Tensor) -> None:
+    def select(self, q: torch.Tensor, stats_valid_len: Optional[torch.Tensor] = None) -> None:
+        """Run the selector.  With `stats_valid_len` (device int32 [batch]) the statistics of the logical
+        pages holding tokens at or above it are rebuilt inside the scoring kernel."""
         B.lserve_select_pages(self.desc, self.kv, q, self.budget_tokens, self.sel_pages, self.sel_count,
-                              self.sel_seq_len, self.scores, self.ws_select)
+                              self.sel_seq_len, self.scores, self.ws_select, stats_valid_len=stats_valid_len)
         self.steps_since_selection = 0
 
     def decode(self, q: torch.Tensor) -> torch.Tensor:
@@ -90,9 +95,12 @@ class DecodeSession:
             self._stats_from = prev_seq_lens
         self._stats_tokens += 1
         if self.steps_since_selection is None or self.steps_since_selection >= self.reuse_interval:
-            self.update_stats_tail(self._stats_from, self._stats_tokens)
+            if self.fused_stats:
+                self.select(q, stats_valid_len=self._stats_from)
+            else:
+                self.update_stats_tail(self._stats_from, self._stats_tokens)
+                self.select(q)
             self._stats_from, self._stats_tokens = seq_lens, 0
-            self.select(q)
         self.steps_since_selection += 1
         return self.decode(q) if run_decode else self.out  # run_decode=False: selector side only (timing)
 

@@ -103,6 +103,9 @@ def test_invalid_arguments_are_rejected_on_the_host(L):
     assert _rc(lambda: L.lserve_select_pages(desc(), kv, q, 256, sel, cnt, ssl, None, ws[:16], stream)) == -3
     # misaligned pointer
     assert _rc(lambda: L.lserve_select_pages(desc(), kv, q.view(-1)[1:], 256, sel, cnt, ssl, None, ws, stream)) == -1
+    # the fused statistics refresh reads keys: the key pool must be given
+    nok = L.PagedKV(None, None, kv.stats, kv.page_table, kv.seq_lens)
+    assert _rc(lambda: L.lserve_select_pages(desc(), nok, q, 256, sel, cnt, ssl, None, ws, stream, stats_valid_len=ssl)) == -1
     # decode: selecting head present but no selection given; workspace missing
     assert _rc(lambda: L.lserve_sparse_decode(desc(), kv, q, None, None, None, out, None, ws, stream)) == -1
     assert _rc(lambda: L.lserve_sparse_decode(desc(), kv, q, sel, cnt, ssl, out, None, None, stream)) == -3

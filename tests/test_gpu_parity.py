@@ -293,15 +293,18 @@ def test_hip_graph_replays_of_a_decode_episode_equal_the_eager_run():
         assert torch.equal(sess.sel_pages, sel_eager)
 
 
-def test_session_step_loop_with_lazy_statistics_matches_oracle():
-    """DecodeSession.step refreshes the statistics only right before a selector run; the selection made
-    then and every step's output must still match the oracle."""
+@pytest.mark.parametrize("fused_stats", [True, False])
+def test_session_step_loop_with_lazy_statistics_matches_oracle(fused_stats):
+    """DecodeSession.step refreshes the statistics only at a selector run (inside the scoring kernel, or by a
+    separate launch right before it); the statistics left behind, the selection made then and every step's
+    output must still match the oracle."""
     L = _lib()
     dev = torch.device("cuda:0")
     w = small_decode_workload(batch=3, lengths=(1000, 127, 2500), decode_steps=9, reuse_interval=4,
                               budget_tokens=512)
     inp = make_decode_inputs(w)
     sess = _session(L, w, inp, dev)
+    sess.fused_stats = fused_stats
     flags = w.streaming_flags()
     lens = torch.zeros((w.decode_steps + 1, 4), dtype=torch.int32, device=dev)
     for t in range(w.decode_steps + 1):
@@ -321,6 +324,40 @@ def test_session_step_loop_with_lazy_statistics_matches_oracle():
                                       sess.sel_pages.cpu().numpy(), sess.sel_count.cpu().numpy(),
                                       sess.sel_seq_len.cpu().numpy(), flags, w.sink_tokens, w.local_tokens)
         assert_attention_close(out, ref, f"session step {t}")
+
+
+def test_selector_rebuilds_every_stale_logical_page_itself():
+    """stats_valid_len = 0, a page boundary and the current length: the selector's own statistics pass must
+    leave the same statistics, scores and selection as a full rebuild followed by a plain selector run."""
+    L = _lib()
+    dev = torch.device("cuda:0")
+    w = small_decode_workload(batch=3, lengths=(1500, 640, 2100), budget_tokens=512, dtype="bf16")
+    inp = make_decode_inputs(w)
+    seq_cpu = inp.seq_lens_at(0)
+    q = inp.q[0].to(dev)
+    ref = _session(L, w, inp, dev)
+    ref.set_seq_lens(seq_cpu.to(dev))
+    ref.build_stats_full()
+    ref.select(q)
+    got = _session(L, w, inp, dev)
+    got.set_seq_lens(seq_cpu.to(dev))
+    got.build_stats_full()
+    valid = torch.tensor([0, 640, int(seq_cpu[2]), 0], dtype=torch.int32, device=dev)[:3]
+    # spoil everything the selector is told to rebuild, so that reading a stored row there would show
+    for b in range(3):
+        if int(valid[b]) >= int(seq_cpu[b]):
+            continue  # nothing is stale for this sequence
+        lo_page = int(valid[b]) // w.page_size
+        pages = inp.page_table[b, lo_page:(int(seq_cpu[b]) + w.page_size - 1) // w.page_size].long().to(dev)
+        lo_logical = (int(valid[b]) % w.page_size) // w.logical_page_size
+        got.stats[pages[1:]] = float("nan")
+        if len(pages):
+            got.stats[pages[0], :, lo_logical:] = float("nan")
+    got.select(q, stats_valid_len=valid)
+    torch.cuda.synchronize()
+    _check_stats(w, inp, got, seq_cpu)
+    assert torch.equal(got.sel_pages, ref.sel_pages) and torch.equal(got.sel_count, ref.sel_count)
+    assert torch.equal(got.scores, ref.scores)
 
 
 # ---- KV write-back with fused statistics (Sec. 3.2, Sec. 3.5.2) ---------------------------------
