@@ -453,7 +453,7 @@ def run_profile_only(args, torch, L, sess, inp, len_table, w, dev):
         if args.profile_only == "decode":
             sess.decode(inp.q[t])
         elif args.profile_only == "select":
-            sess.select(inp.q[t])
+            sess.select(inp.q[t], stats_valid_len=len_table[t, :B])  # one stale token per sequence, as in the decode loop
         else:
             sess.update_stats_tail(len_table[t, :B], 1)
     torch.cuda.synchronize()
