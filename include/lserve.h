@@ -80,18 +80,37 @@ typedef struct lserve_attn_desc {
 } lserve_attn_desc;
 
 /*
- * Paged KV cache (Sec. 2.1 "Paged Attention"; Sec. 3.5.2 for the statistics).
+ * Paged KV cache (Sec. 2.1 "Paged Attention"; Sec. 3.5.2 for the statistics; Sec. 3.2 for the
+ * two-way cache).
  * Token t of sequence b is slot t % N_P of physical page page_table[b][t / N_P].
+ *
+ * One pool (pool_heads == 0 or Hkv, k_pool_stream == NULL): every KV head lives in k_pool / v_pool.
+ *
+ * Two-way cache (Sec. 3.2: dense heads and streaming heads keep separate caches, the streaming one
+ * holding only sink and local tokens): set pool_heads to the number of non-streaming KV heads; k_pool,
+ * v_pool and stats then hold only those heads, in KV-head order.  Streaming heads live in
+ * k_pool_stream / v_pool_stream, [num_pages_stream][Hs][N_P][D] with Hs the number of streaming heads
+ * (KV-head order), through a ring of s + w pages per sequence: the page at position p of the sequence
+ * (p = t / N_P) is ring slot r(p) = p for p < s, s + (p - s) % w otherwise, stored in physical page
+ * ring_table[b][r(p)].  A local page is overwritten by the page w positions later, so at length L_b
+ * only pages p < s and p >= P_b - w are present, which is all a streaming head attends (Sec. 3.1).
+ * k_pool_stream may also be given next to a main pool that holds every head (pool_heads == Hkv):
+ * the streaming heads are then read from and written to the ring only.
  */
 typedef struct lserve_paged_kv {
-    void *k_pool;              /* device, [num_pages][Hkv][N_P][D] */
-    void *v_pool;              /* device, [num_pages][Hkv][N_P][D] */
-    void *stats;               /* device, [num_pages][Hkv][g][2][D]; [..][0][:] = max, [..][1][:] = min */
+    void *k_pool;              /* device, [num_pages][pool_heads][N_P][D] */
+    void *v_pool;              /* device, [num_pages][pool_heads][N_P][D] */
+    void *stats;               /* device, [num_pages][pool_heads][g][2][D]; [..][0][:] = max, [..][1][:] = min */
     const int32_t *page_table; /* device, [batch][max_pages_per_seq], physical page ids in [0, num_pages) */
     const int32_t *seq_lens;   /* device, [batch], 1 <= L_b <= max_pages_per_seq * N_P */
     int32_t batch;
     int32_t max_pages_per_seq;
     int32_t num_pages;
+    int32_t pool_heads;        /* 0 = Hkv; otherwise Hkv or the number of non-streaming KV heads */
+    void *k_pool_stream;       /* device, [num_pages_stream][Hs][N_P][D], or NULL */
+    void *v_pool_stream;       /* device, same shape, or NULL (both or neither) */
+    const int32_t *ring_table; /* device, [batch][s + w], page ids in [0, num_pages_stream) */
+    int32_t num_pages_stream;
 } lserve_paged_kv;
 
 /*

@@ -51,6 +51,9 @@ class _CPagedKV(ctypes.Structure):
         ("k_pool", ctypes.c_void_p), ("v_pool", ctypes.c_void_p), ("stats", ctypes.c_void_p),
         ("page_table", ctypes.c_void_p), ("seq_lens", ctypes.c_void_p),
         ("batch", ctypes.c_int32), ("max_pages_per_seq", ctypes.c_int32), ("num_pages", ctypes.c_int32),
+        ("pool_heads", ctypes.c_int32),
+        ("k_pool_stream", ctypes.c_void_p), ("v_pool_stream", ctypes.c_void_p), ("ring_table", ctypes.c_void_p),
+        ("num_pages_stream", ctypes.c_int32),
     ]
 
 
@@ -121,14 +124,22 @@ class PagedKV:
     stats: Optional[torch.Tensor]
     page_table: torch.Tensor
     seq_lens: torch.Tensor
+    # two-way cache: heads per page of the main pool (0 = all KV heads) and the streaming heads' bounded pool
+    pool_heads: int = 0
+    k_pool_stream: Optional[torch.Tensor] = None
+    v_pool_stream: Optional[torch.Tensor] = None
+    ring_table: Optional[torch.Tensor] = None
 
     def c(self):
         num_pages = 0
         for t in (self.k_pool, self.v_pool, self.stats):
             if t is not None:
                 num_pages = t.shape[0]
+        num_pages_stream = 0 if self.k_pool_stream is None else self.k_pool_stream.shape[0]
         self._c = _CPagedKV(_ptr(self.k_pool), _ptr(self.v_pool), _ptr(self.stats), _ptr(self.page_table),
-                            _ptr(self.seq_lens), self.page_table.shape[0], self.page_table.shape[1], num_pages)
+                            _ptr(self.seq_lens), self.page_table.shape[0], self.page_table.shape[1], num_pages,
+                            self.pool_heads, _ptr(self.k_pool_stream), _ptr(self.v_pool_stream),
+                            _ptr(self.ring_table), num_pages_stream)
         return ctypes.byref(self._c)
 
 

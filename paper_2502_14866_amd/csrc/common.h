@@ -107,11 +107,32 @@ struct LayerParams {
 };
 
 struct PagedParams {
-    const void *k_pool, *v_pool;
+    const void *k_pool, *v_pool;      // main pool, pool_heads KV heads per page
     void* stats;
     const int* page_table;
     const int* seq_lens;
     int batch, max_pages, num_pages;
+    int pool_heads;
+    const void *k_stream, *v_stream;  // bounded pool of the streaming heads (Sec. 3.2), or null
+    const int* ring_table;            // [batch][ring]
+    int stream_heads, ring;           // heads per page of that pool; ring = s + w slots per sequence
 };
+
+// Ring slot of the page at position p of a streaming head's sequence: sink pages keep their place,
+// local pages reuse w slots in turn.
+__device__ __forceinline__ int ring_slot(const LayerParams& lp, int p) {
+    return p < lp.sink_pages ? p : lp.sink_pages + (p - lp.sink_pages) % lp.local_pages;
+}
+// Does KV head hk live in the bounded streaming pool?
+__device__ __forceinline__ bool in_stream_pool(const LayerParams& lp, const PagedParams& kv, int hk) {
+    return kv.k_stream != nullptr && ((lp.streaming_mask >> hk) & 1ull);
+}
+// Index of KV head hk inside the pages of the pool that stores it: pools keep their heads in KV-head
+// order, so the index is the number of lower heads of the same pool.
+__device__ __forceinline__ int pool_rank(const LayerParams& lp, const PagedParams& kv, int hk, bool ring) {
+    const unsigned long long below = (1ull << hk) - 1ull;
+    if (ring) return __popcll(lp.streaming_mask & below);
+    return kv.pool_heads == lp.Hkv ? hk : __popcll(~lp.streaming_mask & below);
+}
 
 }  // namespace lserve

@@ -51,7 +51,9 @@ int make_layer(const lserve_attn_desc* d, LayerParams* lp) {
     return LSERVE_OK;
 }
 
-int make_paged(const lserve_paged_kv* kv, bool need_k, bool need_v, bool need_stats, PagedParams* pp) {
+// need_stream: the call touches streaming heads, so every one of them must live in some pool.
+int make_paged(const lserve_paged_kv* kv, const LayerParams& lp, bool need_k, bool need_v, bool need_stats,
+               bool need_stream, PagedParams* pp) {
     if (!kv || !kv->page_table || !kv->seq_lens) return LSERVE_ERR_INVALID_ARG;
     if (kv->batch <= 0 || kv->max_pages_per_seq <= 0 || kv->num_pages <= 0) return LSERVE_ERR_INVALID_ARG;
     if (kv->batch > 65535) return LSERVE_ERR_UNSUPPORTED;
@@ -67,6 +69,24 @@ int make_paged(const lserve_paged_kv* kv, bool need_k, bool need_v, bool need_st
     pp->batch = kv->batch;
     pp->max_pages = kv->max_pages_per_seq;
     pp->num_pages = kv->num_pages;
+    int n_stream = 0;
+    for (int h = 0; h < lp.Hkv; ++h) n_stream += (int)((lp.streaming_mask >> h) & 1ull);
+    const int n_dense = lp.Hkv - n_stream;
+    pp->pool_heads = kv->pool_heads == 0 ? lp.Hkv : kv->pool_heads;
+    if (pp->pool_heads != lp.Hkv && pp->pool_heads != n_dense) return LSERVE_ERR_INVALID_ARG;
+    if ((kv->k_pool_stream == nullptr) != (kv->v_pool_stream == nullptr)) return LSERVE_ERR_INVALID_ARG;
+    pp->k_stream = kv->k_pool_stream;
+    pp->v_stream = kv->v_pool_stream;
+    pp->ring_table = kv->ring_table;
+    pp->stream_heads = n_stream;
+    pp->ring = lp.sink_pages + lp.local_pages;
+    if (pp->k_stream) {
+        if (!kv->ring_table || kv->num_pages_stream <= 0 || n_stream == 0) return LSERVE_ERR_INVALID_ARG;
+        if (!aligned16(kv->k_pool_stream) || !aligned16(kv->v_pool_stream) || !aligned16(kv->ring_table))
+            return LSERVE_ERR_INVALID_ARG;
+    }
+    const bool main_holds_all = pp->pool_heads == lp.Hkv;
+    if (need_stream && n_stream > 0 && !main_holds_all && !pp->k_stream) return LSERVE_ERR_INVALID_ARG;
     return LSERVE_OK;
 }
 
@@ -92,7 +112,7 @@ int lserve_build_page_stats(const lserve_attn_desc* desc, const lserve_paged_kv*
     PagedParams pp;
     int rc = make_layer(desc, &lp);
     if (rc) return rc;
-    rc = make_paged(kv, true, false, true, &pp);
+    rc = make_paged(kv, lp, true, false, true, false, &pp);
     if (rc) return rc;
     if (max_tail_pages < 0 || !aligned16(start_pos)) return LSERVE_ERR_INVALID_ARG;
     const int tail = (max_tail_pages == 0 || max_tail_pages > pp.max_pages) ? pp.max_pages : max_tail_pages;
@@ -106,7 +126,7 @@ int lserve_append_kv(const lserve_attn_desc* desc, const lserve_paged_kv* kv, co
     PagedParams pp;
     int rc = make_layer(desc, &lp);
     if (rc) return rc;
-    rc = make_paged(kv, true, true, selecting_heads(lp).count > 0, &pp);
+    rc = make_paged(kv, lp, true, true, selecting_heads(lp).count > 0, true, &pp);
     if (rc) return rc;
     if (!k_new || !v_new || !cu_new || !start_pos || max_new_per_seq <= 0) return LSERVE_ERR_INVALID_ARG;
     if (!aligned16(k_new) || !aligned16(v_new) || !aligned16(cu_new) || !aligned16(start_pos)) return LSERVE_ERR_INVALID_ARG;
@@ -122,7 +142,7 @@ int lserve_select_pages(const lserve_attn_desc* desc, const lserve_paged_kv* kv,
     PagedParams pp;
     int rc = make_layer(desc, &lp);
     if (rc) return rc;
-    rc = make_paged(kv, stats_valid_len != nullptr, false, true, &pp);
+    rc = make_paged(kv, lp, stats_valid_len != nullptr, false, true, false, &pp);
     if (rc) return rc;
     if (!q || !sel_pages || !sel_count || !sel_seq_len) return LSERVE_ERR_INVALID_ARG;
     if (!aligned16(q) || !aligned16(stats_valid_len) || !aligned16(sel_pages) || !aligned16(sel_count) || !aligned16(sel_seq_len) ||
@@ -166,7 +186,7 @@ int lserve_sparse_decode(const lserve_attn_desc* desc, const lserve_paged_kv* kv
     PagedParams pp;
     int rc = make_layer(desc, &lp);
     if (rc) return rc;
-    rc = make_paged(kv, true, true, false, &pp);
+    rc = make_paged(kv, lp, true, true, false, true, &pp);
     if (rc) return rc;
     if (!q || !out) return LSERVE_ERR_INVALID_ARG;
     const bool any_selecting = selecting_heads(lp).count > 0;

@@ -25,7 +25,8 @@ __global__ __launch_bounds__(kWave* kMaxLogical) void page_stats_kernel(LayerPar
 
     const int phys = kv.page_table[(size_t)b * kv.max_pages + p];
     const int r = lane / 16, c = lane % 16;
-    const uint4* slab = reinterpret_cast<const uint4*>(kv.k_pool) + ((size_t)phys * lp.Hkv + hk) * lp.NP * (kHeadDim / 8);
+    const size_t ph = (size_t)phys * kv.pool_heads + pool_rank(lp, kv, hk, false);  // (page, head) index inside the main pool
+    const uint4* slab = reinterpret_cast<const uint4*>(kv.k_pool) + ph * lp.NP * (kHeadDim / 8);
 
     float vmax[8], vmin[8];
 #pragma unroll
@@ -51,7 +52,7 @@ __global__ __launch_bounds__(kWave* kMaxLogical) void page_stats_kernel(LayerPar
         vmin[i] = rows4_min(vmin[i]);
     }
     if (r == 0) {
-        uint4* dst = reinterpret_cast<uint4*>(kv.stats) + ((((size_t)phys * lp.Hkv + hk) * lp.g + j) * 2) * (kHeadDim / 8);
+        uint4* dst = reinterpret_cast<uint4*>(kv.stats) + ((ph * lp.g + j) * 2) * (kHeadDim / 8);
         // max / min of stored values are stored values: the conversion back is exact
         dst[c] = make_uint4(Elem<T>::pack(vmax[0], vmax[1]), Elem<T>::pack(vmax[2], vmax[3]),
                             Elem<T>::pack(vmax[4], vmax[5]), Elem<T>::pack(vmax[6], vmax[7]));
@@ -81,10 +82,24 @@ __global__ __launch_bounds__(kWave* kMaxLogical) void append_kv_kernel(LayerPara
     const int t0 = max(lo, s), t1 = min(hi, e);
     if (t0 >= t1) return;
     const bool streaming = (lp.streaming_mask >> hk) & 1ull;
-    const int phys = kv.page_table[(size_t)b * kv.max_pages + p];
-    const size_t slab = ((size_t)phys * lp.Hkv + hk) * lp.NP * (kHeadDim / 8);
-    uint4* kdst = reinterpret_cast<uint4*>(const_cast<void*>(kv.k_pool)) + slab;
-    uint4* vdst = reinterpret_cast<uint4*>(const_cast<void*>(kv.v_pool)) + slab;
+    size_t ph;  // (page, head) index inside the pool that stores this head
+    uint4 *kdst, *vdst;
+    if (in_stream_pool(lp, kv, hk)) {
+        // bounded pool: only sink pages and the pages that are still local once all new tokens are in
+        // are stored; a local page lands on the ring slot of the page w positions before it
+        if (p >= lp.sink_pages && p < ceil_div(e, lp.NP) - lp.local_pages) return;
+        const int phys = kv.ring_table[(size_t)b * kv.ring + ring_slot(lp, p)];
+        ph = (size_t)phys * kv.stream_heads + pool_rank(lp, kv, hk, true);
+        kdst = reinterpret_cast<uint4*>(const_cast<void*>(kv.k_stream));
+        vdst = reinterpret_cast<uint4*>(const_cast<void*>(kv.v_stream));
+    } else {
+        const int phys = kv.page_table[(size_t)b * kv.max_pages + p];
+        ph = (size_t)phys * kv.pool_heads + pool_rank(lp, kv, hk, false);
+        kdst = reinterpret_cast<uint4*>(const_cast<void*>(kv.k_pool));
+        vdst = reinterpret_cast<uint4*>(const_cast<void*>(kv.v_pool));
+    }
+    kdst += ph * lp.NP * (kHeadDim / 8);
+    vdst += ph * lp.NP * (kHeadDim / 8);
 
     float vmax[8], vmin[8];
 #pragma unroll
@@ -116,7 +131,7 @@ __global__ __launch_bounds__(kWave* kMaxLogical) void append_kv_kernel(LayerPara
         vmin[i] = rows4_min(vmin[i]);
     }
     if (r == 0) {
-        uint4* st = reinterpret_cast<uint4*>(kv.stats) + ((((size_t)phys * lp.Hkv + hk) * lp.g + j) * 2) * (kHeadDim / 8);
+        uint4* st = reinterpret_cast<uint4*>(kv.stats) + ((ph * lp.g + j) * 2) * (kHeadDim / 8);
         if (lo < s) {  // the logical page already held tokens: fold the stored rows in
             const uint4 om = st[c], on = st[kHeadDim / 8 + c];
             const uint32_t wm[4] = {om.x, om.y, om.z, om.w}, wn[4] = {on.x, on.y, on.z, on.w};

@@ -58,7 +58,8 @@ __global__ __launch_bounds__(kScoreThreads) void page_score_kernel(LayerParams l
     }
 
     const int phys = kv.page_table[(size_t)b * kv.max_pages + p];
-    uint4* st = reinterpret_cast<uint4*>(kv.stats) + ((size_t)phys * lp.Hkv + hk) * lp.g * 2 * (kHeadDim / 8);
+    const size_t ph = (size_t)phys * kv.pool_heads + pool_rank(lp, kv, hk, false);  // (page, head) index inside the main pool
+    uint4* st = reinterpret_cast<uint4*>(kv.stats) + ph * lp.g * 2 * (kHeadDim / 8);
     const int fresh_below = stats_valid_len ? stats_valid_len[b] : L;  // stored statistics cover tokens below this
     float best = -INFINITY;
     for (int j = 0; j < lp.g; ++j) {
@@ -69,7 +70,7 @@ __global__ __launch_bounds__(kScoreThreads) void page_score_kernel(LayerParams l
             // tokens arrived since the statistics were last brought up to date: rebuild this logical
             // page's rows from its keys (lane c owns channels 8c .. 8c+7), use them and store them
             const uint4* keys = reinterpret_cast<const uint4*>(kv.k_pool) +
-                                (((size_t)phys * lp.Hkv + hk) * lp.NP + (lo - p * lp.NP)) * (kHeadDim / 8) + c;
+                                (ph * lp.NP + (lo - p * lp.NP)) * (kHeadDim / 8) + c;
             float vmax[8], vmin[8];
 #pragma unroll
             for (int i = 0; i < 8; ++i) {

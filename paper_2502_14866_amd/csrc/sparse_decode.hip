@@ -405,9 +405,18 @@ __global__ __launch_bounds__(kDecodeThreads) void sparse_decode_kernel(
     const int lane = threadIdx.x % kWave, wave = threadIdx.x / kWave;
     const int r = lane / 16, c = lane % 16;
     const int tok0 = wave * (NP / 4);
+    const size_t slab = (size_t)NP * (kHeadDim / 8);  // uint4 per (page, head)
     const uint4* kpool = reinterpret_cast<const uint4*>(kv.k_pool);
     const uint4* vpool = reinterpret_cast<const uint4*>(kv.v_pool);
-    const size_t slab = (size_t)NP * (kHeadDim / 8);  // uint4 per (page, head)
+    const uint4* kstream = reinterpret_cast<const uint4*>(kv.k_stream);
+    const uint4* vstream = reinterpret_cast<const uint4*>(kv.v_stream);
+    // slab of (physical page, KV head): streaming heads may live in their own bounded pool (Sec. 3.2)
+    auto slab_of = [&](int phys, int hk, const uint4*& kslab, const uint4*& vslab) {
+        const bool ring = in_stream_pool(lp, kv, hk);
+        const size_t o = ((size_t)phys * (ring ? kv.stream_heads : kv.pool_heads) + pool_rank(lp, kv, hk, ring)) * slab;
+        kslab = (ring ? kstream : kpool) + o;
+        vslab = (ring ? vstream : vpool) + o;
+    };
 
     WaveState<N> st;
     int cur_list = -1, cur_b = 0, cur_hk = 0;
@@ -442,7 +451,9 @@ __global__ __launch_bounds__(kDecodeThreads) void sparse_decode_kernel(
             my_pos = i < head ? sel_entry : tail_start + (i - head);
             my_tail = tail_start - head;  // position of entry i >= head is my_tail + i
             if (i == nominal - 1 && len > nominal) my_extra = len - nominal;
-            if (my_valid) my_phys = kv.page_table[(size_t)b * kv.max_pages + my_pos];
+            if (my_valid)
+                my_phys = in_stream_pool(lp, kv, hk) ? kv.ring_table[(size_t)b * kv.ring + ring_slot(lp, my_pos)]
+                                                     : kv.page_table[(size_t)b * kv.max_pages + my_pos];
             // Validity is monotone in i, so if the first nominal entry of a split list inside this range
             // is past the real length the range holds nothing of the list: leave a neutral piece so that
             // the merge kernel needs no lengths.
@@ -460,20 +471,20 @@ __global__ __launch_bounds__(kDecodeThreads) void sparse_decode_kernel(
         Slabs<NP> cur, nxt;
         {
             const int idx0 = __builtin_ctzll(todo);
-            const size_t o0 = ((size_t)__builtin_amdgcn_readlane(my_phys, idx0) * lp.Hkv +
-                               __builtin_amdgcn_readlane(my_list, idx0) % lp.Hkv) * slab;
-            load_k<NP>(cur, kpool + o0, tok0, lane);
-            load_v<NP>(cur, vpool + o0, tok0, r, c);
+            const uint4 *k0, *v0;
+            slab_of(__builtin_amdgcn_readlane(my_phys, idx0), __builtin_amdgcn_readlane(my_list, idx0) % lp.Hkv, k0, v0);
+            load_k<NP>(cur, k0, tok0, lane);
+            load_v<NP>(cur, v0, tok0, r, c);
         }
         while (todo) {
             const int idx = __builtin_ctzll(todo);
             todo &= todo - 1;
             if (todo) {
                 const int idx1 = __builtin_ctzll(todo);
-                const size_t o1 = ((size_t)__builtin_amdgcn_readlane(my_phys, idx1) * lp.Hkv +
-                                   __builtin_amdgcn_readlane(my_list, idx1) % lp.Hkv) * slab;
-                load_k<NP>(nxt, kpool + o1, tok0, lane);
-                load_v<NP>(nxt, vpool + o1, tok0, r, c);
+                const uint4 *k1, *v1;
+                slab_of(__builtin_amdgcn_readlane(my_phys, idx1), __builtin_amdgcn_readlane(my_list, idx1) % lp.Hkv, k1, v1);
+                load_k<NP>(nxt, k1, tok0, lane);
+                load_v<NP>(nxt, v1, tok0, r, c);
             }
             const int list = __builtin_amdgcn_readlane(my_list, idx);
             if (list != cur_list) {  // uniform: the range crossed into the next list
@@ -495,9 +506,10 @@ __global__ __launch_bounds__(kDecodeThreads) void sparse_decode_kernel(
                 for (int e = 0; e < extra; ++e) {
                     const int epos = tail + nominal + e;
                     const int ephys = kv.page_table[(size_t)cur_b * kv.max_pages + epos];
-                    const size_t oe = ((size_t)ephys * lp.Hkv + cur_hk) * slab;
-                    load_k<NP>(cur, kpool + oe, tok0, lane);
-                    load_v<NP>(cur, vpool + oe, tok0, r, c);
+                    const uint4 *ke, *ve;  // only dense heads outgrow their nominal list: always the main pool
+                    slab_of(ephys, cur_hk, ke, ve);
+                    load_k<NP>(cur, ke, tok0, lane);
+                    load_v<NP>(cur, ve, tok0, r, c);
                     process_quarter_page<T, N, NP>(st, sm.q, sm.p[wave], cur, L - epos * NP, tok0, lane, lp.sm_scale_log2);
                 }
             }

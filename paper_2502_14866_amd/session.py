@@ -20,18 +20,24 @@ class DecodeSession:
                  num_q_heads: int, streaming_flags: Sequence[int], sink_tokens: int, local_tokens: int,
                  budget_tokens: int, logical_page_size: int = 16, reuse_interval: int = 4,
                  sm_scale: float = 0.0, want_scores: bool = False, want_lse: bool = False,
-                 fused_stats: bool = True):
+                 fused_stats: bool = True, k_pool_stream: Optional[torch.Tensor] = None,
+                 v_pool_stream: Optional[torch.Tensor] = None, ring_table: Optional[torch.Tensor] = None):
+        """k_pool / v_pool hold every KV head, or only the non-streaming ones when the streaming heads live in
+        the bounded pool k_pool_stream / v_pool_stream behind ring_table (two-way cache)."""
         dev = k_pool.device
-        num_pages, hkv, page_size, head_dim = k_pool.shape
+        num_pages, pool_heads, page_size, head_dim = k_pool.shape
+        hkv = len(streaming_flags)
         batch, max_pages = page_table.shape
         self.desc = B.AttnDesc(num_q_heads=num_q_heads, num_kv_heads=hkv, streaming_flags=streaming_flags,
                                head_dim=head_dim, page_size=page_size, logical_page_size=logical_page_size,
                                dtype=k_pool.dtype, sink_tokens=sink_tokens, local_tokens=local_tokens,
                                sm_scale=sm_scale)
         g = page_size // logical_page_size
-        self.stats = torch.zeros((num_pages, hkv, g, 2, head_dim), dtype=k_pool.dtype, device=dev)
+        self.stats = torch.zeros((num_pages, pool_heads, g, 2, head_dim), dtype=k_pool.dtype, device=dev)
         self.seq_lens = torch.zeros((batch,), dtype=torch.int32, device=dev)
-        self.kv = B.PagedKV(k_pool, v_pool, self.stats, page_table, self.seq_lens)
+        self.kv = B.PagedKV(k_pool, v_pool, self.stats, page_table, self.seq_lens,
+                            pool_heads=0 if pool_heads == hkv else pool_heads, k_pool_stream=k_pool_stream,
+                            v_pool_stream=v_pool_stream, ring_table=ring_table)
         self.budget_tokens = budget_tokens
         self.reuse_interval = max(1, reuse_interval)
         K = budget_tokens // page_size

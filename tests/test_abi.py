@@ -103,6 +103,16 @@ def test_invalid_arguments_are_rejected_on_the_host(L):
     assert _rc(lambda: L.lserve_select_pages(desc(), kv, q, 256, sel, cnt, ssl, None, ws[:16], stream)) == -3
     # misaligned pointer
     assert _rc(lambda: L.lserve_select_pages(desc(), kv, q.view(-1)[1:], 256, sel, cnt, ssl, None, ws, stream)) == -1
+    # two-way cache: a main pool without the streaming heads needs the bounded pool wherever streaming heads
+    # are touched; pool_heads must be Hkv or the number of non-streaming heads; the ring needs its table
+    dense_only = L.PagedKV(kv.k_pool[:, :1].contiguous(), kv.v_pool[:, :1].contiguous(), kv.stats[:, :1].contiguous(),
+                           kv.page_table, kv.seq_lens, pool_heads=1)
+    assert _rc(lambda: L.lserve_sparse_decode(desc(), dense_only, q, sel, cnt, ssl, out, None, ws, stream)) == -1
+    bad_heads = L.PagedKV(kv.k_pool, kv.v_pool, kv.stats, kv.page_table, kv.seq_lens, pool_heads=3)
+    assert _rc(lambda: L.lserve_build_page_stats(desc(), bad_heads, None, 0, stream)) == -1
+    no_table = L.PagedKV(kv.k_pool, kv.v_pool, kv.stats, kv.page_table, kv.seq_lens, k_pool_stream=kv.k_pool,
+                         v_pool_stream=kv.v_pool)
+    assert _rc(lambda: L.lserve_sparse_decode(desc(), no_table, q, sel, cnt, ssl, out, None, ws, stream)) == -1
     # the fused statistics refresh reads keys: the key pool must be given
     nok = L.PagedKV(None, None, kv.stats, kv.page_table, kv.seq_lens)
     assert _rc(lambda: L.lserve_select_pages(desc(), nok, q, 256, sel, cnt, ssl, None, ws, stream, stats_valid_len=ssl)) == -1

@@ -476,3 +476,114 @@ def test_append_then_select_and_decode_match_the_oracle_without_a_statistics_pas
                                             sess.sel_seq_len.cpu().numpy(), flags, w.sink_tokens, w.local_tokens)
         assert_attention_close(out, ref, f"append step {step}")
         assert_lse_close(sess.lse, lse_ref, f"append step {step}")
+
+
+# ---- two-way paged cache: dense heads in the main pool, streaming heads in a bounded ring (Sec. 3.2) ------
+
+def _ring_slot(p, s, w_):
+    return p if p < s else s + (p - s) % w_
+
+
+def _two_way_layout(w, inp, dev, seed=9):
+    """Main pool with the non-streaming heads only, an empty (NaN) bounded pool for the streaming heads and a
+    scattered ring table.  Pure re-indexing of the generator's one-pool inputs."""
+    dense = [h for h in range(w.num_kv_heads) if h not in w.streaming_kv_heads]
+    stream = list(w.streaming_kv_heads)
+    s = -(-w.sink_tokens // w.page_size)
+    w_ = -(-w.local_tokens // w.page_size)
+    ring = s + w_
+    g = torch.Generator().manual_seed(seed)
+    n_ring_pages = w.batch * ring + 3
+    ring_table = torch.randperm(n_ring_pages, generator=g)[: w.batch * ring].to(torch.int32).reshape(w.batch, ring)
+    k_main = inp.k_pool[:, dense].contiguous()
+    v_main = inp.v_pool[:, dense].contiguous()
+    shape = (n_ring_pages, len(stream), w.page_size, 128)
+    k_ring = torch.full(shape, float("nan"), dtype=inp.k_pool.dtype)
+    v_ring = torch.full(shape, float("nan"), dtype=inp.k_pool.dtype)
+    return dense, stream, s, w_, ring_table, k_main, v_main, k_ring, v_ring
+
+
+def test_two_way_cache_decode_and_append_equal_the_one_pool_path_and_the_oracle():
+    """Streaming heads read from / written to a ring of s + w pages per sequence, dense heads compacted in the
+    main pool: outputs must be bit-identical to the one-pool GPU path (same arithmetic, other addresses) and
+    within tolerance of the oracle; the ring is filled only through lserve_append_kv."""
+    L = _lib()
+    dev = torch.device("cuda:0")
+    w = small_decode_workload(batch=3, num_q_heads=8, num_kv_heads=4, streaming_kv_heads=(0, 2),
+                              lengths=(700, 64, 1500), decode_steps=8, reuse_interval=2, budget_tokens=256,
+                              sink_tokens=64, local_tokens=192)
+    inp = make_decode_inputs(w)
+    dense, stream, s, w_, ring_table, k_main, v_main, k_ring, v_ring = _two_way_layout(w, inp, dev)
+    flags = w.streaming_flags()
+    NP = w.page_size
+    one = _session(L, w, inp, dev)
+    from paper_2502_14866_amd.session import DecodeSession
+    two = DecodeSession(torch.zeros_like(k_main).to(dev), torch.zeros_like(v_main).to(dev), inp.page_table.to(dev),
+                        w.num_q_heads, flags, w.sink_tokens, w.local_tokens, w.budget_tokens,
+                        logical_page_size=w.logical_page_size, reuse_interval=w.reuse_interval, want_scores=True,
+                        want_lse=True, k_pool_stream=k_ring.to(dev), v_pool_stream=v_ring.to(dev),
+                        ring_table=ring_table.to(dev))
+    two.stats.fill_(float("nan"))
+
+    def append(start, n_new):
+        ks, vs = [], []
+        for b in range(w.batch):
+            pos = torch.arange(start[b], start[b] + n_new[b])
+            phys = inp.page_table[b].long()[pos // NP]
+            ks.append(inp.k_pool[phys, :, pos % NP])
+            vs.append(inp.v_pool[phys, :, pos % NP])
+        cu = np.concatenate([[0], np.cumsum(n_new)]).astype(np.int32)
+        L.lserve_append_kv(two.desc, two.kv, torch.cat(ks).contiguous().to(dev), torch.cat(vs).contiguous().to(dev),
+                           torch.from_numpy(cu).to(dev), torch.tensor(start, dtype=torch.int32, device=dev),
+                           max(max(n_new), 1))
+
+    have = [0] * w.batch
+    for step in range(w.decode_steps):
+        seq_cpu = inp.seq_lens_at(step)
+        want = [int(x) for x in seq_cpu]
+        if step == 0:  # the prompt in two chunks, so that local pages of the first chunk get overwritten
+            mid = [x // 2 for x in want]
+            append(have, mid)
+            append(mid, [a - m for a, m in zip(want, mid)])
+        else:
+            append(have, [a - h for a, h in zip(want, have)])
+        have = want
+        torch.cuda.synchronize()
+        # main pool: every token of the dense heads, bit for bit; ring: the pages a streaming head attends
+        km, kr = two.kv.k_pool.cpu(), two.kv.k_pool_stream.cpu()
+        vm, vr = two.kv.v_pool.cpu(), two.kv.v_pool_stream.cpu()
+        for b in range(w.batch):
+            Lb = want[b]
+            P = -(-Lb // NP)
+            pos = torch.arange(Lb)
+            phys = inp.page_table[b].long()[pos // NP]
+            assert torch.equal(km[phys, :, pos % NP].view(torch.int16), inp.k_pool[phys][:, dense][torch.arange(Lb), :, pos % NP].view(torch.int16))
+            assert torch.equal(vm[phys, :, pos % NP].view(torch.int16), inp.v_pool[phys][:, dense][torch.arange(Lb), :, pos % NP].view(torch.int16))
+            for p in [q for q in range(P) if q < s or q >= P - w_]:
+                n_tok = min(NP, Lb - p * NP)
+                src = int(inp.page_table[b, p])
+                dst = int(ring_table[b, _ring_slot(p, s, w_)])
+                assert torch.equal(kr[dst, :, :n_tok].view(torch.int16), inp.k_pool[src][stream][:, :n_tok].view(torch.int16)), (step, b, p)
+                assert torch.equal(vr[dst, :, :n_tok].view(torch.int16), inp.v_pool[src][stream][:, :n_tok].view(torch.int16)), (step, b, p)
+        seq = seq_cpu.to(dev)
+        q = inp.q[step].to(dev)
+        one.set_seq_lens(seq)
+        two.set_seq_lens(seq)
+        one.build_stats_full()
+        if step % w.reuse_interval == 0:
+            one.select(q)
+            two.select(q)  # statistics were kept current by the appends
+            assert torch.equal(one.sel_pages, two.sel_pages) and torch.equal(one.sel_count, two.sel_count)
+            assert torch.equal(one.scores, two.scores)
+        o1 = one.decode(q).clone()
+        o2 = two.decode(q)
+        assert torch.equal(o1.view(torch.int16), o2.view(torch.int16)), step
+        assert torch.equal(one.lse, two.lse)
+        ref, lse_ref = oracle.sparse_decode(inp.q[step], inp.k_pool, inp.v_pool, inp.page_table, seq_cpu,
+                                            two.sel_pages.cpu().numpy(), two.sel_count.cpu().numpy(),
+                                            two.sel_seq_len.cpu().numpy(), flags, w.sink_tokens, w.local_tokens)
+        assert_attention_close(o2, ref, f"two-way step {step}")
+        assert_lse_close(two.lse, lse_ref, f"two-way step {step}")
+    # statistics of the dense heads in the compacted layout equal the one-pool statistics
+    assert torch.equal(one.stats[:, dense].cpu().view(torch.int16)[inp.page_table[0, :5].long()],
+                       two.stats.cpu().view(torch.int16)[inp.page_table[0, :5].long()])
