@@ -18,6 +18,7 @@
  *                                      K highest pages under the token budget)
  *   - decode over an index table     : Sec. 3.6 (selected pages for dense heads, sink + local
  *                                      pages for streaming heads), Sec. 3.2 ("shorter page table")
+ *   - general block mask in prefill  : Sec. 3.1 / Sec. 3.4 (kept key tiles listed per query tile and head)
  *   - KV write-back                  : Sec. 3.2 / Sec. 2.1 (new tokens stored at their slots of the
  *                                      paged cache; statistics afterwards = the definition above
  *                                      evaluated at the new lengths)
@@ -384,6 +385,79 @@ void oracle_sparse_prefill_rows(const uint16_t *q, const uint16_t *k, const uint
             for (int c = 0; c < D; ++c) o[c] += pr * oracle_widen(vu[c], dtype);
         }
         if (lse) lse[r] = mx + log(denom);
+        free(score);
+    }
+}
+
+/* ---- prefill under a general block mask (Sec. 3.1: every tile is skipped or computed whole; Sec. 3.4:
+ *      the kernel walks whatever list of key tiles it is given) --------------------------------------- */
+/*
+ * As oracle_sparse_prefill_rows, but the kept tiles of query head h come from a list: head_mask[h] = m >= 0
+ * names mask m, whose row for query tile i of sequence b is cols[row_ptr[r] .. row_ptr[r + 1]) with
+ * r = m * rows_per_mask + q_tile_start[b] + i; key position u is allowed iff u <= t and tile(u) is listed in
+ * the row of tile(t).  head_mask[h] = -1 keeps the analytic mask (dense or streaming) of the other function.
+ * A row with no allowed key gives out = 0 and lse = -inf.
+ */
+void oracle_block_mask_prefill_rows(const uint16_t *q, const uint16_t *k, const uint16_t *v,
+                                    const int32_t *cu_seqlens, int batch, int H, int Hkv, int D, int dtype,
+                                    int T, int sink_tokens, int local_tokens,
+                                    const uint8_t *kv_head_is_streaming, double sm_scale,
+                                    const int32_t *head_mask, const int32_t *q_tile_start,
+                                    const int32_t *row_ptr, const int32_t *cols, int rows_per_mask,
+                                    const int32_t *rows_token, const int32_t *rows_head, int n_rows,
+                                    double *out, double *lse)
+{
+    int n = H / Hkv;
+    int s = ceil_div(sink_tokens, T);
+    int w = ceil_div(local_tokens, T);
+#pragma omp parallel for schedule(dynamic, 4)
+    for (int r = 0; r < n_rows; ++r) {
+        int tok = rows_token[r], h = rows_head[r], hk = h / n;
+        int b = 0;
+        while (b + 1 < batch && cu_seqlens[b + 1] <= tok) ++b;
+        int start = cu_seqlens[b];
+        int t = tok - start;
+        int m = head_mask[h];
+        int lo = 0, hi = 0;
+        if (m >= 0) {
+            int row = m * rows_per_mask + q_tile_start[b] + t / T;
+            lo = row_ptr[row];
+            hi = row_ptr[row + 1];
+        }
+        double *score = (double *)malloc(sizeof(double) * (size_t)(t + 1));
+        const uint16_t *qh = &q[((size_t)tok * H + h) * D];
+        double mx = -INFINITY;
+        for (int u = 0; u <= t; ++u) {
+            int allowed;
+            if (m >= 0) {
+                allowed = 0;
+                for (int e = lo; e < hi; ++e)
+                    if (cols[e] == u / T) allowed = 1;
+            } else {
+                allowed = !kv_head_is_streaming[hk] || (u / T < s) || (u / T > t / T - w);
+            }
+            if (!allowed) { score[u] = -INFINITY; continue; }
+            const uint16_t *ku = &k[((size_t)(start + u) * Hkv + hk) * D];
+            double dot = 0.0;
+            for (int c = 0; c < D; ++c)
+                dot += oracle_widen(qh[c], dtype) * oracle_widen(ku[c], dtype);
+            score[u] = dot * sm_scale;
+            if (score[u] > mx) mx = score[u];
+        }
+        double denom = 0.0;
+        for (int u = 0; u <= t; ++u)
+            if (score[u] != -INFINITY) denom += exp(score[u] - mx);
+        double *o = &out[(size_t)r * D];
+        for (int c = 0; c < D; ++c) o[c] = 0.0;
+        if (denom > 0.0) {
+            for (int u = 0; u <= t; ++u) {
+                if (score[u] == -INFINITY) continue;
+                double pr = exp(score[u] - mx) / denom;
+                const uint16_t *vu = &v[((size_t)(start + u) * Hkv + hk) * D];
+                for (int c = 0; c < D; ++c) o[c] += pr * oracle_widen(vu[c], dtype);
+            }
+        }
+        if (lse) lse[r] = denom > 0.0 ? mx + log(denom) : -INFINITY;
         free(score);
     }
 }

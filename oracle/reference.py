@@ -197,6 +197,34 @@ def sparse_prefill_rows(q: torch.Tensor, k: torch.Tensor, v: torch.Tensor, cu_se
     return out, lse
 
 
+def block_mask_prefill_rows(q: torch.Tensor, k: torch.Tensor, v: torch.Tensor, cu_seqlens,
+                            streaming_flags: Sequence[int], tile: int, sink_tokens: int, local_tokens: int,
+                            head_mask, q_tile_start, row_ptr, cols, rows_per_mask: int, rows_token, rows_head,
+                            sm_scale: Optional[float] = None):
+    """Prefill rows under a general block mask (CSR of kept key tiles per query tile, per mask; head_mask[h]
+    picks the mask of query head h, -1 = the analytic dense / streaming mask): (out [R,D] f64, lse [R])."""
+    total, H, D = q.shape
+    Hkv = k.shape[1]
+    cu = _i32(cu_seqlens)
+    rt, rh = _i32(rows_token), _i32(rows_head)
+    hm, qs, rp, cl = _i32(head_mask), _i32(q_tile_start), _i32(row_ptr), _i32(cols)
+    if cl.size == 0:
+        cl = np.zeros((1,), dtype=np.int32)
+    flags = _u8(streaming_flags)
+    out = np.zeros((rt.shape[0], D), dtype=np.float64)
+    lse = np.zeros((rt.shape[0],), dtype=np.float64)
+    scale = float(sm_scale) if sm_scale else 1.0 / float(np.sqrt(D))
+    qb, kb, vb = _bits(q), _bits(k), _bits(v)
+    _load().oracle_block_mask_prefill_rows(_p(qb), _p(kb), _p(vb), _p(cu), ctypes.c_int(cu.shape[0] - 1),
+                                           ctypes.c_int(H), ctypes.c_int(Hkv), ctypes.c_int(D),
+                                           ctypes.c_int(_dtype_code(q)), ctypes.c_int(tile),
+                                           ctypes.c_int(sink_tokens), ctypes.c_int(local_tokens), _p(flags),
+                                           ctypes.c_double(scale), _p(hm), _p(qs), _p(rp), _p(cl),
+                                           ctypes.c_int(rows_per_mask), _p(rt), _p(rh),
+                                           ctypes.c_int(rt.shape[0]), _p(out), _p(lse))
+    return out, lse
+
+
 def count_nonempty_tiles(n_tokens: int, tile: int, sink_tokens: int, local_tokens: int,
                          streaming: bool) -> int:
     return int(_load().oracle_count_nonempty_tiles(n_tokens, tile, sink_tokens, local_tokens,

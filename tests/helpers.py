@@ -55,3 +55,24 @@ def sub_problem(inp, seqs):
         needle_pos=None if inp.needle_pos is None else inp.needle_pos[list(seqs)],
         k_scale=inp.k_scale,
     )
+
+
+def block_mask_csr(masks, lengths, tile=64):
+    """CSR arrays of a list of block masks.
+
+    masks[m](b, i) -> iterable of kept key tiles (each <= i) of query tile i of sequence b.  Returns
+    (q_tile_start [B+1], row_ptr [M*R+1], cols, R) as int32 numpy arrays, rows ordered mask-major.
+    """
+    import numpy as np
+    n_tiles = [-(-int(l) // tile) for l in lengths]
+    q_tile_start = np.concatenate([[0], np.cumsum(n_tiles)]).astype(np.int32)
+    R = int(q_tile_start[-1])
+    row_ptr, cols = [0], []
+    for fn in masks:
+        for b, nt in enumerate(n_tiles):
+            for i in range(nt):
+                row = sorted(set(int(j) for j in fn(b, i)))
+                assert all(0 <= j <= i for j in row)
+                cols.extend(row)
+                row_ptr.append(len(cols))
+    return q_tile_start, np.asarray(row_ptr, dtype=np.int32), np.asarray(cols, dtype=np.int32), R

@@ -273,3 +273,72 @@ def test_block_counts_match_the_papers_printed_example_and_closed_forms():
         assert oracle.count_nonempty_tiles(n, T, sink, local, True) == closed
         assert oracle.count_nonempty_tiles(n, T, sink, local, False) == nt * (nt + 1) // 2
     assert oracle.count_nonempty_tiles(2048, 64, 64, 256, True) == 150
+
+
+# ---- prefill under a general block mask (Sec. 3.1, Sec. 3.4) --------------------------------------
+
+def _mask_rows(pin, w, lengths, masks, head_mask, tile=64):
+    from helpers import block_mask_csr
+    qts, rp, cl, R = block_mask_csr(masks, lengths, tile)
+    total = sum(lengths)
+    tok, head = _all_rows(total, w.num_q_heads)
+    out, lse = oracle.block_mask_prefill_rows(pin.q, pin.k, pin.v, pin.cu_seqlens, w.streaming_flags(), tile,
+                                              w.sink_tokens, w.local_tokens, head_mask, qts, rp, cl, R, tok, head)
+    return out.reshape(total, w.num_q_heads, w.head_dim), lse.reshape(total, w.num_q_heads)
+
+
+def test_block_mask_with_every_lower_tile_is_dense_and_with_the_analytic_tiles_is_streaming():
+    w = _prefill_workload(batch=2, sink_tokens=64, local_tokens=128)
+    lengths = (150, 203)
+    pin = make_prefill_inputs(w, lengths=lengths)
+    total = sum(lengths)
+    tok, head = _all_rows(total, w.num_q_heads)
+    lower = lambda b, i: range(i + 1)
+    s, wl = 1, 2
+    lam = lambda b, i: [j for j in range(i + 1) if j < s or j > i - wl]
+    # mask 0 = all lower tiles for heads 0, 1 (KV head 0 is flagged streaming but the mask overrides it);
+    # mask 1 = the streaming tiles for heads 2, 3 (KV head 1 is flagged dense)
+    out, lse = _mask_rows(pin, w, lengths, [lower, lam], [0, 0, 1, 1])
+    dense, dl = oracle.sparse_prefill_rows(pin.q, pin.k, pin.v, pin.cu_seqlens, [0, 0], 64, w.sink_tokens,
+                                           w.local_tokens, tok, head)
+    strm, sl = oracle.sparse_prefill_rows(pin.q, pin.k, pin.v, pin.cu_seqlens, [1, 1], 64, w.sink_tokens,
+                                          w.local_tokens, tok, head)
+    dense, strm = dense.reshape(total, 4, -1), strm.reshape(total, 4, -1)
+    np.testing.assert_allclose(out[:, :2], dense[:, :2], rtol=0, atol=0)
+    np.testing.assert_allclose(out[:, 2:], strm[:, 2:], rtol=0, atol=0)
+    np.testing.assert_allclose(lse[:, :2], dl.reshape(total, 4)[:, :2], rtol=0, atol=0)
+    # head_mask = -1 falls back to the analytic mask of the flags
+    out2, _ = _mask_rows(pin, w, lengths, [lower], [-1, -1, -1, -1])
+    mixed, _ = oracle.sparse_prefill_rows(pin.q, pin.k, pin.v, pin.cu_seqlens, w.streaming_flags(), 64,
+                                          w.sink_tokens, w.local_tokens, tok, head)
+    np.testing.assert_allclose(out2, mixed.reshape(total, 4, -1), rtol=0, atol=0)
+
+
+def test_block_mask_rows_equal_textbook_attention_under_the_expanded_boolean_mask():
+    rng = np.random.default_rng(5)
+    w = _prefill_workload(batch=2, num_q_heads=2, num_kv_heads=1, streaming_kv_heads=())
+    lengths = (23, 17)
+    pin = make_prefill_inputs(w, lengths=lengths)
+    T = 4
+    kept = {}
+
+    def rnd(b, i):  # random subset of the lower tiles, always with the diagonal, different per sequence
+        if (b, i) not in kept:
+            kept[(b, i)] = [j for j in range(i) if rng.random() < 0.4] + [i]
+        return kept[(b, i)]
+
+    empty_diag = lambda b, i: [j for j in range(i) if j % 2 == 0]  # the first tile row keeps nothing at all
+    out, lse = _mask_rows(pin, w, lengths, [rnd, empty_diag], [0, 1], tile=T)
+    q, k, v = (x.to(torch.float64).numpy() for x in (pin.q, pin.k, pin.v))
+    start = 0
+    for b, n in enumerate(lengths):
+        for t in range(n):
+            for h, fn in ((0, rnd), (1, empty_diag)):
+                tiles = set(fn(b, t // T))
+                mask = np.array([(u <= t) and (u // T in tiles) for u in range(n)])
+                if not mask.any():
+                    assert np.all(out[start + t, h] == 0) and lse[start + t, h] == -np.inf
+                    continue
+                ref = _sdpa(q[start + t, h], k[start:start + n, 0], v[start:start + n, 0], mask=mask)
+                np.testing.assert_allclose(out[start + t, h], ref, rtol=1e-10, atol=1e-12)
+        start += n
