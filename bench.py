@@ -356,7 +356,33 @@ def bench_prefill(torch, L, dev, n_tokens):
     flops_stream = 4.0 * D * stream_tiles * T * T * n_stream  # executed tiles (diagonal tiles counted whole)
     flops_equiv = 4.0 * D * dense_pairs * (n_dense + n_stream)
     tf = (flops_dense + flops_stream) / (ms * 1e-3) / 1e12
+    # the same pattern given as explicit tile lists (general block mask): identical work, list walk instead of closed form
+    masked_ms = None
+    try:
+        import numpy as np
+        rows = [np.arange(i + 1, dtype=np.int32) for i in range(nt)]
+        rows += [np.asarray([j for j in range(i + 1) if j < s_t or j > i - w_t], dtype=np.int32) for i in range(nt)]
+        row_ptr = np.concatenate([[0], np.cumsum([len(r) for r in rows])]).astype(np.int32)
+        cols = np.concatenate(rows).astype(np.int32)
+        flags = w.streaming_flags()
+        head_mask = [1 if flags[h // n] else 0 for h in range(w.num_q_heads)]
+        i32 = lambda a: torch.as_tensor(np.asarray(a, dtype=np.int32)).to(dev)
+        mask = L.BlockMask(i32(head_mask), i32([0, nt]), i32(row_ptr), i32(cols), 2, nt)
+        ws_m = torch.empty((L.lserve_masked_prefill_workspace_bytes(desc, 1, n_tokens, n_tokens, 2, len(cols)),),
+                           dtype=torch.uint8, device=dev)
+        call_m = lambda: L.lserve_sparse_prefill_masked(desc, mask, pin.q, pin.k, pin.v, pin.cu_seqlens, n_tokens, out, None, ws_m)  # noqa: E731
+        call_m()
+        torch.cuda.synchronize()
+        e0.record()
+        for _ in range(reps):
+            call_m()
+        e1.record()
+        torch.cuda.synchronize()
+        masked_ms = e0.elapsed_time(e1) / reps
+    except Exception as e:  # reported, never fatal
+        masked_ms = repr(e)
     return {
+        "same_pattern_as_block_mask_ms": masked_ms,
         "workload": f"cfg3: prefill {n_tokens} tokens, bf16, {w.num_q_heads}/{w.num_kv_heads} heads, "
                     f"{n_stream} streaming + {n_dense} dense query heads",
         "ms": ms,

@@ -9,7 +9,8 @@
  *                            top-K physical pages under a token budget (Sec. 3.5.2)
  *   lserve_sparse_decode     paged decode attention over an index table (Sec. 3.6)
  * and, around them, lserve_append_kv: write-back of new K/V into the pages with the statistics
- * updated in the same pass (Sec. 3.2, Sec. 3.5.2).
+ * updated in the same pass (Sec. 3.2, Sec. 3.5.2), and lserve_sparse_prefill_masked: prefill under
+ * a caller-supplied block mask (Sec. 3.1, Sec. 3.4).
  *
  * Conventions common to every call
  *   - "device" pointers are HIP device memory owned by the caller; "host" pointers are ordinary
@@ -206,6 +207,45 @@ int lserve_sparse_prefill(const lserve_attn_desc *desc, const void *q, const voi
                           const int32_t *cu_seqlens, int32_t batch, int32_t total_tokens,
                           int32_t max_seqlen, void *out, float *lse_out, void *workspace,
                           size_t workspace_bytes, void *stream);
+
+/*
+ * Block-sparse prefill under a general block mask (Sec. 3.1: every tile of the attention map is skipped or
+ * computed whole; Sec. 3.4: the kernel walks whatever list of key tiles it is given, the analytic
+ * streaming pattern being one case).  A mask lists, for every 64-row query tile i of every sequence, the
+ * 64-key tiles it keeps, in CSR form; query head h uses mask head_mask[h], or the analytic mask of `desc`
+ * (dense or streaming, as in lserve_sparse_prefill) when head_mask[h] = -1.  Key u is attended by query t
+ * iff u <= t and tile(u) is listed in the row of tile(t); the diagonal tile, if listed, is causal inside.
+ * A query row whose tile row lists nothing gets out = 0 and lse = -inf.
+ *
+ *   head_mask      device [H], values in [-1, num_masks)
+ *   q_tile_start   device [batch + 1]: row of query tile 0 of sequence b inside one mask;
+ *                  q_tile_start[b + 1] - q_tile_start[b] = ceil(len_b / 64), q_tile_start[batch] = rows_per_mask
+ *   row_ptr        device [num_masks * rows_per_mask + 1]; row of (mask m, sequence b, tile i) is
+ *                  r = m * rows_per_mask + q_tile_start[b] + i, its entries cols[row_ptr[r] .. row_ptr[r + 1])
+ *   cols           device [nnz]: key tile indices inside the sequence, strictly ascending within a row;
+ *                  entries above the row's own tile index are ignored
+ *   workspace      device, >= lserve_masked_prefill_workspace_bytes(...)
+ * Other arguments as in lserve_sparse_prefill.  Data errors inside the CSR arrays (unsorted rows, row_ptr
+ * not monotone or beyond nnz) are not detected.  Unsupported: max_seqlen > 4194304.
+ */
+typedef struct lserve_block_mask {
+    const int32_t *head_mask;
+    const int32_t *q_tile_start;
+    const int32_t *row_ptr;
+    const int32_t *cols;
+    int32_t num_masks;
+    int32_t rows_per_mask;
+    int32_t nnz;
+} lserve_block_mask;
+
+int lserve_sparse_prefill_masked(const lserve_attn_desc *desc, const lserve_block_mask *mask, const void *q,
+                                 const void *k, const void *v, const int32_t *cu_seqlens, int32_t batch,
+                                 int32_t total_tokens, int32_t max_seqlen, void *out, float *lse_out,
+                                 void *workspace, size_t workspace_bytes, void *stream);
+
+/* Workspace of lserve_sparse_prefill_masked (0 on invalid arguments). */
+size_t lserve_masked_prefill_workspace_bytes(const lserve_attn_desc *desc, int32_t batch, int32_t total_tokens,
+                                             int32_t max_seqlen, int32_t num_masks, int32_t nnz);
 
 /*
  * Paged sparse decode (Eq. 1 over the pages of an index table; Sec. 3.6).

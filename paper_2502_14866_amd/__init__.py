@@ -15,7 +15,10 @@ from .binding import (  # noqa: F401
     PagedKV,
     library_path,
     load_library,
+    BlockMask,
     lserve_append_kv,
+    lserve_masked_prefill_workspace_bytes,
+    lserve_sparse_prefill_masked,
     lserve_build_page_stats,
     lserve_last_hip_error,
     lserve_select_pages,

@@ -24,6 +24,9 @@ EXPORTED_SYMBOLS = (
     "lserve_sparse_prefill",
     "lserve_sparse_decode",
     "lserve_append_kv",
+    "lserve_sparse_prefill_masked",
+    "lserve_masked_prefill_workspace_bytes",
+    "BlockMask",
     "lserve_workspace_bytes",
     "lserve_strerror",
     "lserve_last_hip_error",
@@ -57,6 +60,14 @@ class _CPagedKV(ctypes.Structure):
     ]
 
 
+class _CBlockMask(ctypes.Structure):
+    _fields_ = [
+        ("head_mask", ctypes.c_void_p), ("q_tile_start", ctypes.c_void_p), ("row_ptr", ctypes.c_void_p),
+        ("cols", ctypes.c_void_p),
+        ("num_masks", ctypes.c_int32), ("rows_per_mask", ctypes.c_int32), ("nnz", ctypes.c_int32),
+    ]
+
+
 def library_path() -> str:
     return _LIB_PATH
 
@@ -78,6 +89,11 @@ def load_library():
         lib.lserve_sparse_decode.argtypes = [dp, kp, vp, vp, vp, vp, i32, vp, vp, vp, sz, vp]
         lib.lserve_append_kv.argtypes = [dp, kp, vp, vp, vp, vp, i32, vp]
         lib.lserve_append_kv.restype = ctypes.c_int
+        mp = ctypes.POINTER(_CBlockMask)
+        lib.lserve_sparse_prefill_masked.argtypes = [dp, mp, vp, vp, vp, vp, i32, i32, i32, vp, vp, vp, sz, vp]
+        lib.lserve_sparse_prefill_masked.restype = ctypes.c_int
+        lib.lserve_masked_prefill_workspace_bytes.argtypes = [dp, i32, i32, i32, i32, i32]
+        lib.lserve_masked_prefill_workspace_bytes.restype = ctypes.c_size_t
         lib.lserve_workspace_bytes.argtypes = [ctypes.c_int, dp, i32, i32, i32, i32]
         lib.lserve_workspace_bytes.restype = sz
         lib.lserve_strerror.argtypes = [ctypes.c_int]
@@ -208,6 +224,44 @@ def lserve_sparse_prefill(desc: AttnDesc, q: torch.Tensor, k: torch.Tensor, v: t
                                                 cu_seqlens.shape[0] - 1, q.shape[0], max_seqlen, _ptr(out),
                                                 _ptr(lse_out), _ptr(workspace), ws_bytes, _stream(stream)),
            "lserve_sparse_prefill")
+
+
+@dataclass
+class BlockMask:
+    """Mirror of lserve_block_mask (device int32 tensors); keeps the tensors alive."""
+    head_mask: torch.Tensor
+    q_tile_start: torch.Tensor
+    row_ptr: torch.Tensor
+    cols: Optional[torch.Tensor]
+    num_masks: int
+    rows_per_mask: int
+
+    @property
+    def nnz(self) -> int:
+        return 0 if self.cols is None else int(self.cols.numel())
+
+    def c(self):
+        self._c = _CBlockMask(_ptr(self.head_mask), _ptr(self.q_tile_start), _ptr(self.row_ptr), _ptr(self.cols),
+                              self.num_masks, self.rows_per_mask, self.nnz)
+        return ctypes.byref(self._c)
+
+
+def lserve_masked_prefill_workspace_bytes(desc: AttnDesc, batch: int, total_tokens: int, max_seqlen: int,
+                                          num_masks: int, nnz: int) -> int:
+    return int(load_library().lserve_masked_prefill_workspace_bytes(desc.c(), batch, total_tokens, max_seqlen,
+                                                                    num_masks, nnz))
+
+
+def lserve_sparse_prefill_masked(desc: AttnDesc, mask: BlockMask, q: torch.Tensor, k: torch.Tensor, v: torch.Tensor,
+                                 cu_seqlens: torch.Tensor, max_seqlen: int, out: torch.Tensor,
+                                 lse_out: Optional[torch.Tensor] = None, workspace: Optional[torch.Tensor] = None,
+                                 stream=None) -> None:
+    ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    _check(load_library().lserve_sparse_prefill_masked(desc.c(), mask.c(), _ptr(q), _ptr(k), _ptr(v),
+                                                       _ptr(cu_seqlens), cu_seqlens.shape[0] - 1, q.shape[0],
+                                                       max_seqlen, _ptr(out), _ptr(lse_out), _ptr(workspace),
+                                                       ws_bytes, _stream(stream)),
+           "lserve_sparse_prefill_masked")
 
 
 def lserve_sparse_decode(desc: AttnDesc, kv: PagedKV, q: torch.Tensor, sel_pages: Optional[torch.Tensor],

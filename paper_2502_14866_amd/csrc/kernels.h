@@ -29,10 +29,21 @@ hipError_t launch_sparse_decode(int dtype, const LayerParams& lp, const PagedPar
                                 const int* sel_pages, const int* sel_count, const int* sel_seq_len,
                                 int sel_stride, void* out, float* lse_out, void* workspace, hipStream_t stream);
 
+// Caller-side description of a general block mask for prefill (device pointers).
+struct PrefillMaskArgs {
+    const int* head_mask;
+    const int* q_tile_start;
+    const int* row_ptr;
+    const int* cols;
+    int num_masks, rows_per_mask, nnz;
+};
+
 size_t prefill_workspace_bytes(const LayerParams& lp, int total_tokens, int batch);
+size_t masked_prefill_workspace_bytes(const LayerParams& lp, int total_tokens, int batch, int max_seqlen, int num_masks,
+                                      int nnz);
 
 hipError_t launch_sparse_prefill(int dtype, const LayerParams& lp, const void* q, const void* k, const void* v,
                                  const int* cu_seqlens, int batch, int total_tokens, int max_seqlen, void* out,
-                                 float* lse_out, void* workspace, hipStream_t stream);
+                                 float* lse_out, void* workspace, const PrefillMaskArgs* mask, hipStream_t stream);
 
 }  // namespace lserve

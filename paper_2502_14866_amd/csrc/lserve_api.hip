@@ -159,9 +159,10 @@ int lserve_select_pages(const lserve_attn_desc* desc, const lserve_paged_kv* kv,
     return e == hipSuccess ? LSERVE_OK : fail_hip(e);
 }
 
-int lserve_sparse_prefill(const lserve_attn_desc* desc, const void* q, const void* k, const void* v,
-                          const int32_t* cu_seqlens, int32_t batch, int32_t total_tokens, int32_t max_seqlen, void* out,
-                          float* lse_out, void* workspace, size_t workspace_bytes, void* stream) {
+namespace {
+int prefill_impl(const lserve_attn_desc* desc, const lserve_block_mask* mask, const void* q, const void* k, const void* v,
+                 const int32_t* cu_seqlens, int32_t batch, int32_t total_tokens, int32_t max_seqlen, void* out,
+                 float* lse_out, void* workspace, size_t workspace_bytes, void* stream) {
     LayerParams lp;
     int rc = make_layer(desc, &lp);
     if (rc) return rc;
@@ -172,10 +173,54 @@ int lserve_sparse_prefill(const lserve_attn_desc* desc, const void* q, const voi
         !aligned16(lse_out) || !aligned16(workspace))
         return LSERVE_ERR_INVALID_ARG;
     if (lp.NP != 64) return LSERVE_ERR_UNSUPPORTED;
-    if (!workspace || workspace_bytes < prefill_workspace_bytes(lp, total_tokens, batch)) return LSERVE_ERR_WORKSPACE;
+    PrefillMaskArgs ma = {};
+    size_t need = prefill_workspace_bytes(lp, total_tokens, batch);
+    if (mask) {
+        if (!mask->head_mask || !mask->q_tile_start || !mask->row_ptr || (mask->nnz > 0 && !mask->cols))
+            return LSERVE_ERR_INVALID_ARG;
+        if (mask->num_masks <= 0 || mask->rows_per_mask <= 0 || mask->nnz < 0) return LSERVE_ERR_INVALID_ARG;
+        if (!aligned16(mask->head_mask) || !aligned16(mask->q_tile_start) || !aligned16(mask->row_ptr) ||
+            !aligned16(mask->cols))
+            return LSERVE_ERR_INVALID_ARG;
+        if (max_seqlen > 65536 * 64) return LSERVE_ERR_UNSUPPORTED;  // one byte of LDS per key tile in the merge pass
+        ma.head_mask = mask->head_mask;
+        ma.q_tile_start = mask->q_tile_start;
+        ma.row_ptr = mask->row_ptr;
+        ma.cols = mask->cols;
+        ma.num_masks = mask->num_masks;
+        ma.rows_per_mask = mask->rows_per_mask;
+        ma.nnz = mask->nnz;
+        need = masked_prefill_workspace_bytes(lp, total_tokens, batch, max_seqlen, mask->num_masks, mask->nnz);
+    }
+    if (!workspace || workspace_bytes < need) return LSERVE_ERR_WORKSPACE;
     hipError_t e = launch_sparse_prefill(desc->dtype, lp, q, k, v, cu_seqlens, batch, total_tokens, max_seqlen, out,
-                                         lse_out, workspace, (hipStream_t)stream);
+                                         lse_out, workspace, mask ? &ma : nullptr, (hipStream_t)stream);
     return e == hipSuccess ? LSERVE_OK : fail_hip(e);
+}
+}  // namespace
+
+int lserve_sparse_prefill(const lserve_attn_desc* desc, const void* q, const void* k, const void* v,
+                          const int32_t* cu_seqlens, int32_t batch, int32_t total_tokens, int32_t max_seqlen, void* out,
+                          float* lse_out, void* workspace, size_t workspace_bytes, void* stream) {
+    return prefill_impl(desc, nullptr, q, k, v, cu_seqlens, batch, total_tokens, max_seqlen, out, lse_out, workspace,
+                        workspace_bytes, stream);
+}
+
+int lserve_sparse_prefill_masked(const lserve_attn_desc* desc, const lserve_block_mask* mask, const void* q, const void* k,
+                                 const void* v, const int32_t* cu_seqlens, int32_t batch, int32_t total_tokens,
+                                 int32_t max_seqlen, void* out, float* lse_out, void* workspace, size_t workspace_bytes,
+                                 void* stream) {
+    if (!mask) return LSERVE_ERR_INVALID_ARG;
+    return prefill_impl(desc, mask, q, k, v, cu_seqlens, batch, total_tokens, max_seqlen, out, lse_out, workspace,
+                        workspace_bytes, stream);
+}
+
+size_t lserve_masked_prefill_workspace_bytes(const lserve_attn_desc* desc, int32_t batch, int32_t total_tokens,
+                                             int32_t max_seqlen, int32_t num_masks, int32_t nnz) {
+    LayerParams lp;
+    if (make_layer(desc, &lp) != LSERVE_OK) return 0;
+    if (batch <= 0 || total_tokens <= 0 || max_seqlen <= 0 || num_masks <= 0 || nnz < 0) return 0;
+    return masked_prefill_workspace_bytes(lp, total_tokens, batch, max_seqlen, num_masks, nnz);
 }
 
 int lserve_sparse_decode(const lserve_attn_desc* desc, const lserve_paged_kv* kv, const void* q,

@@ -162,15 +162,68 @@ __device__ __forceinline__ bool decode_work(const HeadClass& hc, int n, int qblo
     return rank < qblocks_total;
 }
 
+// General block mask (Sec. 3.1, Sec. 3.4): per mask and query tile, the ascending list of kept key
+// tiles.  A workgroup owns four query tiles; a pre-pass merges their rows into one ascending list of
+// (key tile, which of the four query tiles keep it) so that the main loop walks a single list.
+struct PrefillMask {
+    const int* head_mask;     // [H]: mask of query head h, -1 = analytic mask of the layer description
+    const int* q_tile_start;  // [batch + 1]: first row of sequence b inside one mask
+    const int* row_ptr;       // [num_masks * rows_per_mask + 1]
+    const int* cols;          // key tiles, ascending inside a row
+    int rows_per_mask;
+    int* blk_list;            // merged lists; the list of a workgroup starts at row_ptr[its first row]
+    int* blk_count;           // [num_masks][batch][blocks_per_seq]
+};
+constexpr int kKeepShift = 24;  // list entry = key tile | keep bits << 24
+
+__global__ __launch_bounds__(kWave) void merge_mask_rows_kernel(PrefillMask mk, const int* __restrict__ cu_seqlens,
+                                                                int batch, int blocks_per_seq) {
+    extern __shared__ unsigned char keep_bits[];  // one byte per key tile of the sequence
+    const int qblk = blockIdx.x, b = blockIdx.y, m = blockIdx.z, lane = threadIdx.x;
+    const int len = cu_seqlens[b + 1] - cu_seqlens[b];
+    const int n_tiles = ceil_div(len, kTile);
+    int* count = mk.blk_count + ((size_t)m * batch + b) * blocks_per_seq + qblk;
+    const int iq0 = qblk * kTilesPerBlock;
+    if (iq0 >= n_tiles) {
+        if (lane == 0) *count = 0;
+        return;
+    }
+    const int rows = min(kTilesPerBlock, n_tiles - iq0);
+    const int r0 = m * mk.rows_per_mask + mk.q_tile_start[b] + iq0;
+    const int last = min(iq0 + rows, n_tiles);  // key tiles the block can keep: [0, last)
+    for (int j = lane; j < last; j += kWave) keep_bits[j] = 0;
+    __builtin_amdgcn_s_waitcnt(0);
+    __builtin_amdgcn_wave_barrier();
+    for (int t = 0; t < rows; ++t) {  // one row at a time: no two lanes touch the same byte
+        const int lo = mk.row_ptr[r0 + t], hi = mk.row_ptr[r0 + t + 1];
+        for (int e = lo + lane; e < hi; e += kWave) {
+            const int j = mk.cols[e];
+            if (j >= 0 && j <= iq0 + t) keep_bits[j] |= (unsigned char)(1u << t);
+        }
+        __builtin_amdgcn_s_waitcnt(0);
+        __builtin_amdgcn_wave_barrier();
+    }
+    int* dst = mk.blk_list + mk.row_ptr[r0];
+    int total = 0;
+    for (int j0 = 0; j0 < last; j0 += kWave) {
+        const int j = j0 + lane;
+        const unsigned bits = j < last ? keep_bits[j] : 0u;
+        const unsigned long long live = __ballot(bits != 0);
+        if (bits) dst[total + __popcll(live & ((1ull << lane) - 1ull))] = j | (int)(bits << kKeepShift);
+        total += __popcll(live);
+    }
+    if (lane == 0) *count = total;
+}
+
 template <class T> struct Ones;
 template <> struct Ones<F16> { static constexpr uint32_t pair = 0x3c003c00u; };
 template <> struct Ones<BF16> { static constexpr uint32_t pair = 0x3f803f80u; };
 
-template <class T>
+template <class T, bool MASKED>
 __global__ __launch_bounds__(kPrefillThreads, 512 / kPrefillThreads) void sparse_prefill_kernel(
     LayerParams lp, const uint16_t* __restrict__ q, const uint16_t* __restrict__ k, const uint16_t* __restrict__ vt,
     const int* __restrict__ cu_seqlens, int batch, int blocks_per_seq, int tiles_total, uint16_t* __restrict__ out,
-    float* __restrict__ lse_out, int total_tokens, PrefillSchedule sched) {
+    float* __restrict__ lse_out, int total_tokens, PrefillSchedule sched, PrefillMask mk) {
     // Two stages of (K tile, V^T tile).  Four separate arrays, and a loop unrolled over the two stages,
     // so that the compiler can tell the tile being read from the tile being filled and does not wait
     // for the loads in flight before every operand read.
@@ -214,7 +267,16 @@ __global__ __launch_bounds__(kPrefillThreads, 512 / kPrefillThreads) void sparse
         band_begin = 0;
         sink_end = 0;
     }
-    const int n_visit = sink_end + (iq_last - band_begin + 1);
+    int n_visit = sink_end + (iq_last - band_begin + 1);
+    // a listed mask replaces the closed form: the merged list of this workgroup's four query tiles
+    const int* lst = nullptr;
+    if (MASKED) {
+        const int m = mk.head_mask[h];
+        if (m >= 0) {
+            lst = mk.blk_list + mk.row_ptr[m * mk.rows_per_mask + mk.q_tile_start[b] + qblk * kTilesPerBlock];
+            n_visit = mk.blk_count[((size_t)m * batch + b) * blocks_per_seq + qblk];
+        }
+    }
 
     // ---- Q^T operand: lane (n, half) holds Q[row][16 kk + 8 half .. + 8]
     uint4 qreg[8];
@@ -271,7 +333,12 @@ __global__ __launch_bounds__(kPrefillThreads, 512 / kPrefillThreads) void sparse
             dma_load16(vtile, vofs[i], __builtin_amdgcn_readfirstlane(lds_address(vd) + lds_wave + i * 1024));
         }
     };
-    auto tile_of = [sink_end, band_begin](int it) { return it < sink_end ? it : band_begin + (it - sink_end); };
+    // Entry `it` of the walk: key tile in the low bits; with a listed mask also which query tiles keep it.
+    auto entry_of = [&](int it) {
+        if (MASKED && lst) return lst[it];
+        return it < sink_end ? it : band_begin + (it - sink_end);
+    };
+    int e_cur = n_visit > 0 ? entry_of(0) : 0, e_nxt = n_visit > 1 ? entry_of(1) : 0;
 
     // loop-invariant operand offsets of this lane inside a tile
     int koff[8], voff[4];
@@ -281,11 +348,17 @@ __global__ __launch_bounds__(kPrefillThreads, 512 / kPrefillThreads) void sparse
     for (int step = 0; step < 4; ++step) voff[step] = n * kVRowBytes + v_chunk_pos(n, step * 2 + half) * 16;
 
     auto tile_step = [&](int it, const unsigned char* ks, const unsigned char* vs, unsigned char* kd, unsigned char* vd) {
-        const int jt = tile_of(it);
-        if (it + 1 < n_visit) fetch(kd, vd, tile_of(it + 1));
+        const int e_new = it + 2 < n_visit ? entry_of(it + 2) : 0;  // requested two steps ahead of its use
+        const int jt = e_cur & ((1 << kKeepShift) - 1);
+        if (it + 1 < n_visit) fetch(kd, vd, e_nxt & ((1 << kKeepShift) - 1));
         // does this wave's mask tile keep key tile jt?
         bool keep = wave_has_rows && jt <= iq;
-        if (streaming) keep = keep && (jt < lp.sink_pages || jt > iq - lp.local_pages);
+        if (MASKED && lst)
+            keep = keep && ((e_cur >> (kKeepShift + wave / 2)) & 1);
+        else if (streaming)
+            keep = keep && (jt < lp.sink_pages || jt > iq - lp.local_pages);
+        e_cur = e_nxt;
+        e_nxt = e_new;
         if (keep) {
             const bool diagonal = jt == iq;
             // S^T for the 64 keys of the tile, two blocks of 32 keys.  All operand reads of a block are
@@ -371,7 +444,7 @@ __global__ __launch_bounds__(kPrefillThreads, 512 / kPrefillThreads) void sparse
         __syncthreads();  // the next tile has landed and this one is free
     };
 
-    fetch(k_lds0, v_lds0, tile_of(0));
+    if (n_visit > 0) fetch(k_lds0, v_lds0, e_cur & ((1 << kKeepShift) - 1));
     dma_wait();
     __syncthreads();
     for (int it = 0; it < n_visit; it += 2) {
@@ -385,7 +458,7 @@ __global__ __launch_bounds__(kPrefillThreads, 512 / kPrefillThreads) void sparse
     const float lt = halves_sum(l_run);
     const int row = iq * kTile + row0 + n;
     if (row >= len) return;
-    const float inv = 1.f / lt;
+    const float inv = lt > 0.f ? 1.f / lt : 0.f;  // a row that keeps nothing (possible with a listed mask) gives 0
     uint16_t* dst = out + ((size_t)(start + row) * lp.H + h) * kHeadDim;
 #pragma unroll
     for (int db = 0; db < 4; ++db)
@@ -397,15 +470,21 @@ __global__ __launch_bounds__(kPrefillThreads, 512 / kPrefillThreads) void sparse
             w.y = Elem<T>::pack(acc[db][4 * g4 + 2] * inv, acc[db][4 * g4 + 3] * inv);
             *reinterpret_cast<uint2*>(dst + d) = w;
         }
-    if (lse_out && half == 0) lse_out[(size_t)h * total_tokens + start + row] = (m_run + __builtin_amdgcn_logf(lt)) * kLn2;
+    if (lse_out && half == 0)
+        lse_out[(size_t)h * total_tokens + start + row] = lt > 0.f ? (m_run + __builtin_amdgcn_logf(lt)) * kLn2 : -INFINITY;
 }
 
 int prefill_tile_slots(int total_tokens, int batch) { return total_tokens / kTile + batch; }
 
+size_t vt_bytes(const LayerParams& lp, int total_tokens, int batch) {
+    return (size_t)lp.Hkv * prefill_tile_slots(total_tokens, batch) * kHeadDim * kTile * sizeof(uint16_t);
+}
+size_t align16(size_t x) { return (x + 15) & ~(size_t)15; }
+
 template <class T>
 hipError_t launch_prefill(const LayerParams& lp, const void* q, const void* k, const void* v, const int* cu_seqlens,
                           int batch, int total_tokens, int max_seqlen, void* out, float* lse_out, void* workspace,
-                          hipStream_t stream) {
+                          const PrefillMaskArgs* mask, hipStream_t stream) {
     const int tiles_total = prefill_tile_slots(total_tokens, batch);
     uint16_t* vt = reinterpret_cast<uint16_t*>(workspace);
     const int max_tiles = (max_seqlen + kTile - 1) / kTile;
@@ -414,6 +493,21 @@ hipError_t launch_prefill(const LayerParams& lp, const void* q, const void* k, c
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     const int blocks_per_seq = (max_seqlen + kRowsPerBlock - 1) / kRowsPerBlock;
+    PrefillMask mk = {};
+    if (mask) {
+        unsigned char* ws = reinterpret_cast<unsigned char*>(workspace) + align16(vt_bytes(lp, total_tokens, batch));
+        mk.head_mask = mask->head_mask;
+        mk.q_tile_start = mask->q_tile_start;
+        mk.row_ptr = mask->row_ptr;
+        mk.cols = mask->cols;
+        mk.rows_per_mask = mask->rows_per_mask;
+        mk.blk_list = reinterpret_cast<int*>(ws);
+        mk.blk_count = reinterpret_cast<int*>(ws + align16((size_t)mask->nnz * sizeof(int)));
+        hipLaunchKernelGGL(merge_mask_rows_kernel, dim3(blocks_per_seq, batch, mask->num_masks), dim3(kWave),
+                           (size_t)align16(max_tiles), stream, mk, cu_seqlens, batch, blocks_per_seq);
+        e = hipGetLastError();
+        if (e != hipSuccess) return e;
+    }
     PrefillSchedule sched;
     sched.qblocks_total = blocks_per_seq * batch;
     for (int c = 0; c < 2; ++c) {
@@ -431,25 +525,39 @@ hipError_t launch_prefill(const LayerParams& lp, const void* q, const void* k, c
             hc.items_per_xcd = (hc.heads * lp.group * sched.qblocks_total + kXcds - 1) / kXcds;
     }
     const int grid = kXcds * (sched.cls[0].items_per_xcd + sched.cls[1].items_per_xcd);
-    hipLaunchKernelGGL(sparse_prefill_kernel<T>, dim3(grid), dim3(kPrefillThreads), 0, stream,
-                       lp, reinterpret_cast<const uint16_t*>(q), reinterpret_cast<const uint16_t*>(k), vt, cu_seqlens,
-                       batch, blocks_per_seq, tiles_total, reinterpret_cast<uint16_t*>(out), lse_out, total_tokens, sched);
+    if (mask)
+        hipLaunchKernelGGL((sparse_prefill_kernel<T, true>), dim3(grid), dim3(kPrefillThreads), 0, stream, lp,
+                           reinterpret_cast<const uint16_t*>(q), reinterpret_cast<const uint16_t*>(k), vt, cu_seqlens, batch,
+                           blocks_per_seq, tiles_total, reinterpret_cast<uint16_t*>(out), lse_out, total_tokens, sched, mk);
+    else
+        hipLaunchKernelGGL((sparse_prefill_kernel<T, false>), dim3(grid), dim3(kPrefillThreads), 0, stream, lp,
+                           reinterpret_cast<const uint16_t*>(q), reinterpret_cast<const uint16_t*>(k), vt, cu_seqlens, batch,
+                           blocks_per_seq, tiles_total, reinterpret_cast<uint16_t*>(out), lse_out, total_tokens, sched, mk);
     return hipGetLastError();
 }
 
 }  // namespace
 
 size_t prefill_workspace_bytes(const LayerParams& lp, int total_tokens, int batch) {
-    return (size_t)lp.Hkv * prefill_tile_slots(total_tokens, batch) * kHeadDim * kTile * sizeof(uint16_t);
+    return vt_bytes(lp, total_tokens, batch);
+}
+
+// V^T tiles, then the merged tile lists (at most one entry per mask entry), then one count per
+// (mask, sequence, workgroup of query rows).
+size_t masked_prefill_workspace_bytes(const LayerParams& lp, int total_tokens, int batch, int max_seqlen, int num_masks,
+                                      int nnz) {
+    const int blocks_per_seq = (max_seqlen + kRowsPerBlock - 1) / kRowsPerBlock;
+    return align16(vt_bytes(lp, total_tokens, batch)) + align16((size_t)nnz * sizeof(int)) +
+           align16((size_t)num_masks * batch * blocks_per_seq * sizeof(int));
 }
 
 hipError_t launch_sparse_prefill(int dtype, const LayerParams& lp, const void* q, const void* k, const void* v,
                                  const int* cu_seqlens, int batch, int total_tokens, int max_seqlen, void* out,
-                                 float* lse_out, void* workspace, hipStream_t stream) {
+                                 float* lse_out, void* workspace, const PrefillMaskArgs* mask, hipStream_t stream) {
     return dtype == 0 ? launch_prefill<F16>(lp, q, k, v, cu_seqlens, batch, total_tokens, max_seqlen, out, lse_out,
-                                            workspace, stream)
+                                            workspace, mask, stream)
                       : launch_prefill<BF16>(lp, q, k, v, cu_seqlens, batch, total_tokens, max_seqlen, out, lse_out,
-                                             workspace, stream);
+                                             workspace, mask, stream);
 }
 
 }  // namespace lserve

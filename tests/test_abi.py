@@ -127,6 +127,19 @@ def test_invalid_arguments_are_rejected_on_the_host(L):
                                                None, ws, stream)) == -1
     assert _rc(lambda: L.lserve_sparse_prefill(desc(), q, q[:, :2].contiguous(), q[:, :2].contiguous(), cu, 2, out,
                                                None, ws[:64], stream)) == -3
+    # masked prefill: missing arrays, non-positive counts, workspace smaller than the masked call needs
+    i4 = torch.zeros((8,), dtype=torch.int32)
+    kk = q[:, :2].contiguous()
+    good_mask = L.BlockMask(i4[:4], i4[:2], i4[:3], i4[:1], 1, 1)
+    assert _rc(lambda: L.lserve_sparse_prefill_masked(desc(), L.BlockMask(i4[:4], i4[:2], i4[:3], i4[:1], 0, 1), q, kk, kk,
+                                                      cu, 2, out, None, ws, stream)) == -1
+    assert _rc(lambda: L.lserve_sparse_prefill_masked(desc(), L.BlockMask(i4[1:5], i4[:2], i4[:3], i4[:1], 1, 1), q, kk,
+                                                      kk, cu, 2, out, None, ws, stream)) == -1  # misaligned
+    need = L.lserve_masked_prefill_workspace_bytes(desc(), 1, 2, 2, 1, 1)
+    assert need > L.lserve_workspace_bytes(L.LSERVE_CALL_SPARSE_PREFILL, desc(), 1, 0, 0, 2)
+    assert _rc(lambda: L.lserve_sparse_prefill_masked(desc(), good_mask, q, kk, kk, cu, 2, out, None, ws[:need - 16],
+                                                      stream)) == -3
+    assert L.lserve_masked_prefill_workspace_bytes(desc(), 1, 2, 2, 0, 1) == 0
 
 
 def test_product_path_does_not_reach_for_the_oracle():

@@ -587,3 +587,83 @@ def test_two_way_cache_decode_and_append_equal_the_one_pool_path_and_the_oracle(
     # statistics of the dense heads in the compacted layout equal the one-pool statistics
     assert torch.equal(one.stats[:, dense].cpu().view(torch.int16)[inp.page_table[0, :5].long()],
                        two.stats.cpu().view(torch.int16)[inp.page_table[0, :5].long()])
+
+
+# ---- prefill under a general block mask (Sec. 3.1, Sec. 3.4) ------------------------------------------
+
+def _masked_prefill(L, w, pin, dev, lengths, masks, head_mask):
+    from helpers import block_mask_csr
+    qts, rp, cl, R = block_mask_csr(masks, lengths)
+    desc = L.AttnDesc(w.num_q_heads, w.num_kv_heads, w.streaming_flags(), dtype=w.torch_dtype,
+                      sink_tokens=w.sink_tokens, local_tokens=w.local_tokens)
+    q, k, v = pin.q.to(dev), pin.k.to(dev), pin.v.to(dev)
+    total = q.shape[0]
+
+    def dev_i32(a, pad=4):  # 16-byte aligned device copies with a little slack
+        t = torch.zeros((len(a) + pad,), dtype=torch.int32, device=dev)
+        t[:len(a)] = torch.as_tensor(np.asarray(a, dtype=np.int32))
+        return t[:len(a)]
+
+    mask = L.BlockMask(dev_i32(head_mask), dev_i32(qts), dev_i32(rp), dev_i32(cl) if len(cl) else None,
+                       len(masks), R)
+    nbytes = L.lserve_masked_prefill_workspace_bytes(desc, len(lengths), total, max(lengths), len(masks), len(cl))
+    assert nbytes >= L.lserve_workspace_bytes(L.LSERVE_CALL_SPARSE_PREFILL, desc, len(lengths), 0, 0, total)
+    ws = torch.empty((nbytes,), dtype=torch.uint8, device=dev)
+    out = torch.full_like(q, float("nan"))
+    lse = torch.full((w.num_q_heads, total), float("nan"), dtype=torch.float32, device=dev)
+    L.lserve_sparse_prefill_masked(desc, mask, q, k, v, pin.cu_seqlens.to(dev), max(lengths), out, lse, ws)
+    torch.cuda.synchronize()
+    tok = np.repeat(np.arange(total, dtype=np.int32), w.num_q_heads)
+    head = np.tile(np.arange(w.num_q_heads, dtype=np.int32), total)
+    ref, lse_ref = oracle.block_mask_prefill_rows(pin.q, pin.k, pin.v, pin.cu_seqlens, w.streaming_flags(), 64,
+                                                  w.sink_tokens, w.local_tokens, head_mask, qts, rp, cl, R, tok, head)
+    return out, lse, ref.reshape(total, w.num_q_heads, -1), lse_ref.reshape(total, w.num_q_heads)
+
+
+@pytest.mark.parametrize("dtype", ["fp16", "bf16"])
+@pytest.mark.parametrize("lengths", [(130,), (700, 64, 1000), (2049,)])
+def test_masked_prefill_matches_oracle_on_every_row(dtype, lengths):
+    """Random block masks (diagonal always kept), a vertical-and-slash style mask, the analytic fallback and
+    a mask whose first rows keep nothing, on different heads of one call; every row against the oracle."""
+    L = _lib()
+    dev = torch.device("cuda:0")
+    w = Workload(name="pm", batch=len(lengths), num_q_heads=8, num_kv_heads=2, dtype=dtype, streaming_kv_heads=(0,),
+                 sink_tokens=64, local_tokens=192, seed=23)
+    pin = make_prefill_inputs(w, lengths=lengths)
+    rng = np.random.default_rng(7)
+    kept = {}
+
+    def rnd(b, i):
+        if (b, i) not in kept:
+            kept[(b, i)] = [j for j in range(i) if rng.random() < 0.3] + [i]
+        return kept[(b, i)]
+
+    vslash = lambda b, i: [j for j in range(i + 1) if j % 5 == 0 or i - j < 2]   # vertical lines and a slash
+    holes = lambda b, i: [] if i < 2 else [j for j in range(i + 1) if j % 2 == 1]  # tile rows 0, 1 keep nothing; no diagonal on even rows
+    # heads 0-3 share KV head 0 (flagged streaming), heads 4-7 KV head 1 (dense)
+    head_mask = [0, 1, -1, 2, 0, -1, 1, 2]
+    out, lse, ref, lse_ref = _masked_prefill(L, w, pin, dev, lengths, [rnd, vslash, holes], head_mask)
+    empty = ~np.isfinite(lse_ref)
+    assert empty.any()
+    got = out.float().cpu().numpy()
+    assert not np.isnan(got).any()
+    assert (got[empty] == 0).all() and np.isneginf(lse.t().cpu().numpy()[empty]).all()
+    assert_attention_close(out, ref, f"masked prefill {dtype} {lengths}")
+    lse_got = lse.t().contiguous().cpu().numpy()
+    np.testing.assert_allclose(lse_got[~empty], lse_ref[~empty], atol=5e-3, rtol=0)
+
+
+def test_masked_prefill_with_analytic_tiles_is_bit_identical_to_the_unmasked_call():
+    L = _lib()
+    dev = torch.device("cuda:0")
+    lengths = (900, 333)
+    w = Workload(name="pm2", batch=2, num_q_heads=4, num_kv_heads=2, dtype="fp16", streaming_kv_heads=(0,),
+                 sink_tokens=64, local_tokens=192, seed=29)
+    pin = make_prefill_inputs(w, lengths=lengths)
+    s, wl = 1, 3
+    lam = lambda b, i: [j for j in range(i + 1) if j < s or j > i - wl]
+    lower = lambda b, i: range(i + 1)
+    out_m, lse_m, _, _ = _masked_prefill(L, w, pin, dev, lengths, [lam, lower], [0, 0, 1, 1])
+    out_u, lse_u = _prefill(L, w, pin, dev)
+    assert torch.equal(out_m.view(torch.int16), out_u.view(torch.int16))
+    assert torch.equal(lse_m, lse_u)
