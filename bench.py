@@ -44,6 +44,8 @@ def parse_args():
     ap.add_argument("--warmup", type=int, default=64)
     ap.add_argument("--workload", default="cfg2", choices=["cfg2", "cfg4", "cfg5"])
     ap.add_argument("--context", type=int, default=0, help="override the context length (cfg2 / cfg4)")
+    ap.add_argument("--page-size", type=int, default=0, choices=[0, 16, 32, 64, 128],
+                    help="override N_P (N_L = min(16, N_P)); the page-size sweep of the decode path")
     ap.add_argument("--no-graph", action="store_true", help="launch eagerly instead of replaying a HIP graph")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-prefill", action="store_true")
@@ -109,6 +111,9 @@ def main():
     over = {}
     if args.context:
         over["context"] = args.context
+    if args.page_size:
+        over["page_size"] = args.page_size
+        over["logical_page_size"] = min(16, args.page_size)
     w = get_config(args.workload, **over)
     t0 = time.time()
     inp = make_decode_inputs(w, device=dev)
