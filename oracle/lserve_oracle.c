@@ -18,6 +18,7 @@
  *                                      K highest pages under the token budget)
  *   - decode over an index table     : Sec. 3.6 (selected pages for dense heads, sink + local
  *                                      pages for streaming heads), Sec. 3.2 ("shorter page table")
+ *   - chunked prefill over paged KV  : Sec. 2.1 (prefill with S tokens of history), mask of Sec. 3.1
  *   - general block mask in prefill  : Sec. 3.1 / Sec. 3.4 (kept key tiles listed per query tile and head)
  *   - KV write-back                  : Sec. 3.2 / Sec. 2.1 (new tokens stored at their slots of the
  *                                      paged cache; statistics afterwards = the definition above
@@ -383,6 +384,62 @@ void oracle_sparse_prefill_rows(const uint16_t *q, const uint16_t *k, const uint
             double pr = exp(score[u] - mx) / denom;
             const uint16_t *vu = &v[((size_t)(start + u) * Hkv + hk) * D];
             for (int c = 0; c < D; ++c) o[c] += pr * oracle_widen(vu[c], dtype);
+        }
+        if (lse) lse[r] = mx + log(denom);
+        free(score);
+    }
+}
+
+/* ---- chunked prefill over a paged cache (Sec. 2.1: prefill with S tokens of KV history; Sec. 3.1 mask) ---- */
+/*
+ * The K / V of every token, the chunk's own included, sit in the paged pools; sequence b has L_b =
+ * seq_lens[b] tokens and its chunk holds the last n_b = cu_q[b+1] - cu_q[b] of them, so query j of the
+ * chunk is the token at position t = L_b - n_b + j.  It attends the positions u <= t allowed by the same
+ * tile-granular mask as oracle_sparse_prefill_rows, with tiles counted from position 0 of the sequence.
+ * Row r asks for chunk token rows_token[r] (index into q) and query head rows_head[r].
+ */
+void oracle_paged_prefill_rows(const uint16_t *q, const uint16_t *k_pool, const uint16_t *v_pool,
+                               const int32_t *page_table, const int32_t *seq_lens, const int32_t *cu_q,
+                               int batch, int max_pages, int H, int Hkv, int D, int NP, int dtype,
+                               int sink_tokens, int local_tokens, const uint8_t *kv_head_is_streaming,
+                               double sm_scale, const int32_t *rows_token, const int32_t *rows_head,
+                               int n_rows, double *out, double *lse)
+{
+    int n = H / Hkv;
+    int s = ceil_div(sink_tokens, NP);
+    int w = ceil_div(local_tokens, NP);
+#pragma omp parallel for schedule(dynamic, 4)
+    for (int r = 0; r < n_rows; ++r) {
+        int tok = rows_token[r], h = rows_head[r], hk = h / n;
+        int b = 0;
+        while (b + 1 < batch && cu_q[b + 1] <= tok) ++b;
+        int t = seq_lens[b] - (cu_q[b + 1] - cu_q[b]) + (tok - cu_q[b]);
+        int streaming = kv_head_is_streaming[hk];
+        double *score = (double *)malloc(sizeof(double) * (size_t)(t + 1));
+        const uint16_t *qh = &q[((size_t)tok * H + h) * D];
+        double mx = -INFINITY;
+        for (int u = 0; u <= t; ++u) {
+            int allowed = !streaming || (u / NP < s) || (u / NP > t / NP - w);
+            if (!allowed) { score[u] = -INFINITY; continue; }
+            int page = page_table[(size_t)b * max_pages + u / NP];
+            double dot = 0.0;
+            for (int c = 0; c < D; ++c)
+                dot += oracle_widen(qh[c], dtype) *
+                       oracle_widen(k_pool[pool_index(page, hk, u % NP, c, Hkv, NP, D)], dtype);
+            score[u] = dot * sm_scale;
+            if (score[u] > mx) mx = score[u];
+        }
+        double denom = 0.0;
+        for (int u = 0; u <= t; ++u)
+            if (score[u] != -INFINITY) denom += exp(score[u] - mx);
+        double *o = &out[(size_t)r * D];
+        for (int c = 0; c < D; ++c) o[c] = 0.0;
+        for (int u = 0; u <= t; ++u) {
+            if (score[u] == -INFINITY) continue;
+            double pr = exp(score[u] - mx) / denom;
+            int page = page_table[(size_t)b * max_pages + u / NP];
+            for (int c = 0; c < D; ++c)
+                o[c] += pr * oracle_widen(v_pool[pool_index(page, hk, u % NP, c, Hkv, NP, D)], dtype);
         }
         if (lse) lse[r] = mx + log(denom);
         free(score);

@@ -197,6 +197,27 @@ def sparse_prefill_rows(q: torch.Tensor, k: torch.Tensor, v: torch.Tensor, cu_se
     return out, lse
 
 
+def paged_prefill_rows(q: torch.Tensor, k_pool: torch.Tensor, v_pool: torch.Tensor, page_table, seq_lens, cu_q,
+                       streaming_flags: Sequence[int], sink_tokens: int, local_tokens: int, rows_token, rows_head,
+                       sm_scale: Optional[float] = None):
+    """Chunked prefill rows over a paged cache that already holds the chunk: (out [R,D] f64, lse [R])."""
+    total, H, D = q.shape
+    num_pages, Hkv, NP, _ = k_pool.shape
+    pt, sl, cu = _i32(page_table), _i32(seq_lens), _i32(cu_q)
+    rt, rh = _i32(rows_token), _i32(rows_head)
+    flags = _u8(streaming_flags)
+    out = np.zeros((rt.shape[0], D), dtype=np.float64)
+    lse = np.zeros((rt.shape[0],), dtype=np.float64)
+    scale = float(sm_scale) if sm_scale else 1.0 / float(np.sqrt(D))
+    qb, kb, vb = _bits(q), _bits(k_pool), _bits(v_pool)
+    _load().oracle_paged_prefill_rows(_p(qb), _p(kb), _p(vb), _p(pt), _p(sl), _p(cu), ctypes.c_int(pt.shape[0]),
+                                      ctypes.c_int(pt.shape[1]), ctypes.c_int(H), ctypes.c_int(Hkv), ctypes.c_int(D),
+                                      ctypes.c_int(NP), ctypes.c_int(_dtype_code(q)), ctypes.c_int(sink_tokens),
+                                      ctypes.c_int(local_tokens), _p(flags), ctypes.c_double(scale), _p(rt), _p(rh),
+                                      ctypes.c_int(rt.shape[0]), _p(out), _p(lse))
+    return out, lse
+
+
 def block_mask_prefill_rows(q: torch.Tensor, k: torch.Tensor, v: torch.Tensor, cu_seqlens,
                             streaming_flags: Sequence[int], tile: int, sink_tokens: int, local_tokens: int,
                             head_mask, q_tile_start, row_ptr, cols, rows_per_mask: int, rows_token, rows_head,

@@ -342,3 +342,40 @@ def test_block_mask_rows_equal_textbook_attention_under_the_expanded_boolean_mas
                 ref = _sdpa(q[start + t, h], k[start:start + n, 0], v[start:start + n, 0], mask=mask)
                 np.testing.assert_allclose(out[start + t, h], ref, rtol=1e-10, atol=1e-12)
         start += n
+
+
+# ---- chunked prefill over a paged cache ---------------------------------------------------------------
+
+def test_paged_chunk_rows_equal_the_contiguous_prefill_rows_and_the_decode_of_the_same_position():
+    """Scatter a contiguous prefill into pages: the chunk holding the last n tokens must reproduce the rows of
+    the contiguous prefill (independent function, independent addressing), whatever the chunk boundary; and a
+    one-token chunk is a decode step with the analytic page lists."""
+    from workloads import scatter_prefill_kv_to_pages
+    w = _prefill_workload(batch=2, sink_tokens=64, local_tokens=128)
+    lengths = (300, 131)
+    pin = make_prefill_inputs(w, lengths=lengths)
+    NP = 64
+    g = torch.Generator().manual_seed(3)
+    page_table = torch.randperm(16, generator=g).to(torch.int32).reshape(2, 8)
+    k_pool = torch.randn((16, w.num_kv_heads, NP, w.head_dim), generator=g).to(pin.k.dtype)
+    v_pool = torch.randn((16, w.num_kv_heads, NP, w.head_dim), generator=g).to(pin.k.dtype)
+    scatter_prefill_kv_to_pages(pin.k, pin.v, pin.cu_seqlens, k_pool, v_pool, page_table)
+    total = sum(lengths)
+    tok, head = _all_rows(total, w.num_q_heads)
+    full, full_lse = oracle.sparse_prefill_rows(pin.q, pin.k, pin.v, pin.cu_seqlens, w.streaming_flags(), NP,
+                                                w.sink_tokens, w.local_tokens, tok, head)
+    full = full.reshape(total, w.num_q_heads, -1)
+    for chunk in ((300, 131), (100, 67), (1, 1), (64, 3)):
+        qs, idx = [], []
+        for b, (L, n) in enumerate(zip(lengths, chunk)):
+            a = int(pin.cu_seqlens[b]) + L - n
+            qs.append(pin.q[a:a + n])
+            idx.extend(range(a, a + n))
+        qc = torch.cat(qs)
+        cu_q = np.concatenate([[0], np.cumsum(chunk)]).astype(np.int32)
+        t2, h2 = _all_rows(sum(chunk), w.num_q_heads)
+        out, lse = oracle.paged_prefill_rows(qc, k_pool, v_pool, page_table, np.asarray(lengths, np.int32), cu_q,
+                                             w.streaming_flags(), w.sink_tokens, w.local_tokens, t2, h2)
+        out = out.reshape(sum(chunk), w.num_q_heads, -1)
+        np.testing.assert_allclose(out, full[idx], rtol=1e-12, atol=1e-14)
+        np.testing.assert_allclose(lse.reshape(sum(chunk), -1), full_lse.reshape(total, -1)[idx], rtol=1e-12, atol=1e-12)
