@@ -433,6 +433,15 @@ def bench_append(torch, L, dev, n_tokens, w_dec):
         return e0.elapsed_time(e1) / reps
 
     ms = timed(lambda: L.lserve_append_kv(desc, kv, k_new, v_new, cu, zero, n_tokens), 5)
+    # chunked prefill reading the pages just written (whole prompt as one chunk: same work as the contiguous call)
+    paged_ms = None
+    try:
+        qn = torch.randn((n_tokens, w.num_q_heads, D), generator=gen, device=dev, dtype=torch.float32).to(dt)
+        on = torch.empty_like(qn)
+        ws_p = torch.empty((L.lserve_paged_prefill_workspace_bytes(desc, 1, pages),), dtype=torch.uint8, device=dev)
+        paged_ms = timed(lambda: L.lserve_sparse_prefill_paged(desc, kv, qn, cu, n_tokens, n_tokens, on, None, ws_p), 2)
+    except Exception as e:  # reported, never fatal
+        paged_ms = repr(e)
     n_sel = sum(1 for f in w.streaming_flags() if not f)
     moved = 2 * 2 * n_tokens * Hkv * D * 2 + pages * n_sel * g * 2 * D * 2  # K and V read + written, statistics written
     # the decode workload's per-step append: one token per sequence into its tail page
@@ -457,6 +466,7 @@ def bench_append(torch, L, dev, n_tokens, w_dec):
                               "ms": ms, "algorithmic_bytes": moved, "achieved_GBs": moved / (ms * 1e-3) / 1e9,
                               "frac_of_hbm_peak": moved / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS},
         "decode_append_us_per_call": us,
+        "prefill_over_the_written_pages_ms": paged_ms,
         "note": "not part of `value`: the decode benchmark reads a pre-written cache",
     }
 

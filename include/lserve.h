@@ -9,8 +9,9 @@
  *                            top-K physical pages under a token budget (Sec. 3.5.2)
  *   lserve_sparse_decode     paged decode attention over an index table (Sec. 3.6)
  * and, around them, lserve_append_kv: write-back of new K/V into the pages with the statistics
- * updated in the same pass (Sec. 3.2, Sec. 3.5.2), and lserve_sparse_prefill_masked: prefill under
- * a caller-supplied block mask (Sec. 3.1, Sec. 3.4).
+ * updated in the same pass (Sec. 3.2, Sec. 3.5.2), lserve_sparse_prefill_masked: prefill under a
+ * caller-supplied block mask (Sec. 3.1, Sec. 3.4), and lserve_sparse_prefill_paged: chunked prefill
+ * whose keys and values come from the paged cache (Sec. 2.1).
  *
  * Conventions common to every call
  *   - "device" pointers are HIP device memory owned by the caller; "host" pointers are ordinary
@@ -207,6 +208,29 @@ int lserve_sparse_prefill(const lserve_attn_desc *desc, const void *q, const voi
                           const int32_t *cu_seqlens, int32_t batch, int32_t total_tokens,
                           int32_t max_seqlen, void *out, float *lse_out, void *workspace,
                           size_t workspace_bytes, void *stream);
+
+/*
+ * Chunked prefill over the paged cache (Sec. 2.1: prefill of N tokens with S tokens of KV history; mask of
+ * Sec. 3.1).  The K / V of every token, the chunk's own included (lserve_append_kv first), are read from
+ * kv; sequence b has L_b = kv->seq_lens[b] tokens and the chunk is its last n_b = cu_q[b+1] - cu_q[b]
+ * tokens, so query j sits at position t = L_b - n_b + j and attends the positions u <= t that the analytic
+ * mask of `desc` allows, tiles counted from position 0.  With n_b = L_b this equals lserve_sparse_prefill on
+ * the same tokens; with n_b = 1 it equals a decode step with nothing left out for dense heads.
+ *
+ *   kv           one pool holding every KV head (pool_heads 0 or Hkv, no streaming pool), N_P = 64;
+ *                stats are not used
+ *   q            device [total_new][H][D], cu_q device [batch + 1] (batch = kv->batch), n_b >= 0
+ *   max_new_per_seq  host bound of n_b (> 0); max_seqlen host bound of L_b
+ *   out          device [total_new][H][D]; lse_out device [H][total_new] fp32 or NULL
+ *   workspace    device, >= lserve_paged_prefill_workspace_bytes(desc, batch, max_pages_per_seq)
+ */
+int lserve_sparse_prefill_paged(const lserve_attn_desc *desc, const lserve_paged_kv *kv, const void *q,
+                                const int32_t *cu_q, int32_t total_new, int32_t max_new_per_seq,
+                                int32_t max_seqlen, void *out, float *lse_out, void *workspace,
+                                size_t workspace_bytes, void *stream);
+
+size_t lserve_paged_prefill_workspace_bytes(const lserve_attn_desc *desc, int32_t batch,
+                                            int32_t max_pages_per_seq);
 
 /*
  * Block-sparse prefill under a general block mask (Sec. 3.1: every tile of the attention map is skipped or

@@ -19,6 +19,8 @@ from .binding import (  # noqa: F401
     lserve_append_kv,
     lserve_masked_prefill_workspace_bytes,
     lserve_sparse_prefill_masked,
+    lserve_paged_prefill_workspace_bytes,
+    lserve_sparse_prefill_paged,
     lserve_build_page_stats,
     lserve_last_hip_error,
     lserve_select_pages,

@@ -25,6 +25,8 @@ EXPORTED_SYMBOLS = (
     "lserve_sparse_decode",
     "lserve_append_kv",
     "lserve_sparse_prefill_masked",
+    "lserve_sparse_prefill_paged",
+    "lserve_paged_prefill_workspace_bytes",
     "lserve_masked_prefill_workspace_bytes",
     "BlockMask",
     "lserve_workspace_bytes",
@@ -94,6 +96,10 @@ def load_library():
         lib.lserve_sparse_prefill_masked.restype = ctypes.c_int
         lib.lserve_masked_prefill_workspace_bytes.argtypes = [dp, i32, i32, i32, i32, i32]
         lib.lserve_masked_prefill_workspace_bytes.restype = ctypes.c_size_t
+        lib.lserve_sparse_prefill_paged.argtypes = [dp, kp, vp, vp, i32, i32, i32, vp, vp, vp, sz, vp]
+        lib.lserve_sparse_prefill_paged.restype = ctypes.c_int
+        lib.lserve_paged_prefill_workspace_bytes.argtypes = [dp, i32, i32]
+        lib.lserve_paged_prefill_workspace_bytes.restype = ctypes.c_size_t
         lib.lserve_workspace_bytes.argtypes = [ctypes.c_int, dp, i32, i32, i32, i32]
         lib.lserve_workspace_bytes.restype = sz
         lib.lserve_strerror.argtypes = [ctypes.c_int]
@@ -262,6 +268,21 @@ def lserve_sparse_prefill_masked(desc: AttnDesc, mask: BlockMask, q: torch.Tenso
                                                        max_seqlen, _ptr(out), _ptr(lse_out), _ptr(workspace),
                                                        ws_bytes, _stream(stream)),
            "lserve_sparse_prefill_masked")
+
+
+def lserve_paged_prefill_workspace_bytes(desc: AttnDesc, batch: int, max_pages_per_seq: int) -> int:
+    return int(load_library().lserve_paged_prefill_workspace_bytes(desc.c(), batch, max_pages_per_seq))
+
+
+def lserve_sparse_prefill_paged(desc: AttnDesc, kv: PagedKV, q: torch.Tensor, cu_q: torch.Tensor,
+                                max_new_per_seq: int, max_seqlen: int, out: torch.Tensor,
+                                lse_out: Optional[torch.Tensor] = None, workspace: Optional[torch.Tensor] = None,
+                                stream=None) -> None:
+    ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    _check(load_library().lserve_sparse_prefill_paged(desc.c(), kv.c(), _ptr(q), _ptr(cu_q), q.shape[0],
+                                                      max_new_per_seq, max_seqlen, _ptr(out), _ptr(lse_out),
+                                                      _ptr(workspace), ws_bytes, _stream(stream)),
+           "lserve_sparse_prefill_paged")
 
 
 def lserve_sparse_decode(desc: AttnDesc, kv: PagedKV, q: torch.Tensor, sel_pages: Optional[torch.Tensor],

@@ -23,6 +23,11 @@ hipError_t launch_select_pages(int dtype, const LayerParams& lp, const PagedPara
                                float* scores, bool scores_is_user_buffer, const HeadList& selecting,
                                hipStream_t stream);
 
+size_t paged_prefill_workspace_bytes(const LayerParams& lp, int batch, int max_pages);
+hipError_t launch_sparse_prefill_paged(int dtype, const LayerParams& lp, const PagedParams& kv, const void* q,
+                                       const int* cu_q, int total_new, int max_new_per_seq, int max_seqlen, void* out,
+                                       float* lse_out, void* workspace, hipStream_t stream);
+
 size_t decode_workspace_bytes(const LayerParams& lp, int batch, int sel_stride);
 
 hipError_t launch_sparse_decode(int dtype, const LayerParams& lp, const PagedParams& kv, const void* q,

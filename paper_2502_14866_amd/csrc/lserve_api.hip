@@ -215,6 +215,34 @@ int lserve_sparse_prefill_masked(const lserve_attn_desc* desc, const lserve_bloc
                         workspace_bytes, stream);
 }
 
+int lserve_sparse_prefill_paged(const lserve_attn_desc* desc, const lserve_paged_kv* kv, const void* q,
+                                const int32_t* cu_q, int32_t total_new, int32_t max_new_per_seq, int32_t max_seqlen,
+                                void* out, float* lse_out, void* workspace, size_t workspace_bytes, void* stream) {
+    LayerParams lp;
+    PagedParams pp;
+    int rc = make_layer(desc, &lp);
+    if (rc) return rc;
+    rc = make_paged(kv, lp, true, true, false, true, &pp);
+    if (rc) return rc;
+    if (lp.NP != 64) return LSERVE_ERR_UNSUPPORTED;
+    if (pp.pool_heads != lp.Hkv || pp.k_stream) return LSERVE_ERR_UNSUPPORTED;  // one pool holding every head
+    if (!q || !cu_q || !out) return LSERVE_ERR_INVALID_ARG;
+    if (total_new <= 0 || max_new_per_seq <= 0 || max_new_per_seq > total_new || max_seqlen < max_new_per_seq)
+        return LSERVE_ERR_INVALID_ARG;
+    if (!aligned16(q) || !aligned16(cu_q) || !aligned16(out) || !aligned16(lse_out) || !aligned16(workspace))
+        return LSERVE_ERR_INVALID_ARG;
+    if (!workspace || workspace_bytes < paged_prefill_workspace_bytes(lp, pp.batch, pp.max_pages)) return LSERVE_ERR_WORKSPACE;
+    hipError_t e = launch_sparse_prefill_paged(desc->dtype, lp, pp, q, cu_q, total_new, max_new_per_seq, max_seqlen, out,
+                                               lse_out, workspace, (hipStream_t)stream);
+    return e == hipSuccess ? LSERVE_OK : fail_hip(e);
+}
+
+size_t lserve_paged_prefill_workspace_bytes(const lserve_attn_desc* desc, int32_t batch, int32_t max_pages_per_seq) {
+    LayerParams lp;
+    if (make_layer(desc, &lp) != LSERVE_OK || batch <= 0 || max_pages_per_seq <= 0) return 0;
+    return paged_prefill_workspace_bytes(lp, batch, max_pages_per_seq);
+}
+
 size_t lserve_masked_prefill_workspace_bytes(const lserve_attn_desc* desc, int32_t batch, int32_t total_tokens,
                                              int32_t max_seqlen, int32_t num_masks, int32_t nnz) {
     LayerParams lp;

@@ -16,6 +16,8 @@
 //   O^T (d x queries) += V^T (d x keys) * P^T (keys x queries).
 // V^T tiles come from a small pre-pass that transposes V once per call into 64-key tiles whose key
 // order matches the accumulator layout, so every LDS operand read is one 16-byte access.
+#include <algorithm>
+
 #include "kernels.h"
 
 namespace lserve {
@@ -112,6 +114,40 @@ __global__ __launch_bounds__(256) void transpose_v_kernel(const uint16_t* __rest
         const int d = idx / kTile, key = idx % kTile;
         const int sl = vt_slot(key);
         dst[(size_t)d * kTile + v_chunk_pos(d, sl / 8) * 8 + sl % 8] = sm[key][d];  // stored as the LDS tile is laid out
+    }
+}
+
+// Chunked prefill over a paged cache: keys and values of every token, the chunk's own included, are read
+// from the pages; the queries are the last cu_q[b+1] - cu_q[b] tokens of each sequence.
+struct PrefillPaged {
+    const uint16_t* k_pool;  // [pages][Hkv][64][D]
+    const int* page_table;   // [batch][max_pages]
+    const int* seq_lens;     // [batch]
+    int max_pages;
+};
+
+// V^T tiles of a paged cache: page jt of sequence b -> vt [Hkv][b * max_pages + jt][D][64 key slots], chunks
+// permuted as in LDS; slots at or past the sequence length become 0 (a page may hold anything there).
+template <class T>
+__global__ __launch_bounds__(256) void transpose_v_paged_kernel(const uint16_t* __restrict__ v_pool,
+                                                                uint16_t* __restrict__ vt, PrefillPaged pg, int Hkv,
+                                                                int tiles_total) {
+    __shared__ uint16_t sm[kTile][kHeadDim + 2];
+    const int b = blockIdx.z, hk = blockIdx.y, jt = blockIdx.x;
+    const int len = pg.seq_lens[b];
+    if (jt * kTile >= len) return;
+    const int phys = pg.page_table[(size_t)b * pg.max_pages + jt];
+    const uint16_t* src = v_pool + ((size_t)phys * Hkv + hk) * kTile * kHeadDim;
+    for (int idx = threadIdx.x; idx < kTile * kHeadDim; idx += 256) {
+        const int key = idx / kHeadDim, d = idx % kHeadDim;
+        sm[key][d] = jt * kTile + key < len ? src[idx] : (uint16_t)0;
+    }
+    __syncthreads();
+    uint16_t* dst = vt + ((size_t)hk * tiles_total + (size_t)b * pg.max_pages + jt) * kHeadDim * kTile;
+    for (int idx = threadIdx.x; idx < kTile * kHeadDim; idx += 256) {
+        const int d = idx / kTile, key = idx % kTile;
+        const int sl = vt_slot(key);
+        dst[(size_t)d * kTile + v_chunk_pos(d, sl / 8) * 8 + sl % 8] = sm[key][d];
     }
 }
 
@@ -219,11 +255,14 @@ template <class T> struct Ones;
 template <> struct Ones<F16> { static constexpr uint32_t pair = 0x3c003c00u; };
 template <> struct Ones<BF16> { static constexpr uint32_t pair = 0x3f803f80u; };
 
-template <class T, bool MASKED>
+enum PrefillMode { kPlain = 0, kMasked = 1, kPaged = 2 };
+
+template <class T, int MODE>
 __global__ __launch_bounds__(kPrefillThreads, 512 / kPrefillThreads) void sparse_prefill_kernel(
     LayerParams lp, const uint16_t* __restrict__ q, const uint16_t* __restrict__ k, const uint16_t* __restrict__ vt,
     const int* __restrict__ cu_seqlens, int batch, int blocks_per_seq, int tiles_total, uint16_t* __restrict__ out,
-    float* __restrict__ lse_out, int total_tokens, PrefillSchedule sched, PrefillMask mk) {
+    float* __restrict__ lse_out, int total_tokens, PrefillSchedule sched, PrefillMask mk, PrefillPaged pg) {
+    constexpr bool MASKED = MODE == kMasked, PAGED = MODE == kPaged;
     // Two stages of (K tile, V^T tile).  Four separate arrays, and a loop unrolled over the two stages,
     // so that the compiler can tell the tile being read from the tile being filled and does not wait
     // for the loads in flight before every operand read.
@@ -245,9 +284,14 @@ __global__ __launch_bounds__(kPrefillThreads, 512 / kPrefillThreads) void sparse
     if (!real) return;
     const int h = hk * lp.group + hh;
     const int b = rank % batch;
-    const int qblk = blocks_per_seq - 1 - rank / batch;
-    const int start = cu_seqlens[b], len = cu_seqlens[b + 1] - start;
+    // start: row of the sequence's first query in q / out; len: keys of the sequence; first: position of
+    // that first query (0 unless the keys come from a paged cache that already holds earlier tokens)
+    const int start = cu_seqlens[b];
+    const int len = PAGED ? pg.seq_lens[b] : cu_seqlens[b + 1] - start;
+    const int first = PAGED ? len - (cu_seqlens[b + 1] - start) : 0;
+    const int qblk = first / kRowsPerBlock + blocks_per_seq - 1 - rank / batch;
     if (qblk * kRowsPerBlock >= len) return;
+    if (PAGED && first >= len) return;  // a sequence without queries in this chunk
 
     const int tid = threadIdx.x, lane = tid % kWave, wave = tid / kWave;
     const int n = lane % 32, half = lane / 32;
@@ -256,7 +300,7 @@ __global__ __launch_bounds__(kPrefillThreads, 512 / kPrefillThreads) void sparse
     const int row0 = (wave % 2) * 32;    // first row of the wave inside the mask tile
     const int n_qtiles = ceil_div(len, kTile);
     const int iq_last = min(qblk * kTilesPerBlock + kTilesPerBlock - 1, n_qtiles - 1);  // last mask tile of the block that holds rows
-    const bool wave_has_rows = iq * kTile + row0 < len;
+    const bool wave_has_rows = iq * kTile + row0 < len && iq * kTile + row0 + 32 > first;
 
     // key tiles the block visits: [0, sink_end) and [band_begin, iq_last]
     int sink_end, band_begin;
@@ -281,7 +325,7 @@ __global__ __launch_bounds__(kPrefillThreads, 512 / kPrefillThreads) void sparse
     // ---- Q^T operand: lane (n, half) holds Q[row][16 kk + 8 half .. + 8]
     uint4 qreg[8];
     {
-        const int row = min(iq * kTile + row0 + n, len - 1);
+        const int row = min(max(iq * kTile + row0 + n, first), len - 1) - first;
         const uint4* src = reinterpret_cast<const uint4*>(q + ((size_t)(start + row) * lp.H + h) * kHeadDim);
 #pragma unroll
         for (int kk = 0; kk < 8; ++kk) qreg[kk] = src[kk * 2 + half];
@@ -301,12 +345,16 @@ __global__ __launch_bounds__(kPrefillThreads, 512 / kPrefillThreads) void sparse
     float m_run = -INFINITY, l_run = 0.f;  // running maximum (scaled, base 2) and sum of this lane's query row
 
     // ---- staging: every wave issues two direct-to-LDS loads of 1 KiB per tile and operand
-    const uint16_t* kbase = k + ((size_t)start * lp.Hkv + hk) * kHeadDim;
-    const uint16_t* vtbase = vt + ((size_t)hk * tiles_total + tile_base(start, b)) * kHeadDim * kTile;
+    // contiguous keys: tile jt starts jt * 64 rows after the sequence's first row; paged keys: tile jt is
+    // the slab of (page_table[b][jt], hk), rows 256 bytes apart
+    const uint16_t* kbase = PAGED ? pg.k_pool + (size_t)hk * kTile * kHeadDim : k + ((size_t)start * lp.Hkv + hk) * kHeadDim;
+    const uint16_t* vtbase = vt + ((size_t)hk * tiles_total + (PAGED ? b * pg.max_pages : tile_base(start, b))) * kHeadDim * kTile;
+    const int* page_row = PAGED ? pg.page_table + (size_t)b * pg.max_pages : nullptr;
     // lane `lane` of load i of this wave fills slot (2 wave + i) * 64 + lane of the tile.  Addresses are a
     // wave-uniform 64-bit tile base (scalar arithmetic) plus a 32-bit lane offset that does not depend
     // on the tile, except in the ragged last tile of a sequence where rows past the end are clamped.
-    const unsigned k_row_bytes = (unsigned)__builtin_amdgcn_readfirstlane(lp.Hkv * kHeadDim * 2);
+    const unsigned k_row_bytes = PAGED ? kHeadDim * 2u : (unsigned)__builtin_amdgcn_readfirstlane(lp.Hkv * kHeadDim * 2);
+    const unsigned long long k_page_bytes = (unsigned long long)lp.Hkv * kTile * kHeadDim * 2;
     const int krow0 = wave * (4 * kDmaLoads) + lane / 16;  // K row of load 0; load i takes row + 4 i
     unsigned kofs[kDmaLoads], vofs[kDmaLoads];
 #pragma unroll
@@ -317,11 +365,13 @@ __global__ __launch_bounds__(kPrefillThreads, 512 / kPrefillThreads) void sparse
     const unsigned lds_wave = (unsigned)__builtin_amdgcn_readfirstlane(wave * kDmaLoads * 1024);
     const unsigned long long kbase_u = uniform64((unsigned long long)kbase), vtbase_u = uniform64((unsigned long long)vtbase);
     const int len_u = __builtin_amdgcn_readfirstlane(len);
-    auto fetch = [&](unsigned char* kd, unsigned char* vd, int jt) {
+    auto fetch = [&](unsigned char* kd, unsigned char* vd, int jt, int phys) {
         jt = __builtin_amdgcn_readfirstlane(jt);
-        const unsigned long long ktile = kbase_u + (unsigned long long)jt * (kTile * k_row_bytes);
+        const unsigned long long ktile =
+            PAGED ? kbase_u + (unsigned long long)(unsigned)__builtin_amdgcn_readfirstlane(phys) * k_page_bytes
+                  : kbase_u + (unsigned long long)jt * (kTile * k_row_bytes);
         const unsigned long long vtile = vtbase_u + (unsigned long long)jt * (kHeadDim * kTile * 2);
-        const int rows_left = len_u - jt * kTile;
+        const int rows_left = PAGED ? kTile : len_u - jt * kTile;  // a page is readable to its end
 #pragma unroll
         for (int i = 0; i < kDmaLoads; ++i) {
             unsigned ko = kofs[i];
@@ -339,6 +389,8 @@ __global__ __launch_bounds__(kPrefillThreads, 512 / kPrefillThreads) void sparse
         return it < sink_end ? it : band_begin + (it - sink_end);
     };
     int e_cur = n_visit > 0 ? entry_of(0) : 0, e_nxt = n_visit > 1 ? entry_of(1) : 0;
+    // physical pages of the tiles to come, looked up two steps ahead of the loads that need them
+    int ph_cur = PAGED && n_visit > 0 ? page_row[e_cur] : 0, ph_nxt = PAGED && n_visit > 1 ? page_row[e_nxt] : 0;
 
     // loop-invariant operand offsets of this lane inside a tile
     int koff[8], voff[4];
@@ -349,8 +401,10 @@ __global__ __launch_bounds__(kPrefillThreads, 512 / kPrefillThreads) void sparse
 
     auto tile_step = [&](int it, const unsigned char* ks, const unsigned char* vs, unsigned char* kd, unsigned char* vd) {
         const int e_new = it + 2 < n_visit ? entry_of(it + 2) : 0;  // requested two steps ahead of its use
+        const int ph_new = PAGED && it + 2 < n_visit ? page_row[e_new] : 0;
         const int jt = e_cur & ((1 << kKeepShift) - 1);
-        if (it + 1 < n_visit) fetch(kd, vd, e_nxt & ((1 << kKeepShift) - 1));
+        if (it + 1 < n_visit) fetch(kd, vd, e_nxt & ((1 << kKeepShift) - 1), ph_nxt);
+        ph_nxt = ph_new;
         // does this wave's mask tile keep key tile jt?
         bool keep = wave_has_rows && jt <= iq;
         if (MASKED && lst)
@@ -444,7 +498,7 @@ __global__ __launch_bounds__(kPrefillThreads, 512 / kPrefillThreads) void sparse
         __syncthreads();  // the next tile has landed and this one is free
     };
 
-    if (n_visit > 0) fetch(k_lds0, v_lds0, e_cur & ((1 << kKeepShift) - 1));
+    if (n_visit > 0) fetch(k_lds0, v_lds0, e_cur & ((1 << kKeepShift) - 1), ph_cur);
     dma_wait();
     __syncthreads();
     for (int it = 0; it < n_visit; it += 2) {
@@ -456,8 +510,9 @@ __global__ __launch_bounds__(kPrefillThreads, 512 / kPrefillThreads) void sparse
     if (!wave_has_rows) return;
     // ---- epilogue: lane (n, half) holds O^T[d][q] for d = 32 db + 8 (i / 4) + 4 half + i % 4
     const float lt = halves_sum(l_run);
-    const int row = iq * kTile + row0 + n;
-    if (row >= len) return;
+    const int pos = iq * kTile + row0 + n;
+    if (pos >= len || pos < first) return;
+    const int row = pos - first;
     const float inv = lt > 0.f ? 1.f / lt : 0.f;  // a row that keeps nothing (possible with a listed mask) gives 0
     uint16_t* dst = out + ((size_t)(start + row) * lp.H + h) * kHeadDim;
 #pragma unroll
@@ -475,6 +530,26 @@ __global__ __launch_bounds__(kPrefillThreads, 512 / kPrefillThreads) void sparse
 }
 
 int prefill_tile_slots(int total_tokens, int batch) { return total_tokens / kTile + batch; }
+
+PrefillSchedule make_schedule(const LayerParams& lp, int blocks_per_seq, int batch) {
+    PrefillSchedule sched;
+    sched.qblocks_total = blocks_per_seq * batch;
+    for (int c = 0; c < 2; ++c) {
+        HeadClass& hc = sched.cls[c];
+        hc.heads = 0;
+        for (int hk = 0; hk < lp.Hkv; ++hk)
+            if ((int)((lp.streaming_mask >> hk) & 1ull) == c) hc.kv_head[hc.heads++] = (unsigned char)hk;
+        hc.swizzled = hc.heads > 0 && kXcds % hc.heads == 0;
+        hc.slices = hc.swizzled ? kXcds / hc.heads : 1;
+        if (hc.heads == 0)
+            hc.items_per_xcd = 0;
+        else if (hc.swizzled)
+            hc.items_per_xcd = lp.group * ((sched.qblocks_total + hc.slices - 1) / hc.slices);
+        else
+            hc.items_per_xcd = (hc.heads * lp.group * sched.qblocks_total + kXcds - 1) / kXcds;
+    }
+    return sched;
+}
 
 size_t vt_bytes(const LayerParams& lp, int total_tokens, int batch) {
     return (size_t)lp.Hkv * prefill_tile_slots(total_tokens, batch) * kHeadDim * kTile * sizeof(uint16_t);
@@ -508,35 +583,61 @@ hipError_t launch_prefill(const LayerParams& lp, const void* q, const void* k, c
         e = hipGetLastError();
         if (e != hipSuccess) return e;
     }
-    PrefillSchedule sched;
-    sched.qblocks_total = blocks_per_seq * batch;
-    for (int c = 0; c < 2; ++c) {
-        HeadClass& hc = sched.cls[c];
-        hc.heads = 0;
-        for (int hk = 0; hk < lp.Hkv; ++hk)
-            if ((int)((lp.streaming_mask >> hk) & 1ull) == c) hc.kv_head[hc.heads++] = (unsigned char)hk;
-        hc.swizzled = hc.heads > 0 && kXcds % hc.heads == 0;
-        hc.slices = hc.swizzled ? kXcds / hc.heads : 1;
-        if (hc.heads == 0)
-            hc.items_per_xcd = 0;
-        else if (hc.swizzled)
-            hc.items_per_xcd = lp.group * ((sched.qblocks_total + hc.slices - 1) / hc.slices);
-        else
-            hc.items_per_xcd = (hc.heads * lp.group * sched.qblocks_total + kXcds - 1) / kXcds;
-    }
+    const PrefillSchedule sched = make_schedule(lp, blocks_per_seq, batch);
     const int grid = kXcds * (sched.cls[0].items_per_xcd + sched.cls[1].items_per_xcd);
+    const PrefillPaged pg = {};
     if (mask)
-        hipLaunchKernelGGL((sparse_prefill_kernel<T, true>), dim3(grid), dim3(kPrefillThreads), 0, stream, lp,
+        hipLaunchKernelGGL((sparse_prefill_kernel<T, kMasked>), dim3(grid), dim3(kPrefillThreads), 0, stream, lp,
                            reinterpret_cast<const uint16_t*>(q), reinterpret_cast<const uint16_t*>(k), vt, cu_seqlens, batch,
-                           blocks_per_seq, tiles_total, reinterpret_cast<uint16_t*>(out), lse_out, total_tokens, sched, mk);
+                           blocks_per_seq, tiles_total, reinterpret_cast<uint16_t*>(out), lse_out, total_tokens, sched, mk, pg);
     else
-        hipLaunchKernelGGL((sparse_prefill_kernel<T, false>), dim3(grid), dim3(kPrefillThreads), 0, stream, lp,
+        hipLaunchKernelGGL((sparse_prefill_kernel<T, kPlain>), dim3(grid), dim3(kPrefillThreads), 0, stream, lp,
                            reinterpret_cast<const uint16_t*>(q), reinterpret_cast<const uint16_t*>(k), vt, cu_seqlens, batch,
-                           blocks_per_seq, tiles_total, reinterpret_cast<uint16_t*>(out), lse_out, total_tokens, sched, mk);
+                           blocks_per_seq, tiles_total, reinterpret_cast<uint16_t*>(out), lse_out, total_tokens, sched, mk, pg);
+    return hipGetLastError();
+}
+
+template <class T>
+hipError_t launch_prefill_paged(const LayerParams& lp, const PagedParams& kv, const void* q, const int* cu_q,
+                                int total_new, int max_new_per_seq, int max_seqlen, void* out, float* lse_out,
+                                void* workspace, hipStream_t stream) {
+    PrefillPaged pg;
+    pg.k_pool = reinterpret_cast<const uint16_t*>(kv.k_pool);
+    pg.page_table = kv.page_table;
+    pg.seq_lens = kv.seq_lens;
+    pg.max_pages = kv.max_pages;
+    const int tiles_total = kv.batch * kv.max_pages;
+    uint16_t* vt = reinterpret_cast<uint16_t*>(workspace);
+    const int max_tiles = std::min(kv.max_pages, (max_seqlen + kTile - 1) / kTile);
+    hipLaunchKernelGGL(transpose_v_paged_kernel<T>, dim3(max_tiles, lp.Hkv, kv.batch), dim3(256), 0, stream,
+                       reinterpret_cast<const uint16_t*>(kv.v_pool), vt, pg, lp.Hkv, tiles_total);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    // the chunk's rows start anywhere inside a 256-row block: one block more than the chunk length needs
+    const int blocks_per_seq = (max_new_per_seq + kRowsPerBlock - 1) / kRowsPerBlock + 1;
+    const PrefillSchedule sched = make_schedule(lp, blocks_per_seq, kv.batch);
+    const int grid = kXcds * (sched.cls[0].items_per_xcd + sched.cls[1].items_per_xcd);
+    const PrefillMask mk = {};
+    hipLaunchKernelGGL((sparse_prefill_kernel<T, kPaged>), dim3(grid), dim3(kPrefillThreads), 0, stream, lp,
+                       reinterpret_cast<const uint16_t*>(q), nullptr, vt, cu_q, kv.batch, blocks_per_seq, tiles_total,
+                       reinterpret_cast<uint16_t*>(out), lse_out, total_new, sched, mk, pg);
     return hipGetLastError();
 }
 
 }  // namespace
+
+size_t paged_prefill_workspace_bytes(const LayerParams& lp, int batch, int max_pages) {
+    return (size_t)lp.Hkv * batch * max_pages * kHeadDim * kTile * sizeof(uint16_t);
+}
+
+hipError_t launch_sparse_prefill_paged(int dtype, const LayerParams& lp, const PagedParams& kv, const void* q,
+                                       const int* cu_q, int total_new, int max_new_per_seq, int max_seqlen, void* out,
+                                       float* lse_out, void* workspace, hipStream_t stream) {
+    return dtype == 0 ? launch_prefill_paged<F16>(lp, kv, q, cu_q, total_new, max_new_per_seq, max_seqlen, out, lse_out,
+                                                  workspace, stream)
+                      : launch_prefill_paged<BF16>(lp, kv, q, cu_q, total_new, max_new_per_seq, max_seqlen, out, lse_out,
+                                                   workspace, stream);
+}
 
 size_t prefill_workspace_bytes(const LayerParams& lp, int total_tokens, int batch) {
     return vt_bytes(lp, total_tokens, batch);

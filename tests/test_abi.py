@@ -140,6 +140,13 @@ def test_invalid_arguments_are_rejected_on_the_host(L):
     assert _rc(lambda: L.lserve_sparse_prefill_masked(desc(), good_mask, q, kk, kk, cu, 2, out, None, ws[:need - 16],
                                                       stream)) == -3
     assert L.lserve_masked_prefill_workspace_bytes(desc(), 1, 2, 2, 0, 1) == 0
+    # paged prefill: chunk bounds, two-way caches are not supported, workspace
+    assert _rc(lambda: L.lserve_sparse_prefill_paged(desc(), kv, q, cu4, 0, 64, out, None, ws, stream)) == -1
+    assert _rc(lambda: L.lserve_sparse_prefill_paged(desc(), kv, q, cu4, 2, 1, out, None, ws, stream)) == -1
+    assert _rc(lambda: L.lserve_sparse_prefill_paged(desc(), dense_only, q, cu4, 2, 64, out, None, ws, stream)) == -1
+    assert _rc(lambda: L.lserve_sparse_prefill_paged(desc(page_size=32), kv, q, cu4, 2, 64, out, None, ws, stream)) == -2
+    assert _rc(lambda: L.lserve_sparse_prefill_paged(desc(), kv, q, cu4, 2, 64, out, None, ws[:64], stream)) == -3
+    assert L.lserve_paged_prefill_workspace_bytes(desc(), 2, 4) == 2 * 2 * 4 * 128 * 64 * 2
 
 
 def test_product_path_does_not_reach_for_the_oracle():

@@ -667,3 +667,57 @@ def test_masked_prefill_with_analytic_tiles_is_bit_identical_to_the_unmasked_cal
     out_u, lse_u = _prefill(L, w, pin, dev)
     assert torch.equal(out_m.view(torch.int16), out_u.view(torch.int16))
     assert torch.equal(lse_m, lse_u)
+
+
+# ---- chunked prefill over the paged cache -----------------------------------------------------------------
+
+@pytest.mark.parametrize("dtype", ["fp16", "bf16"])
+@pytest.mark.parametrize("case", [
+    dict(lengths=(700, 64, 1000), chunks=(700, 64, 1000)),   # the whole prompt: must equal the contiguous call
+    dict(lengths=(700, 64, 1000), chunks=(257, 1, 0)),       # chunk starts off every boundary; a one-token chunk; an idle sequence
+    dict(lengths=(2049,), chunks=(513,)),
+    dict(lengths=(300, 1300), chunks=(64, 256)),             # chunks aligned to tiles / blocks
+])
+def test_paged_chunk_prefill_matches_oracle_on_every_row(dtype, case):
+    L = _lib()
+    dev = torch.device("cuda:0")
+    lengths, chunks = case["lengths"], case["chunks"]
+    B_ = len(lengths)
+    w = Workload(name="pp", batch=B_, num_q_heads=4, num_kv_heads=2, dtype=dtype, streaming_kv_heads=(0,),
+                 sink_tokens=64, local_tokens=192, seed=31)
+    pin = make_prefill_inputs(w, lengths=lengths)
+    NP = 64
+    max_pages = max(-(-l // NP) for l in lengths) + 1
+    g = torch.Generator().manual_seed(17)
+    page_table = torch.randperm(B_ * max_pages + 2, generator=g)[:B_ * max_pages].to(torch.int32).reshape(B_, max_pages)
+    k_pool = torch.full((B_ * max_pages + 2, 2, NP, 128), float("nan"), dtype=pin.k.dtype)  # unused slots poison the result
+    v_pool = torch.full_like(k_pool, float("nan"))
+    scatter_prefill_kv_to_pages(pin.k, pin.v, pin.cu_seqlens, k_pool, v_pool, page_table)
+    qs = []
+    for b in range(B_):
+        a = int(pin.cu_seqlens[b]) + lengths[b] - chunks[b]
+        qs.append(pin.q[a:a + chunks[b]])
+    qc = torch.cat(qs).contiguous()
+    total_new = qc.shape[0]
+    cu_q = np.concatenate([[0], np.cumsum(chunks)]).astype(np.int32)
+    desc = L.AttnDesc(w.num_q_heads, w.num_kv_heads, w.streaming_flags(), dtype=w.torch_dtype,
+                      sink_tokens=w.sink_tokens, local_tokens=w.local_tokens)
+    pad4 = lambda a: torch.cat([torch.as_tensor(a, dtype=torch.int32), torch.zeros(4, dtype=torch.int32)]).to(dev)[:len(a)]
+    kv = L.PagedKV(k_pool.to(dev), v_pool.to(dev), None, page_table.to(dev), pad4(list(lengths)))
+    ws = torch.empty((L.lserve_paged_prefill_workspace_bytes(desc, B_, max_pages),), dtype=torch.uint8, device=dev)
+    qd = torch.cat([qc, torch.zeros((1, 4, 128), dtype=qc.dtype)]).to(dev)[:total_new]
+    out = torch.full((total_new, 4, 128), float("nan"), dtype=qc.dtype, device=dev)
+    lse = torch.full((4, total_new), float("nan"), dtype=torch.float32, device=dev)
+    L.lserve_sparse_prefill_paged(desc, kv, qd, pad4(cu_q), max(chunks), max(lengths), out, lse, ws)
+    torch.cuda.synchronize()
+    tok = np.repeat(np.arange(total_new, dtype=np.int32), 4)
+    head = np.tile(np.arange(4, dtype=np.int32), total_new)
+    # the oracle reads the same pools; NaN in unused slots must not reach it either
+    ref, lse_ref = oracle.paged_prefill_rows(qc, k_pool, v_pool, page_table, np.asarray(lengths, np.int32), cu_q,
+                                             w.streaming_flags(), w.sink_tokens, w.local_tokens, tok, head)
+    assert_attention_close(out, ref.reshape(total_new, 4, -1), f"paged prefill {dtype} {case}")
+    assert_lse_close(lse.t().contiguous(), lse_ref.reshape(total_new, 4), "paged prefill lse")
+    if chunks == lengths:
+        out_c, lse_c = _prefill(L, w, pin, dev)
+        assert torch.equal(out.view(torch.int16), out_c.view(torch.int16))
+        assert torch.equal(lse, lse_c)
