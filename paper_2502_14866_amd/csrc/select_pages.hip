@@ -30,13 +30,16 @@ __global__ __launch_bounds__(kScoreThreads) void page_score_kernel(LayerParams l
                                                                     const int* __restrict__ stats_valid_len,
                                                                     float* __restrict__ scores, HeadList heads) {
     const int b = blockIdx.z;
-    const int hk = heads.idx[blockIdx.y];
     const int lane = threadIdx.x % kWave, wave = threadIdx.x / kWave;
     const int r = lane / 16, c = lane % 16;
     const int L = kv.seq_lens[b];
     const int P = ceil_div(L, lp.NP);
-    const int p = (blockIdx.x * (kScoreThreads / kWave) + wave) * 4 + r;
+    // (page, selecting head) pairs with the head running fastest: the statistics of the heads of one page
+    // are neighbours in memory, so the rows of a wave read one contiguous stretch
+    const int pair = (blockIdx.x * (kScoreThreads / kWave) + wave) * 4 + r;
+    const int p = pair / heads.count;
     if (p >= kv.max_pages) return;
+    const int hk = heads.idx[pair % heads.count];
     float* dst = scores + ((size_t)b * lp.Hkv + hk) * kv.max_pages + p;
     if (p >= P) {  // whole row (16 lanes) takes this branch together
         if (c == 0) *dst = 0.f;
@@ -280,7 +283,7 @@ __global__ __launch_bounds__(kTopkThreads) void topk_pages_kernel(LayerParams lp
 template <class T>
 hipError_t launch_score(const LayerParams& lp, const PagedParams& kv, const void* q, const int* stats_valid_len,
                         float* scores, const HeadList& selecting, hipStream_t stream) {
-    dim3 grid(ceil_div(kv.max_pages, kPagesPerBlock), selecting.count, kv.batch);
+    dim3 grid(ceil_div(kv.max_pages * selecting.count, kPagesPerBlock), 1, kv.batch);
     dim3 block(kScoreThreads);
     const uint4* q4 = reinterpret_cast<const uint4*>(q);
 #define LSERVE_SCORE_CASE(N)                                                                                   \
