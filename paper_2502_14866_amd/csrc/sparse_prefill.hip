@@ -335,6 +335,16 @@ __global__ __launch_bounds__(kPrefillThreads, 512 / kPrefillThreads) void sparse
 #pragma unroll
         for (int kk = 0; kk < 8; ++kk)
             asm volatile("" : "+v"(qreg[kk].x), "+v"(qreg[kk].y), "+v"(qreg[kk].z), "+v"(qreg[kk].w));
+        // The softmax scale (times log2 e) goes into Q once, so the scores leave the matrix pipe ready for
+        // exp2.  The extra rounding of Q to 16 bit moves a logit by about 2^-9 (bf16) or 2^-11 (fp16) of its
+        // size times 0.13, an order below the rounding of the softmax weights themselves.
+#pragma unroll
+        for (int kk = 0; kk < 8; ++kk) {
+            uint32_t* w = reinterpret_cast<uint32_t*>(&qreg[kk]);
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+                w[i] = Elem<T>::pack(Elem<T>::lo(w[i]) * lp.sm_scale_log2, Elem<T>::hi(w[i]) * lp.sm_scale_log2);
+        }
     }
 
     float16_t acc[4];
@@ -343,6 +353,11 @@ __global__ __launch_bounds__(kPrefillThreads, 512 / kPrefillThreads) void sparse
 #pragma unroll
         for (int i = 0; i < 16; ++i) acc[db][i] = 0.f;
     float m_run = -INFINITY, l_run = 0.f;  // running maximum (scaled, base 2) and sum of this lane's query row
+    // The score products start from -m_run instead of 0 (the accumulator input of the first product), so a
+    // tile whose maxima do not exceed the running ones needs no subtraction before exp2; 0 while m_run = -inf.
+    float16_t neg_m;
+#pragma unroll
+    for (int i = 0; i < 16; ++i) neg_m[i] = 0.f;
 
     // ---- staging: every wave issues two direct-to-LDS loads of 1 KiB per tile and operand
     // contiguous keys: tile jt starts jt * 64 rows after the sequence's first row; paged keys: tile jt is
@@ -426,12 +441,10 @@ __global__ __launch_bounds__(kPrefillThreads, 512 / kPrefillThreads) void sparse
 #pragma unroll
                 for (int kb = 0; kb < 2; ++kb)
                     ka[kk][kb] = *reinterpret_cast<const uint4*>(ks + kb * 32 * kKRowBytes + koff[kk]);
+            s[0] = Mfma<T>::run(ka[0][0], qreg[0], neg_m);
+            s[1] = Mfma<T>::run(ka[0][1], qreg[0], neg_m);
 #pragma unroll
-            for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-                for (int i = 0; i < 16; ++i) s[kb][i] = 0.f;
-#pragma unroll
-            for (int kk = 0; kk < 8; ++kk) {
+            for (int kk = 1; kk < 8; ++kk) {
                 s[0] = Mfma<T>::run(ka[kk][0], qreg[kk], s[0]);
                 s[1] = Mfma<T>::run(ka[kk][1], qreg[kk], s[1]);
             }
@@ -457,23 +470,31 @@ __global__ __launch_bounds__(kPrefillThreads, 512 / kPrefillThreads) void sparse
             float mx = fmaxf(s[0][0], s[1][0]);
 #pragma unroll
             for (int i = 1; i < 16; ++i) mx = __builtin_fmaxf(__builtin_fmaxf(mx, s[0][i]), s[1][i]);  // v_max3_f32
-            mx = halves_max(mx) * lp.sm_scale_log2;
-            const float m_new = fmaxf(m_run, mx);
-            if (__any(m_new > m_run)) {  // rescale only when some row's maximum moved
+            mx = halves_max(mx);  // relative to the running maximum (to 0 before the first kept tile)
+            if (__any(mx > 0.f || m_run == -INFINITY)) {  // some row's maximum moved: subtract and rescale
+                const float m_base = m_run == -INFINITY ? 0.f : m_run;
+                const float m_new = fmaxf(m_run, m_base + mx);
+                const float delta = m_new - m_base;                         // 0 for rows whose maximum stayed
                 const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);  // exp2(-inf) = 0 on the first tile
                 l_run *= alpha;
 #pragma unroll
                 for (int db = 0; db < 4; ++db)
 #pragma unroll
                     for (int i = 0; i < 16; ++i) acc[db][i] *= alpha;
+#pragma unroll
+                for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+                    for (int i = 0; i < 16; ++i) s[kb][i] -= delta;
                 m_run = m_new;
+#pragma unroll
+                for (int i = 0; i < 16; ++i) neg_m[i] = -m_new;
             }
             uint4 pb[2][2];  // P^T packed to 16 bit: [key block][16-key step]
 #pragma unroll
             for (int kb = 0; kb < 2; ++kb) {
                 float pf[16];
 #pragma unroll
-                for (int i = 0; i < 16; ++i) pf[i] = __builtin_amdgcn_exp2f(__builtin_fmaf(s[kb][i], lp.sm_scale_log2, -m_run));
+                for (int i = 0; i < 16; ++i) pf[i] = __builtin_amdgcn_exp2f(s[kb][i]);
                 pb[kb][0] = pack8<T>(pf);
                 pb[kb][1] = pack8<T>(pf + 8);
                 // row sum from the rounded weights, the same values the second product uses

@@ -30,10 +30,18 @@ def assert_attention_close(got: torch.Tensor, ref: np.ndarray, what: str = ""):
     return max_abs, max_rel
 
 
-def assert_lse_close(got: torch.Tensor, ref: np.ndarray, what: str = ""):
+# Log-sum-exp.  Decode keeps the query exact: 2e-3.  Prefill rounds the query times the softmax scale to the
+# storage type (unit roundoff u = 2^-11 for fp16, 2^-8 for bf16), which moves a logit of 128 N(0,1) products by
+# about 0.58 u (one sigma) and the log-sum-exp by at most the largest logit move: four sigma is 1.1e-3 for fp16
+# and 9e-3 for bf16.
+LSE_TOL_DECODE = 2e-3
+LSE_TOL_PREFILL = {"fp16": 2e-3, "bf16": 1.6e-2}
+
+
+def assert_lse_close(got: torch.Tensor, ref: np.ndarray, what: str = "", tol: float = LSE_TOL_DECODE):
     g = got.detach().to(torch.float64).cpu().numpy().reshape(ref.shape)
     err = np.abs(g - ref).max() if ref.size else 0.0
-    assert err <= 2e-3, f"{what}: lse error {err:.3e}"
+    assert err <= tol, f"{what}: lse error {err:.3e} > {tol}"
 
 
 def compare_selection(sel_gpu, cnt_gpu, sel_ref, cnt_ref, scores_ref, streaming_flags):
