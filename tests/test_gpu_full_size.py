@@ -77,6 +77,12 @@ def test_cfg4_long_context_decode_retrieves_needles():
     assert _run_decode_config("cfg4", seqs=(1, 3), steps=5) <= 1
 
 
+def test_more_than_8192_candidate_pages_take_the_top_k_path_that_ranks_from_memory():
+    """16-token pages at 140000 tokens: 8750 pages per sequence, more than the selector keeps in LDS."""
+    assert _run_decode_config("cfg4", seqs=(0, 1), steps=5, batch=2, context=140000, page_size=16,
+                              logical_page_size=16) <= 1
+
+
 def test_cfg5_ragged_mha_decode_sampled_sequences():
     assert _run_decode_config("cfg5", seqs=(0, 13, 31), steps=5) <= 1
 
