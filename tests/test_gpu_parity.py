@@ -61,6 +61,10 @@ WORKLOADS = {
     "page16_flat": dict(page_size=16, logical_page_size=16, lengths=(700, 333), budget_tokens=128, sink_tokens=16,
                         local_tokens=64),
     "group3": dict(num_q_heads=6, num_kv_heads=2, lengths=(1500, 2600), budget_tokens=512),
+    "hkv64": dict(num_q_heads=64, num_kv_heads=64, streaming_kv_heads=tuple(range(1, 64, 2)), lengths=(300, 70),
+                  budget_tokens=128, decode_steps=3),
+    "hkv64_n8": dict(num_q_heads=512, num_kv_heads=64, streaming_kv_heads=tuple(range(0, 64, 3)), lengths=(200, 129),
+                     budget_tokens=128, decode_steps=2),
 }
 
 
