@@ -725,3 +725,22 @@ def test_paged_chunk_prefill_matches_oracle_on_every_row(dtype, case):
         out_c, lse_c = _prefill(L, w, pin, dev)
         assert torch.equal(out.view(torch.int16), out_c.view(torch.int16))
         assert torch.equal(lse, lse_c)
+
+
+@pytest.mark.parametrize("heads", [(6, 3, (1,)), (16, 16, (0, 5, 6, 7, 8, 15)), (24, 3, ()), (5, 5, (0, 1, 2, 3, 4))])
+def test_prefill_head_layouts_that_do_not_divide_the_xcd_count(heads):
+    """Head counts for which the XCD-aware work order falls back to plain round-robin, all-dense and all-streaming."""
+    L = _lib()
+    dev = torch.device("cuda:0")
+    H, Hkv, streaming = heads
+    lengths = (321, 640)
+    w = Workload(name="ph", batch=2, num_q_heads=H, num_kv_heads=Hkv, dtype="fp16", streaming_kv_heads=streaming,
+                 sink_tokens=64, local_tokens=128, seed=37)
+    pin = make_prefill_inputs(w, lengths=lengths)
+    out, lse = _prefill(L, w, pin, dev)
+    total = sum(lengths)
+    tok = np.repeat(np.arange(total, dtype=np.int32), H)
+    head = np.tile(np.arange(H, dtype=np.int32), total)
+    ref, lse_ref = _oracle_rows(w, pin, tok, head)
+    assert_attention_close(out, ref.reshape(total, H, -1), f"prefill heads {heads}")
+    assert_lse_close(lse.t().contiguous(), lse_ref.reshape(total, H), "prefill lse", LSE_TOL_PREFILL["fp16"])
