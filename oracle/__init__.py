@@ -12,6 +12,9 @@ from .reference import (  # noqa: F401
     page_scores,
     select_pages,
     sparse_decode,
+    sparse_decode_values,
+    quantize_q8,
+    dequantize_q8,
     sparse_prefill_rows,
     block_mask_prefill_rows,
     paged_prefill_rows,

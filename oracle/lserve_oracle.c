@@ -271,13 +271,21 @@ void oracle_select_pages(const double *page_scores, const int32_t *seq_lens, int
  * Attended tokens = tokens u < L of those pages.  For each query head h of the group:
  *   score_u = scale * q_h . k_u,  out_h = sum_u softmax(score)_u * v_u,  lse_h = log sum_u exp(score_u).
  */
-void oracle_sparse_decode(const uint16_t *q, const uint16_t *k_pool, const uint16_t *v_pool,
-                          const int32_t *page_table, const int32_t *seq_lens,
-                          const int32_t *sel_pages, const int32_t *sel_count,
-                          const int32_t *sel_seq_len, int k_stride,
-                          const uint8_t *kv_head_is_streaming, int batch, int max_pages, int H,
-                          int Hkv, int D, int NP, int dtype, int sink_tokens, int local_tokens,
-                          double sm_scale, double *out, double *lse)
+/* Element of a KV pool: 16-bit storage, or (k64 / v64 given) a pool of doubles holding the values a
+ * quantised cache stands for. */
+static inline double pool_value(const uint16_t *p16, const double *p64, size_t idx, int dtype)
+{
+    return p64 ? p64[idx] : oracle_widen(p16[idx], dtype);
+}
+
+static void sparse_decode_any(const uint16_t *q, const uint16_t *k_pool, const uint16_t *v_pool,
+                              const double *k64, const double *v64,
+                              const int32_t *page_table, const int32_t *seq_lens,
+                              const int32_t *sel_pages, const int32_t *sel_count,
+                              const int32_t *sel_seq_len, int k_stride,
+                              const uint8_t *kv_head_is_streaming, int batch, int max_pages, int H,
+                              int Hkv, int D, int NP, int dtype, int sink_tokens, int local_tokens,
+                              double sm_scale, double *out, double *lse)
 {
     int n = H / Hkv;
     int s = ceil_div(sink_tokens, NP);
@@ -310,7 +318,7 @@ void oracle_sparse_decode(const uint16_t *q, const uint16_t *k_pool, const uint1
                 double dot = 0.0;
                 for (int c = 0; c < D; ++c)
                     dot += oracle_widen(qh[c], dtype) *
-                           oracle_widen(k_pool[pool_index(page, hk, t, c, Hkv, NP, D)], dtype);
+                           pool_value(k_pool, k64, pool_index(page, hk, t, c, Hkv, NP, D), dtype);
                 score[m] = dot * sm_scale;
                 pos[m] = p * NP + t;
                 ++m;
@@ -326,11 +334,39 @@ void oracle_sparse_decode(const uint16_t *q, const uint16_t *k_pool, const uint1
             double pr = exp(score[i] - mx) / denom;
             int page = page_table[(size_t)b * max_pages + pos[i] / NP];
             for (int c = 0; c < D; ++c)
-                o[c] += pr * oracle_widen(v_pool[pool_index(page, hk, pos[i] % NP, c, Hkv, NP, D)], dtype);
+                o[c] += pr * pool_value(v_pool, v64, pool_index(page, hk, pos[i] % NP, c, Hkv, NP, D), dtype);
         }
         if (lse) lse[(size_t)b * H + h] = mx + log(denom);
         free(use); free(score); free(pos);
     }
+}
+
+void oracle_sparse_decode(const uint16_t *q, const uint16_t *k_pool, const uint16_t *v_pool,
+                          const int32_t *page_table, const int32_t *seq_lens,
+                          const int32_t *sel_pages, const int32_t *sel_count,
+                          const int32_t *sel_seq_len, int k_stride,
+                          const uint8_t *kv_head_is_streaming, int batch, int max_pages, int H,
+                          int Hkv, int D, int NP, int dtype, int sink_tokens, int local_tokens,
+                          double sm_scale, double *out, double *lse)
+{
+    sparse_decode_any(q, k_pool, v_pool, NULL, NULL, page_table, seq_lens, sel_pages, sel_count,
+                      sel_seq_len, k_stride, kv_head_is_streaming, batch, max_pages, H, Hkv, D, NP,
+                      dtype, sink_tokens, local_tokens, sm_scale, out, lse);
+}
+
+/* The same decode over a quantised cache (Sec. 3.2, Sec. 3.6): the pools hold, as doubles, the values
+ * code * scale + zero that the stored bytes stand for; queries stay in 16-bit storage. */
+void oracle_sparse_decode_values(const uint16_t *q, const double *k_values, const double *v_values,
+                                 const int32_t *page_table, const int32_t *seq_lens,
+                                 const int32_t *sel_pages, const int32_t *sel_count,
+                                 const int32_t *sel_seq_len, int k_stride,
+                                 const uint8_t *kv_head_is_streaming, int batch, int max_pages,
+                                 int H, int Hkv, int D, int NP, int dtype, int sink_tokens,
+                                 int local_tokens, double sm_scale, double *out, double *lse)
+{
+    sparse_decode_any(q, NULL, NULL, k_values, v_values, page_table, seq_lens, sel_pages, sel_count,
+                      sel_seq_len, k_stride, kv_head_is_streaming, batch, max_pages, H, Hkv, D, NP,
+                      dtype, sink_tokens, local_tokens, sm_scale, out, lse);
 }
 
 /* ---- block-sparse prefill, one (token, head) row at a time (Eq. 1 + Sec. 3.1 mask) ----- */

@@ -174,6 +174,61 @@ def sparse_decode(q: torch.Tensor, k_pool: torch.Tensor, v_pool: torch.Tensor, p
     return out, lse
 
 
+def quantize_q8(x: torch.Tensor):
+    """8-bit asymmetric quantisation of KV features, one (scale, zero point) per token and KV head
+    (Sec. 3.2: scale factors and zero points are stored next to the token features).
+
+    x [..., D] in fp16 / bf16 storage.  With lo / hi the smallest / largest feature of a token:
+        zero  = fp16(lo)                     (saturating at the largest finite fp16)
+        scale = fp16((hi - zero) / 255)      (same saturation)
+        code  = clamp(rint((x - zero) / scale), 0, 255),   all codes 0 when scale == 0
+    and the stored bytes stand for the value code * scale + zero.  The arithmetic that decides a
+    code runs in IEEE fp32 with round-to-nearest-even, the precision of the GPU kernel, so codes
+    can be compared bit for bit.  Returns (codes uint8 [..., D], scale fp16 [...], zero fp16 [...]).
+    """
+    xf = x.detach().cpu().float().numpy().astype(np.float32)
+    big = np.float32(65504.0)
+    lo = xf.min(axis=-1)
+    hi = xf.max(axis=-1)
+    zero = np.clip(lo, -big, big).astype(np.float16)
+    zf = zero.astype(np.float32)
+    with np.errstate(over="ignore", invalid="ignore", divide="ignore"):
+        scale = np.minimum((hi - zf) / np.float32(255.0), big).astype(np.float16)
+        sf = scale.astype(np.float32)
+        t = (xf - zf[..., None]) / sf[..., None]
+        codes = np.clip(np.rint(t), 0.0, 255.0)
+    codes = np.where(sf[..., None] > 0, codes, 0.0).astype(np.uint8)
+    return codes, scale, zero
+
+
+def dequantize_q8(codes: np.ndarray, scale: np.ndarray, zero: np.ndarray) -> np.ndarray:
+    """Values the stored bytes stand for: code * scale + zero, exact in float64."""
+    return codes.astype(np.float64) * scale.astype(np.float64)[..., None] + zero.astype(np.float64)[..., None]
+
+
+def sparse_decode_values(q: torch.Tensor, k_values: np.ndarray, v_values: np.ndarray, page_table,
+                         seq_lens, sel_pages, sel_count, sel_seq_len, streaming_flags: Sequence[int],
+                         sink_tokens: int, local_tokens: int, sm_scale: Optional[float] = None):
+    """sparse_decode over pools given as float64 values [pages, Hkv, NP, D] (a dequantised cache)."""
+    B, H, D = q.shape
+    _, Hkv, NP, _ = k_values.shape
+    pt, sl = _i32(page_table), _i32(seq_lens)
+    sel, cnt, ssl = _i32(sel_pages), _i32(sel_count), _i32(sel_seq_len)
+    flags = _u8(streaming_flags)
+    out = np.zeros((B, H, D), dtype=np.float64)
+    lse = np.zeros((B, H), dtype=np.float64)
+    scale = float(sm_scale) if sm_scale else 1.0 / float(np.sqrt(D))
+    kv = np.ascontiguousarray(k_values, dtype=np.float64)
+    vv = np.ascontiguousarray(v_values, dtype=np.float64)
+    _load().oracle_sparse_decode_values(_p(_bits(q)), _p(kv), _p(vv), _p(pt), _p(sl), _p(sel), _p(cnt), _p(ssl),
+                                        ctypes.c_int(sel.shape[-1]), _p(flags), ctypes.c_int(B),
+                                        ctypes.c_int(pt.shape[1]), ctypes.c_int(H), ctypes.c_int(Hkv),
+                                        ctypes.c_int(D), ctypes.c_int(NP), ctypes.c_int(_dtype_code(q)),
+                                        ctypes.c_int(sink_tokens), ctypes.c_int(local_tokens),
+                                        ctypes.c_double(scale), _p(out), _p(lse))
+    return out, lse
+
+
 def sparse_prefill_rows(q: torch.Tensor, k: torch.Tensor, v: torch.Tensor, cu_seqlens,
                         streaming_flags: Sequence[int], tile: int, sink_tokens: int,
                         local_tokens: int, rows_token, rows_head,
