@@ -58,7 +58,7 @@ class _CPagedKV(ctypes.Structure):
         ("batch", ctypes.c_int32), ("max_pages_per_seq", ctypes.c_int32), ("num_pages", ctypes.c_int32),
         ("pool_heads", ctypes.c_int32),
         ("k_pool_stream", ctypes.c_void_p), ("v_pool_stream", ctypes.c_void_p), ("ring_table", ctypes.c_void_p),
-        ("num_pages_stream", ctypes.c_int32),
+        ("num_pages_stream", ctypes.c_int32), ("kv_bits", ctypes.c_int32),
     ]
 
 
@@ -151,6 +151,8 @@ class PagedKV:
     k_pool_stream: Optional[torch.Tensor] = None
     v_pool_stream: Optional[torch.Tensor] = None
     ring_table: Optional[torch.Tensor] = None
+    # 16: pools of the layer's 16-bit dtype [pages, heads, N_P, D]; 8: quantised pages, uint8 [pages, heads, 64 * D + 256]
+    kv_bits: int = 16
 
     def c(self):
         num_pages = 0
@@ -161,7 +163,7 @@ class PagedKV:
         self._c = _CPagedKV(_ptr(self.k_pool), _ptr(self.v_pool), _ptr(self.stats), _ptr(self.page_table),
                             _ptr(self.seq_lens), self.page_table.shape[0], self.page_table.shape[1], num_pages,
                             self.pool_heads, _ptr(self.k_pool_stream), _ptr(self.v_pool_stream),
-                            _ptr(self.ring_table), num_pages_stream)
+                            _ptr(self.ring_table), num_pages_stream, self.kv_bits)
         return ctypes.byref(self._c)
 
 

@@ -85,6 +85,9 @@ int make_paged(const lserve_paged_kv* kv, const LayerParams& lp, bool need_k, bo
         if (!aligned16(kv->k_pool_stream) || !aligned16(kv->v_pool_stream) || !aligned16(kv->ring_table))
             return LSERVE_ERR_INVALID_ARG;
     }
+    if (kv->kv_bits != 0 && kv->kv_bits != 16 && kv->kv_bits != 8) return LSERVE_ERR_INVALID_ARG;
+    pp->kv_bits = kv->kv_bits == 8 ? 8 : 16;
+    if (pp->kv_bits == 8 && lp.NP != 64) return LSERVE_ERR_UNSUPPORTED;
     const bool main_holds_all = pp->pool_heads == lp.Hkv;
     if (need_stream && n_stream > 0 && !main_holds_all && !pp->k_stream) return LSERVE_ERR_INVALID_ARG;
     return LSERVE_OK;
@@ -114,6 +117,7 @@ int lserve_build_page_stats(const lserve_attn_desc* desc, const lserve_paged_kv*
     if (rc) return rc;
     rc = make_paged(kv, lp, true, false, true, false, &pp);
     if (rc) return rc;
+    if (pp.kv_bits != 16) return LSERVE_ERR_UNSUPPORTED;  // statistics come from 16-bit keys (lserve_append_kv)
     if (max_tail_pages < 0 || !aligned16(start_pos)) return LSERVE_ERR_INVALID_ARG;
     const int tail = (max_tail_pages == 0 || max_tail_pages > pp.max_pages) ? pp.max_pages : max_tail_pages;
     hipError_t e = launch_page_stats(desc->dtype, lp, pp, start_pos, tail, selecting_heads(lp), (hipStream_t)stream);
@@ -144,6 +148,7 @@ int lserve_select_pages(const lserve_attn_desc* desc, const lserve_paged_kv* kv,
     if (rc) return rc;
     rc = make_paged(kv, lp, stats_valid_len != nullptr, false, true, false, &pp);
     if (rc) return rc;
+    if (stats_valid_len && pp.kv_bits != 16) return LSERVE_ERR_UNSUPPORTED;  // no 16-bit keys to rebuild from
     if (!q || !sel_pages || !sel_count || !sel_seq_len) return LSERVE_ERR_INVALID_ARG;
     if (!aligned16(q) || !aligned16(stats_valid_len) || !aligned16(sel_pages) || !aligned16(sel_count) || !aligned16(sel_seq_len) ||
         !aligned16(scores_out) || !aligned16(workspace))
@@ -226,6 +231,7 @@ int lserve_sparse_prefill_paged(const lserve_attn_desc* desc, const lserve_paged
     if (rc) return rc;
     if (lp.NP != 64) return LSERVE_ERR_UNSUPPORTED;
     if (pp.pool_heads != lp.Hkv || pp.k_stream) return LSERVE_ERR_UNSUPPORTED;  // one pool holding every head
+    if (pp.kv_bits != 16) return LSERVE_ERR_UNSUPPORTED;
     if (!q || !cu_q || !out) return LSERVE_ERR_INVALID_ARG;
     if (total_new <= 0 || max_new_per_seq <= 0 || max_new_per_seq > total_new || max_seqlen < max_new_per_seq)
         return LSERVE_ERR_INVALID_ARG;

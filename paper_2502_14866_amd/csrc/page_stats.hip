@@ -61,12 +61,57 @@ __global__ __launch_bounds__(kWave* kMaxLogical) void page_stats_kernel(LayerPar
     }
 }
 
+// 8-bit asymmetric quantisation of one token row held by the 16 lanes of a DPP row, eight features per
+// lane (Sec. 3.2: scale factor and zero point of a token are stored next to its features):
+//   zero = fp16(min), scale = fp16((max - zero) / 255), code = clamp(rint((x - zero) / scale), 0, 255),
+// every step in IEEE fp32 (true divisions) so that the codes do not depend on the machine.  Returns the
+// lane's eight codes and the token's (scale, zero) pair as two fp16 in one word.
+template <class T>
+__device__ __forceinline__ uint2 quantize_row_q8(const uint4& x, uint32_t& scale_zero) {
+    const uint32_t w[4] = {x.x, x.y, x.z, x.w};
+    float f[8];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        f[2 * i] = Elem<T>::lo(w[i]);
+        f[2 * i + 1] = Elem<T>::hi(w[i]);
+    }
+    float lo = f[0], hi = f[0];
+#pragma unroll
+    for (int i = 1; i < 8; ++i) {
+        lo = fminf(lo, f[i]);
+        hi = fmaxf(hi, f[i]);
+    }
+    lo = fminf(lo, dpp_f<kDppXor1>(lo));
+    hi = fmaxf(hi, dpp_f<kDppXor1>(hi));
+    lo = fminf(lo, dpp_f<kDppXor2>(lo));
+    hi = fmaxf(hi, dpp_f<kDppXor2>(hi));
+    lo = fminf(lo, dpp_f<kDppHalfMirror>(lo));
+    hi = fmaxf(hi, dpp_f<kDppHalfMirror>(hi));
+    lo = fminf(lo, dpp_f<kDppMirror>(lo));
+    hi = fmaxf(hi, dpp_f<kDppMirror>(hi));
+    constexpr float kBig = 65504.f;  // largest finite fp16
+    const _Float16 zero_h = (_Float16)fminf(fmaxf(lo, -kBig), kBig);
+    const float zero = (float)zero_h;
+    const _Float16 scale_h = (_Float16)fminf((hi - zero) / 255.0f, kBig);
+    const float scale = (float)scale_h;
+    uint32_t c[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+        const float t = fminf(fmaxf(__builtin_rintf((f[i] - zero) / scale), 0.f), 255.f);
+        c[i] = scale > 0.f ? (uint32_t)t : 0u;
+    }
+    const half2_t sz = {scale_h, zero_h};
+    scale_zero = __builtin_bit_cast(uint32_t, sz);
+    return make_uint2(c[0] | (c[1] << 8) | (c[2] << 16) | (c[3] << 24), c[4] | (c[5] << 8) | (c[6] << 16) | (c[7] << 24));
+}
+
 // KV write-back with the statistics updated in the same pass (Sec. 3.2, Sec. 3.5.2): one workgroup per
 // (physical page touched by the new tokens, KV head, sequence), one wavefront per logical page.  New
 // rows are copied into both pools with 16-byte accesses; for non-streaming heads the wave folds the
 // new keys into max / min rows and, when the logical page already held tokens, combines them with the
-// stored rows instead of re-reading the old keys.
-template <class T>
+// stored rows instead of re-reading the old keys.  BITS = 8 stores the rows quantised (one byte per feature,
+// then the page's (scale, zero) pairs); the statistics are still those of the 16-bit keys handed in.
+template <class T, int BITS>
 __global__ __launch_bounds__(kWave* kMaxLogical) void append_kv_kernel(LayerParams lp, PagedParams kv,
                                                                         const uint4* __restrict__ k_new,
                                                                         const uint4* __restrict__ v_new,
@@ -98,8 +143,8 @@ __global__ __launch_bounds__(kWave* kMaxLogical) void append_kv_kernel(LayerPara
         kdst = reinterpret_cast<uint4*>(const_cast<void*>(kv.k_pool));
         vdst = reinterpret_cast<uint4*>(const_cast<void*>(kv.v_pool));
     }
-    kdst += ph * lp.NP * (kHeadDim / 8);
-    vdst += ph * lp.NP * (kHeadDim / 8);
+    kdst += ph * slab_chunks(lp.NP, BITS);
+    vdst += ph * slab_chunks(lp.NP, BITS);
 
     float vmax[8], vmin[8];
 #pragma unroll
@@ -111,9 +156,21 @@ __global__ __launch_bounds__(kWave* kMaxLogical) void append_kv_kernel(LayerPara
         const size_t src = ((size_t)(src0 + t - s) * lp.Hkv + hk) * (kHeadDim / 8) + c;
         const uint4 x = k_new[src];
         const uint4 y = v_new[src];
-        const size_t dst = (size_t)(t - p * lp.NP) * (kHeadDim / 8) + c;
-        kdst[dst] = x;
-        vdst[dst] = y;
+        const int slot = t - p * lp.NP;
+        if (BITS == 16) {
+            const size_t dst = (size_t)slot * (kHeadDim / 8) + c;
+            kdst[dst] = x;
+            vdst[dst] = y;
+        } else {
+            uint32_t ksz, vsz;
+            const uint2 kc = quantize_row_q8<T>(x, ksz), vc = quantize_row_q8<T>(y, vsz);
+            reinterpret_cast<uint2*>(kdst)[(size_t)slot * (kHeadDim / 8) + c] = kc;
+            reinterpret_cast<uint2*>(vdst)[(size_t)slot * (kHeadDim / 8) + c] = vc;
+            if (c == 0) {
+                reinterpret_cast<uint32_t*>(kdst + lp.NP * (kHeadDim / 16))[slot] = ksz;
+                reinterpret_cast<uint32_t*>(vdst + lp.NP * (kHeadDim / 16))[slot] = vsz;
+            }
+        }
         const uint32_t w[4] = {x.x, x.y, x.z, x.w};
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
@@ -157,10 +214,16 @@ hipError_t launch_append_kv(int dtype, const LayerParams& lp, const PagedParams&
     dim3 block(kWave * lp.g);
     const uint4* k4 = reinterpret_cast<const uint4*>(k_new);
     const uint4* v4 = reinterpret_cast<const uint4*>(v_new);
-    if (dtype == 0)
-        hipLaunchKernelGGL(append_kv_kernel<F16>, grid, block, 0, stream, lp, kv, k4, v4, cu_new, start_pos);
-    else
-        hipLaunchKernelGGL(append_kv_kernel<BF16>, grid, block, 0, stream, lp, kv, k4, v4, cu_new, start_pos);
+    if (kv.kv_bits == 8) {
+        if (dtype == 0)
+            hipLaunchKernelGGL((append_kv_kernel<F16, 8>), grid, block, 0, stream, lp, kv, k4, v4, cu_new, start_pos);
+        else
+            hipLaunchKernelGGL((append_kv_kernel<BF16, 8>), grid, block, 0, stream, lp, kv, k4, v4, cu_new, start_pos);
+    } else if (dtype == 0) {
+        hipLaunchKernelGGL((append_kv_kernel<F16, 16>), grid, block, 0, stream, lp, kv, k4, v4, cu_new, start_pos);
+    } else {
+        hipLaunchKernelGGL((append_kv_kernel<BF16, 16>), grid, block, 0, stream, lp, kv, k4, v4, cu_new, start_pos);
+    }
     return hipGetLastError();
 }
 

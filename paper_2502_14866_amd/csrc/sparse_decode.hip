@@ -82,12 +82,21 @@ template <int NP> struct KeyMap {
     static constexpr int ITS = NP / 16;                              // 16-byte loads per lane and slab
 };
 
-template <int NP> struct Slabs {
+template <int NP, int BITS> struct Slabs;
+template <int NP> struct Slabs<NP, 16> {
     uint4 k[KeyMap<NP>::ITS], v[KeyMap<NP>::ITS];
+};
+// Quantised pages (N_P = 64 only): a token row is 128 one-byte codes.  The key map keeps four lanes per token,
+// each with two 16-byte chunks; the value map keeps 16 lanes per token row, each with eight codes.  The
+// (scale, zero) pairs of both the K and the V row of a token travel with the key map's lane of that token.
+template <> struct Slabs<64, 8> {
+    uint4 k[2];
+    uint2 v[4];
+    uint32_t ksz, vsz;
 };
 
 template <int NP>
-__device__ __forceinline__ void load_k(Slabs<NP>& s, const uint4* kslab, int tok0, int lane) {
+__device__ __forceinline__ void load_k(Slabs<NP, 16>& s, const uint4* kslab, int tok0, int lane) {
     using M = KeyMap<NP>;
 #pragma unroll
     for (int ps = 0; ps < M::PASSES; ++ps)
@@ -98,18 +107,33 @@ __device__ __forceinline__ void load_k(Slabs<NP>& s, const uint4* kslab, int tok
 }
 
 template <int NP>
-__device__ __forceinline__ void load_v(Slabs<NP>& s, const uint4* vslab, int tok0, int r, int c) {
+__device__ __forceinline__ void load_v(Slabs<NP, 16>& s, const uint4* vslab, int tok0, int r, int c, int) {
 #pragma unroll
     for (int it = 0; it < KeyMap<NP>::ITS; ++it) s.v[it] = vslab[(size_t)(tok0 + 4 * it + r) * (kHeadDim / 8) + c];
 }
 
+__device__ __forceinline__ void load_k(Slabs<64, 8>& s, const uint4* kslab, int tok0, int lane) {
+    const int tok = tok0 + lane / 4;
+#pragma unroll
+    for (int j = 0; j < 2; ++j) s.k[j] = kslab[(size_t)tok * (kHeadDim / 16) + 4 * j + lane % 4];
+    s.ksz = reinterpret_cast<const uint32_t*>(kslab + 64 * (kHeadDim / 16))[tok];
+}
+__device__ __forceinline__ void load_v(Slabs<64, 8>& s, const uint4* vslab, int tok0, int r, int c, int lane) {
+    const uint2* rows = reinterpret_cast<const uint2*>(vslab);
+#pragma unroll
+    for (int it = 0; it < 4; ++it) s.v[it] = rows[(size_t)(tok0 + 4 * it + r) * (kHeadDim / 8) + c];
+    s.vsz = reinterpret_cast<const uint32_t*>(vslab + 64 * (kHeadDim / 16))[tok0 + lane / 4];
+}
+
 template <int N> struct WaveState {
     float m[N], l[N], o[N][8];
+    float z[N];  // quantised values only: sum of weight * zero point, the same for every channel
     __device__ __forceinline__ void reset() {
 #pragma unroll
         for (int hh = 0; hh < N; ++hh) {
             m[hh] = -INFINITY;
             l[hh] = 0.f;
+            z[hh] = 0.f;
 #pragma unroll
             for (int i = 0; i < 8; ++i) o[hh][i] = 0.f;
         }
@@ -137,8 +161,8 @@ __device__ __forceinline__ float wave_max_of_quads(float x) {
 // One quarter page.  q_lds: [N][16] 16-byte chunks of the group's queries; p_lds: this wave's
 // [NP / 4][p_row(N)] weight buffer.  `valid` = tokens of the page below the sequence length.
 template <class T, int N, int NP>
-__device__ __forceinline__ void process_quarter_page(WaveState<N>& st, const uint4* q_lds, float* p_lds,
-                                                     Slabs<NP>& cur, int valid, int tok0, int lane,
+__device__ __forceinline__ void process_quarter_page(WaveState<N>& st, const uint4* q_lds, const float*, float* p_lds,
+                                                     Slabs<NP, 16>& cur, int valid, int tok0, int lane,
                                                      float scale_log2) {
     using M = KeyMap<NP>;
     constexpr int PR = p_row(N);
@@ -183,6 +207,7 @@ __device__ __forceinline__ void process_quarter_page(WaveState<N>& st, const uin
             const float alpha = __builtin_amdgcn_exp2f(st.m[hh] - pm);
             st.m[hh] = pm;
             st.l[hh] *= alpha;
+            st.z[hh] *= alpha;
 #pragma unroll
             for (int i = 0; i < 8; ++i) st.o[hh][i] *= alpha;
         }
@@ -228,26 +253,139 @@ __device__ __forceinline__ void process_quarter_page(WaveState<N>& st, const uin
     __builtin_amdgcn_wave_barrier();
 }
 
+// The same over a quantised quarter page.  q_lds holds the queries as fp16 whatever the storage type and
+// q_sum[h] the sum of query h's channels.  With k = code * scale + zero the logit of a token is
+//   q . k = scale * (q . code) + zero * sum(q).
+// Codes become fp16 without a conversion: byte c under the exponent byte 0x64 is the fp16 number 1024 + c,
+// so one byte permute yields two operands of the packed dot instruction, and the 1024 * sum(q) this adds
+// to every dot product is taken off again.  For values the weight is folded into the scale,
+//   sum_t p_t v_t = sum_t (p_t scale_t) code_t + sum_t p_t zero_t,
+// and the second sum, which no channel distinguishes, is kept as one number per query head.
+template <class T, int N>
+__device__ __forceinline__ void process_quarter_page(WaveState<N>& st, const uint4* q_lds, const float* q_sum,
+                                                     float* p_lds, Slabs<64, 8>& cur, int valid, int tok0, int lane,
+                                                     float scale_log2) {
+    constexpr int PR = p_row(N);
+    const int r = lane / 16;
+    float s[N];
+#pragma unroll
+    for (int hh = 0; hh < N; ++hh) s[hh] = 0.f;
+#pragma unroll
+    for (int j = 0; j < 2; ++j) {
+        const uint32_t kw[4] = {cur.k[j].x, cur.k[j].y, cur.k[j].z, cur.k[j].w};
+        uint32_t kh[8];  // 16 codes as eight fp16 pairs (1024 + code)
+#pragma unroll
+        for (int d = 0; d < 4; ++d) {
+            kh[2 * d] = __builtin_amdgcn_perm(0x64646464u, kw[d], 0x04010400u);
+            kh[2 * d + 1] = __builtin_amdgcn_perm(0x64646464u, kw[d], 0x04030402u);
+        }
+        const int cb = 4 * j + lane % 4;  // 16-byte chunk of codes = channels 16 cb .. 16 cb + 15
+#pragma unroll
+        for (int hh = 0; hh < N; ++hh) {
+            const uint4 qa = q_lds[hh * 16 + 2 * cb], qb = q_lds[hh * 16 + 2 * cb + 1];
+            const uint32_t qw[8] = {qa.x, qa.y, qa.z, qa.w, qb.x, qb.y, qb.z, qb.w};
+#pragma unroll
+            for (int u = 0; u < 8; ++u) s[hh] = Elem<F16>::dot2(qw[u], kh[u], s[hh]);
+        }
+    }
+    const bool dead = valid < 64 && tok0 + lane / 4 >= valid;
+    const half2_t ksz = __builtin_bit_cast(half2_t, cur.ksz), vsz = __builtin_bit_cast(half2_t, cur.vsz);
+    const float k_scale = (float)ksz[0], k_zero = (float)ksz[1];
+    const float v_scale = dead ? 0.f : (float)vsz[0], v_zero = dead ? 0.f : (float)vsz[1];  // slots past the end may hold anything
+    float wgt[N];
+#pragma unroll
+    for (int hh = 0; hh < N; ++hh) {
+        const float dot = token_sum<4>(s[hh]) - 1024.f * q_sum[hh];
+        const float x = (k_scale * dot + k_zero * q_sum[hh]) * scale_log2;
+        float pm = wave_max_of_quads(dead ? -INFINITY : x);
+        if (pm > st.m[hh]) {  // wave-uniform: rescale only when the running maximum moves
+            const float alpha = __builtin_amdgcn_exp2f(st.m[hh] - pm);
+            st.m[hh] = pm;
+            st.l[hh] *= alpha;
+            st.z[hh] *= alpha;
+#pragma unroll
+            for (int i = 0; i < 8; ++i) st.o[hh][i] *= alpha;
+        }
+        const float m_safe = st.m[hh] == -INFINITY ? 0.f : st.m[hh];
+        const float p = dead ? 0.f : __builtin_amdgcn_exp2f(x - m_safe);
+        st.l[hh] += p;  // counted once per lane of the token: divided by 4 at the end, and so is z
+        st.z[hh] += p * v_zero;
+        wgt[hh] = p * v_scale;
+    }
+    if (lane % 4 == 0) {
+        float* dst = p_lds + (lane / 4) * PR;
+#pragma unroll
+        for (int hh = 0; hh < N; ++hh) dst[hh] = wgt[hh];
+    }
+    __builtin_amdgcn_wave_barrier();
+#pragma unroll
+    for (int it = 0; it < 4; ++it) {
+        uint2 vv = cur.v[it];
+        if (valid < 64 && tok0 + 4 * it + r >= valid) vv = make_uint2(0, 0);
+        float pv[PR];
+#pragma unroll
+        for (int x4 = 0; x4 < PR / 4; ++x4) {
+            const float4 t4 = *reinterpret_cast<const float4*>(p_lds + (4 * it + r) * PR + 4 * x4);
+            pv[4 * x4] = t4.x;
+            pv[4 * x4 + 1] = t4.y;
+            pv[4 * x4 + 2] = t4.z;
+            pv[4 * x4 + 3] = t4.w;
+        }
+        const float code[8] = {(float)(vv.x & 0xffu), (float)((vv.x >> 8) & 0xffu), (float)((vv.x >> 16) & 0xffu),
+                               (float)(vv.x >> 24),   (float)(vv.y & 0xffu),        (float)((vv.y >> 8) & 0xffu),
+                               (float)((vv.y >> 16) & 0xffu), (float)(vv.y >> 24)};
+#pragma unroll
+        for (int hh = 0; hh < N; ++hh)
+#pragma unroll
+            for (int i = 0; i < 8; ++i) st.o[hh][i] = __builtin_fmaf(pv[hh], code[i], st.o[hh][i]);
+    }
+    __builtin_amdgcn_wave_barrier();
+}
+
 // Shared memory of a decode workgroup.
 template <int N, int NP> struct DecodeShared {
     float o[kDecodeWaves][N][kHeadDim];   // cross-wave merge
     float m[kDecodeWaves][N], l[kDecodeWaves][N];
     uint4 q[N * 16];                      // queries of the current group
+    float q_sum[kMaxGroup];               // quantised pages only: sum over the channels of each query
     float p[kDecodeWaves][(NP / 4) * p_row(N)];
 };
 
 // Loads the n queries of KV head hk into shared memory.  Called by the whole workgroup.
-template <int N, int NP>
+// For quantised pages the queries are converted to fp16 (exact for every bf16 value of magnitude between
+// 2^-14 and 65504; larger ones saturate) and their channel sums are taken, from the converted values.
+template <class T, int N, int NP, int BITS>
 __device__ __forceinline__ void stage_query(DecodeShared<N, NP>& sm, const uint4* q, int b, int H, int hk) {
     __syncthreads();  // earlier readers of sm.q are done
-    for (int i = threadIdx.x; i < N * 16; i += kDecodeThreads)
-        sm.q[i] = q[((size_t)b * H + hk * N) * (kHeadDim / 8) + i];
+    if (BITS == 16) {
+        for (int i = threadIdx.x; i < N * 16; i += kDecodeThreads)
+            sm.q[i] = q[((size_t)b * H + hk * N) * (kHeadDim / 8) + i];
+    } else {
+        static_assert(N * 16 <= kDecodeThreads, "one pass");
+        const int i = threadIdx.x;  // chunk i of the group: the 16 chunks of a query are the 16 lanes of a DPP row
+        float part = 0.f;
+        if (i < N * 16) {
+            const uint4 x = q[((size_t)b * H + hk * N) * (kHeadDim / 8) + i];
+            const uint32_t w[4] = {x.x, x.y, x.z, x.w};
+            uint32_t o[4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const float a = fminf(fmaxf(Elem<T>::lo(w[u]), -65504.f), 65504.f);
+                const float c = fminf(fmaxf(Elem<T>::hi(w[u]), -65504.f), 65504.f);
+                o[u] = Elem<F16>::pack(a, c);
+                part += Elem<F16>::lo(o[u]) + Elem<F16>::hi(o[u]);
+            }
+            sm.q[i] = make_uint4(o[0], o[1], o[2], o[3]);
+        }
+        part = row16_sum(part);
+        if (i < N * 16 && i % 16 == 0) sm.q_sum[i / 16] = part;
+    }
     __syncthreads();
 }
 
 // Folds the four token rows of every wave, then the four waves of the workgroup, and writes either
 // the final rows (out / lse) or a partial (part_o / part_ml).  Must be called by all 256 threads.
-template <class T, int N, int NP>
+template <class T, int N, int NP, int BITS>
 __device__ __forceinline__ void flush_block(WaveState<N>& st, DecodeShared<N, NP>& sm, bool final_result, int H,
                                             int b, int hk, uint16_t* out, float* lse_out, float* part_o,
                                             float* part_ml, size_t part_slot) {
@@ -262,8 +400,18 @@ __device__ __forceinline__ void flush_block(WaveState<N>& st, DecodeShared<N, NP
         lsum += dpp_f<kDppHalfMirror>(lsum);
         lsum += dpp_f<kDppMirror>(lsum);
         lsum = rows4_sum(lsum) * (1.0f / KeyMap<NP>::LPT);
+        // quantised values: the zero-point term, summed like the weights, belongs to every channel
+        float zsum = 0.f;
+        if (BITS != 16) {
+            zsum = st.z[hh];
+            zsum += dpp_f<kDppXor1>(zsum);
+            zsum += dpp_f<kDppXor2>(zsum);
+            zsum += dpp_f<kDppHalfMirror>(zsum);
+            zsum += dpp_f<kDppMirror>(zsum);
+            zsum = rows4_sum(zsum) * (1.0f / KeyMap<NP>::LPT);
+        }
 #pragma unroll
-        for (int i = 0; i < 8; ++i) st.o[hh][i] = rows4_sum(st.o[hh][i]);
+        for (int i = 0; i < 8; ++i) st.o[hh][i] = rows4_sum(st.o[hh][i]) + zsum;
         if (r == 0) {
 #pragma unroll
             for (int i = 0; i < 8; ++i) sm.o[wave][hh][8 * c + i] = st.o[hh][i];
@@ -382,16 +530,16 @@ __device__ __forceinline__ void fold_pieces(int list, int j0, int j1, int hh, in
 // directly, otherwise the piece goes to the workspace for decode_merge_kernel.  (Folding inside this
 // kernel with a device-scope fence and an arrival counter was measured at 3x the whole kernel time
 // on MI355X: the fence writes back and invalidates the XCD's L2.)  Called by all threads.
-template <class T, int N, int NP>
+template <class T, int N, int NP, int BITS>
 __device__ __forceinline__ void end_piece(WaveState<N>& st, DecodeShared<N, NP>& sm, const DecodePlan& plan, int blk,
                                           int lo, int hi, int list, int H, int Hkv, uint16_t* out, float* lse_out,
                                           float* part_o, float* part_ml) {
     const int b = list / Hkv, hk = list % Hkv;
     const int n0 = b * plan.per_seq + plan.first[hk], n1 = b * plan.per_seq + plan.first[hk + 1];
-    flush_block<T, N, NP>(st, sm, n0 >= lo && n1 <= hi, H, b, hk, out, lse_out, part_o, part_ml, (size_t)blk + list);
+    flush_block<T, N, NP, BITS>(st, sm, n0 >= lo && n1 <= hi, H, b, hk, out, lse_out, part_o, part_ml, (size_t)blk + list);
 }
 
-template <class T, int N, int NP>
+template <class T, int N, int NP, int BITS>
 __global__ __launch_bounds__(kDecodeThreads) void sparse_decode_kernel(
     LayerParams lp, PagedParams kv, DecodePlan plan, const uint4* __restrict__ q, const int* __restrict__ sel_pages,
     const int* __restrict__ sel_count, const int* __restrict__ sel_seq_len, int sel_stride,
@@ -405,7 +553,7 @@ __global__ __launch_bounds__(kDecodeThreads) void sparse_decode_kernel(
     const int lane = threadIdx.x % kWave, wave = threadIdx.x / kWave;
     const int r = lane / 16, c = lane % 16;
     const int tok0 = wave * (NP / 4);
-    const size_t slab = (size_t)NP * (kHeadDim / 8);  // uint4 per (page, head)
+    const size_t slab = slab_chunks(NP, BITS);  // uint4 per (page, head)
     const uint4* kpool = reinterpret_cast<const uint4*>(kv.k_pool);
     const uint4* vpool = reinterpret_cast<const uint4*>(kv.v_pool);
     const uint4* kstream = reinterpret_cast<const uint4*>(kv.k_stream);
@@ -468,13 +616,13 @@ __global__ __launch_bounds__(kDecodeThreads) void sparse_decode_kernel(
         }
         unsigned long long todo = __ballot(my_valid);
         if (todo == 0) continue;
-        Slabs<NP> cur, nxt;
+        Slabs<NP, BITS> cur, nxt;
         {
             const int idx0 = __builtin_ctzll(todo);
             const uint4 *k0, *v0;
             slab_of(__builtin_amdgcn_readlane(my_phys, idx0), __builtin_amdgcn_readlane(my_list, idx0) % lp.Hkv, k0, v0);
-            load_k<NP>(cur, k0, tok0, lane);
-            load_v<NP>(cur, v0, tok0, r, c);
+            load_k(cur, k0, tok0, lane);
+            load_v(cur, v0, tok0, r, c, lane);
         }
         while (todo) {
             const int idx = __builtin_ctzll(todo);
@@ -483,22 +631,22 @@ __global__ __launch_bounds__(kDecodeThreads) void sparse_decode_kernel(
                 const int idx1 = __builtin_ctzll(todo);
                 const uint4 *k1, *v1;
                 slab_of(__builtin_amdgcn_readlane(my_phys, idx1), __builtin_amdgcn_readlane(my_list, idx1) % lp.Hkv, k1, v1);
-                load_k<NP>(nxt, k1, tok0, lane);
-                load_v<NP>(nxt, v1, tok0, r, c);
+                load_k(nxt, k1, tok0, lane);
+                load_v(nxt, v1, tok0, r, c, lane);
             }
             const int list = __builtin_amdgcn_readlane(my_list, idx);
             if (list != cur_list) {  // uniform: the range crossed into the next list
                 if (cur_list >= 0)
-                    end_piece<T, N, NP>(st, sm, plan, blk, lo, hi, cur_list, lp.H, lp.Hkv, out, lse_out, part_o, part_ml);
+                    end_piece<T, N, NP, BITS>(st, sm, plan, blk, lo, hi, cur_list, lp.H, lp.Hkv, out, lse_out, part_o, part_ml);
                 cur_list = list;
                 cur_b = list / lp.Hkv;
                 cur_hk = list % lp.Hkv;
-                stage_query<N, NP>(sm, q, cur_b, lp.H, cur_hk);
+                stage_query<T, N, NP, BITS>(sm, q, cur_b, lp.H, cur_hk);
                 st.reset();
             }
             const int L = __builtin_amdgcn_readlane(my_L, idx);
             const int pos = __builtin_amdgcn_readlane(my_pos, idx);
-            process_quarter_page<T, N, NP>(st, sm.q, sm.p[wave], cur, L - pos * NP, tok0, lane, lp.sm_scale_log2);
+            process_quarter_page<T, N>(st, sm.q, sm.q_sum, sm.p[wave], cur, L - pos * NP, tok0, lane, lp.sm_scale_log2);
             const int extra = __builtin_amdgcn_readlane(my_extra, idx);
             if (extra > 0) {  // real entries beyond the nominal length: rare, not prefetched
                 const int nominal = plan.first[cur_hk + 1] - plan.first[cur_hk];
@@ -508,16 +656,16 @@ __global__ __launch_bounds__(kDecodeThreads) void sparse_decode_kernel(
                     const int ephys = kv.page_table[(size_t)cur_b * kv.max_pages + epos];
                     const uint4 *ke, *ve;  // only dense heads outgrow their nominal list: always the main pool
                     slab_of(ephys, cur_hk, ke, ve);
-                    load_k<NP>(cur, ke, tok0, lane);
-                    load_v<NP>(cur, ve, tok0, r, c);
-                    process_quarter_page<T, N, NP>(st, sm.q, sm.p[wave], cur, L - epos * NP, tok0, lane, lp.sm_scale_log2);
+                    load_k(cur, ke, tok0, lane);
+                    load_v(cur, ve, tok0, r, c, lane);
+                    process_quarter_page<T, N>(st, sm.q, sm.q_sum, sm.p[wave], cur, L - epos * NP, tok0, lane, lp.sm_scale_log2);
                 }
             }
             cur = nxt;
         }
     }
     if (cur_list < 0) return;  // no real entry in this range
-    end_piece<T, N, NP>(st, sm, plan, blk, lo, hi, cur_list, lp.H, lp.Hkv, out, lse_out, part_o, part_ml);
+    end_piece<T, N, NP, BITS>(st, sm, plan, blk, lo, hi, cur_list, lp.H, lp.Hkv, out, lse_out, part_o, part_ml);
 }
 
 // Combines the pieces of every list that was cut by a range boundary, in slot order.
@@ -566,7 +714,7 @@ size_t partial_slots(const LayerParams& lp, int batch) {
     return (size_t)num_compute_units() * kMaxBlocksPerCU + (size_t)batch * lp.Hkv;
 }
 
-template <class T, int N, int NP>
+template <class T, int N, int NP, int BITS>
 hipError_t launch_decode_kernels(const LayerParams& lp, const PagedParams& kv, const void* q, const int* sel_pages,
                                  const int* sel_count, const int* sel_seq_len, int sel_stride, void* out,
                                  float* lse_out, float* part_o, float* part_ml, hipStream_t stream) {
@@ -575,7 +723,7 @@ hipError_t launch_decode_kernels(const LayerParams& lp, const PagedParams& kv, c
     static int per_cu = 0;  // resident workgroups per compute unit of this instantiation
     if (per_cu == 0) {
         int nb = 0;
-        hipError_t e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&nb, sparse_decode_kernel<T, N, NP>, kDecodeThreads, 0);
+        hipError_t e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&nb, sparse_decode_kernel<T, N, NP, BITS>, kDecodeThreads, 0);
         if (e != hipSuccess) return e;
         per_cu = nb < 1 ? 1 : (nb > kBlocksPerCU ? kBlocksPerCU : nb);
         if (const char* e = getenv("LSERVE_DECODE_BLOCKS_PER_CU")) {  // tuning override
@@ -585,7 +733,7 @@ hipError_t launch_decode_kernels(const LayerParams& lp, const PagedParams& kv, c
     }
     const int G = num_compute_units() * per_cu;
     const DecodePlan plan = make_plan(lp, kv.batch, sel_stride, G);
-    hipLaunchKernelGGL((sparse_decode_kernel<T, N, NP>), dim3(G), dim3(kDecodeThreads), 0, stream, lp, kv, plan, q4,
+    hipLaunchKernelGGL((sparse_decode_kernel<T, N, NP, BITS>), dim3(G), dim3(kDecodeThreads), 0, stream, lp, kv, plan, q4,
                        sel_pages, sel_count, sel_seq_len, sel_stride, o16, lse_out, part_o, part_ml);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
@@ -600,8 +748,11 @@ hipError_t launch_decode_np(const LayerParams& lp, const PagedParams& kv, const 
                             float* part_o, float* part_ml, hipStream_t stream) {
 #define LSERVE_DECODE_NP(NPV)                                                                                       \
     case NPV:                                                                                                       \
-        return launch_decode_kernels<T, N, NPV>(lp, kv, q, sel_pages, sel_count, sel_seq_len, sel_stride, out,       \
-                                                lse_out, part_o, part_ml, stream);
+        return launch_decode_kernels<T, N, NPV, 16>(lp, kv, q, sel_pages, sel_count, sel_seq_len, sel_stride, out,   \
+                                                    lse_out, part_o, part_ml, stream);
+    if (kv.kv_bits == 8)  // quantised pages are always 64 tokens (checked by the caller)
+        return launch_decode_kernels<T, N, 64, 8>(lp, kv, q, sel_pages, sel_count, sel_seq_len, sel_stride, out, lse_out,
+                                                  part_o, part_ml, stream);
     switch (lp.NP) {
         LSERVE_DECODE_NP(16)
         LSERVE_DECODE_NP(32)

@@ -21,23 +21,34 @@ class DecodeSession:
                  budget_tokens: int, logical_page_size: int = 16, reuse_interval: int = 4,
                  sm_scale: float = 0.0, want_scores: bool = False, want_lse: bool = False,
                  fused_stats: bool = True, k_pool_stream: Optional[torch.Tensor] = None,
-                 v_pool_stream: Optional[torch.Tensor] = None, ring_table: Optional[torch.Tensor] = None):
+                 v_pool_stream: Optional[torch.Tensor] = None, ring_table: Optional[torch.Tensor] = None,
+                 kv_bits: int = 16, dtype: Optional[torch.dtype] = None):
         """k_pool / v_pool hold every KV head, or only the non-streaming ones when the streaming heads live in
-        the bounded pool k_pool_stream / v_pool_stream behind ring_table (two-way cache)."""
+        the bounded pool k_pool_stream / v_pool_stream behind ring_table (two-way cache).  kv_bits = 8: the pools
+        are uint8 [pages, heads, 64 * 128 + 256] (quantised pages, written by `append`), `dtype` names the 16-bit
+        type of queries, outputs and statistics, and the statistics are kept current by `append` alone."""
         dev = k_pool.device
-        num_pages, pool_heads, page_size, head_dim = k_pool.shape
+        if kv_bits == 8:
+            num_pages, pool_heads, _ = k_pool.shape
+            page_size, head_dim = 64, 128
+            if dtype is None:
+                raise ValueError("a session over quantised pages needs the 16-bit dtype of the layer")
+        else:
+            num_pages, pool_heads, page_size, head_dim = k_pool.shape
+            dtype = k_pool.dtype
+        self.kv_bits = kv_bits
         hkv = len(streaming_flags)
         batch, max_pages = page_table.shape
         self.desc = B.AttnDesc(num_q_heads=num_q_heads, num_kv_heads=hkv, streaming_flags=streaming_flags,
                                head_dim=head_dim, page_size=page_size, logical_page_size=logical_page_size,
-                               dtype=k_pool.dtype, sink_tokens=sink_tokens, local_tokens=local_tokens,
+                               dtype=dtype, sink_tokens=sink_tokens, local_tokens=local_tokens,
                                sm_scale=sm_scale)
         g = page_size // logical_page_size
-        self.stats = torch.zeros((num_pages, pool_heads, g, 2, head_dim), dtype=k_pool.dtype, device=dev)
+        self.stats = torch.zeros((num_pages, pool_heads, g, 2, head_dim), dtype=dtype, device=dev)
         self.seq_lens = torch.zeros((batch,), dtype=torch.int32, device=dev)
         self.kv = B.PagedKV(k_pool, v_pool, self.stats, page_table, self.seq_lens,
                             pool_heads=0 if pool_heads == hkv else pool_heads, k_pool_stream=k_pool_stream,
-                            v_pool_stream=v_pool_stream, ring_table=ring_table)
+                            v_pool_stream=v_pool_stream, ring_table=ring_table, kv_bits=kv_bits)
         self.budget_tokens = budget_tokens
         self.reuse_interval = max(1, reuse_interval)
         K = budget_tokens // page_size
@@ -51,7 +62,7 @@ class DecodeSession:
         ws_dec = B.lserve_workspace_bytes(B.LSERVE_CALL_SPARSE_DECODE, self.desc, batch, max_pages, K, 0)
         self.ws_select = torch.empty((max(ws_sel, 16),), dtype=torch.uint8, device=dev)
         self.ws_decode = torch.empty((max(ws_dec, 16),), dtype=torch.uint8, device=dev)
-        self.out = torch.empty((batch, num_q_heads, head_dim), dtype=k_pool.dtype, device=dev)
+        self.out = torch.empty((batch, num_q_heads, head_dim), dtype=dtype, device=dev)
         self.lse = torch.empty((batch, num_q_heads), dtype=torch.float32, device=dev) if want_lse else None
         self.steps_since_selection: Optional[int] = None
         # True: the selector rebuilds the stale logical pages itself; False: a separate statistics launch
@@ -65,6 +76,12 @@ class DecodeSession:
         """Point the session at the caller's current lengths (device int32 [batch], not copied)."""
         self.seq_lens = seq_lens
         self.kv.seq_lens = seq_lens
+
+    def append(self, k_new: torch.Tensor, v_new: torch.Tensor, cu_new: torch.Tensor, start_pos: torch.Tensor,
+               max_new_per_seq: int) -> None:
+        """Write new tokens' K/V into the pages (quantising them for 8-bit pools) and fold the keys into the
+        statistics in the same pass."""
+        B.lserve_append_kv(self.desc, self.kv, k_new, v_new, cu_new, start_pos, max_new_per_seq)
 
     def build_stats_full(self) -> None:
         """Statistics of every logical page below the current lengths (after prefill)."""
@@ -101,7 +118,9 @@ class DecodeSession:
             self._stats_from = prev_seq_lens
         self._stats_tokens += 1
         if self.steps_since_selection is None or self.steps_since_selection >= self.reuse_interval:
-            if self.fused_stats:
+            if self.kv_bits != 16:
+                self.select(q)  # quantised pages: `append` has kept the statistics current
+            elif self.fused_stats:
                 self.select(q, stats_valid_len=self._stats_from)
             else:
                 self.update_stats_tail(self._stats_from, self._stats_tokens)

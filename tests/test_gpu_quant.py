@@ -1,0 +1,171 @@
+"""Quantised KV pages (Sec. 3.2, Sec. 3.5): the write-back's bytes against the oracle's quantiser, bit for
+bit, and decode over those pages against the oracle's decode over the values the bytes stand for."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from workloads import make_decode_inputs
+
+from helpers import small_decode_workload
+from parity import assert_attention_close, assert_lse_close, compare_selection
+
+pytestmark = pytest.mark.gpu
+
+SLAB = 64 * 128 + 256  # bytes of one (page, head): codes, then 64 (scale, zero) pairs of fp16
+
+
+def _lib():
+    import paper_2502_14866_amd as L
+
+    L.load_library()
+    return L
+
+
+def _write_rows(pool_q: torch.Tensor, phys, hk, slot, x_rows: torch.Tensor):
+    """Oracle-quantised rows x_rows [n, 128] into slots (phys[i], hk, slot[i]) of a CPU byte pool."""
+    codes, scale, zero = oracle.quantize_q8(x_rows)
+    sz = np.stack([scale, zero], axis=-1).view(np.uint8).reshape(-1, 4)
+    for i in range(x_rows.shape[0]):
+        slab = pool_q[int(phys[i]), hk]
+        slab[int(slot[i]) * 128:(int(slot[i]) + 1) * 128] = torch.from_numpy(codes[i])
+        slab[8192 + 4 * int(slot[i]):8192 + 4 * int(slot[i]) + 4] = torch.from_numpy(sz[i])
+
+
+def _values(pool_q: torch.Tensor) -> np.ndarray:
+    """[pages, heads, 64, 128] float64 values a CPU byte pool stands for (unwritten slots: whatever they hold)."""
+    raw = pool_q.numpy()
+    codes = raw[..., :8192].reshape(raw.shape[0], raw.shape[1], 64, 128)
+    sz = np.ascontiguousarray(raw[..., 8192:]).view(np.float16).reshape(raw.shape[0], raw.shape[1], 64, 2)
+    with np.errstate(invalid="ignore", over="ignore"):
+        return oracle.dequantize_q8(codes, sz[..., 0], sz[..., 1])
+
+
+@pytest.mark.parametrize("dtype", ["fp16", "bf16"])
+def test_quantising_append_writes_the_oracles_bytes_and_nothing_else(dtype):
+    L = _lib()
+    dev = torch.device("cuda:0")
+    w = small_decode_workload(batch=3, lengths=(1, 1, 1), dtype=dtype)
+    dt = torch.float16 if dtype == "fp16" else torch.bfloat16
+    max_pages, num_pages = 8, 24
+    g = torch.Generator().manual_seed(5)
+    page_table = torch.randperm(num_pages, generator=g).to(torch.int32).reshape(3, max_pages)
+    k_ref = torch.randint(0, 256, (num_pages, w.num_kv_heads, SLAB), generator=g, dtype=torch.uint8)  # a reused pool
+    v_ref = torch.randint(0, 256, (num_pages, w.num_kv_heads, SLAB), generator=g, dtype=torch.uint8)
+    k16 = torch.zeros((num_pages, w.num_kv_heads, 64, 128), dtype=dt)  # the keys themselves, for the statistics
+    k_dev, v_dev = k_ref.to(dev), v_ref.to(dev)
+    stats = torch.full((num_pages, w.num_kv_heads, 4, 2, 128), float("nan"), dtype=dt, device=dev)
+    desc = L.AttnDesc(num_q_heads=w.num_q_heads, num_kv_heads=w.num_kv_heads, streaming_flags=w.streaming_flags(),
+                      dtype=dt, sink_tokens=w.sink_tokens, local_tokens=w.local_tokens)
+    pt_dev = page_table.to(dev)
+    rounds = [(3 * 64 + 5, 63, 1), (1, 1, 1), (1, 1, 0), (128, 7, 3), (0, 1, 65), (1, 0, 0)]
+    start = [0, 0, 0]
+    heads = [h for h in range(w.num_kv_heads) if h not in w.streaming_kv_heads]
+    for it, n_new in enumerate(rounds):
+        gg = torch.Generator().manual_seed(100 + it)
+        total = sum(n_new)
+        # rows of different spread and offset, one constant row and one with a single outlier
+        k_new = (torch.randn((total, w.num_kv_heads, 128), generator=gg) * (4 * torch.rand((total, w.num_kv_heads, 1), generator=gg))
+                 + torch.randn((total, w.num_kv_heads, 1), generator=gg)).to(dt)
+        v_new = torch.randn((total, w.num_kv_heads, 128), generator=gg).to(dt)
+        k_new[0, 0] = 0.375
+        v_new[0, 1, 5] = 300.0
+        cu = np.concatenate([[0], np.cumsum(n_new)]).astype(np.int32)
+        seq = torch.tensor([s + n for s, n in zip(start, n_new)], dtype=torch.int32, device=dev)
+        kv = L.PagedKV(k_dev, v_dev, stats, pt_dev, seq, kv_bits=8)
+        pad = torch.zeros((1, w.num_kv_heads, 128), dtype=dt)
+        L.lserve_append_kv(desc, kv, torch.cat([k_new, pad]).to(dev), torch.cat([v_new, pad]).to(dev),
+                           torch.from_numpy(cu).to(dev), torch.tensor(start, dtype=torch.int32, device=dev),
+                           max(max(n_new), 1))
+        torch.cuda.synchronize()
+        for b in range(3):
+            pos = np.arange(start[b], start[b] + n_new[b])
+            phys = page_table[b].numpy()[pos // 64]
+            for hk in range(w.num_kv_heads):
+                _write_rows(k_ref, phys, hk, pos % 64, k_new[cu[b]:cu[b + 1], hk])
+                _write_rows(v_ref, phys, hk, pos % 64, v_new[cu[b]:cu[b + 1], hk])
+                k16[torch.from_numpy(phys).long(), hk, torch.from_numpy(pos % 64).long()] = k_new[cu[b]:cu[b + 1], hk]
+        start = [s + n for s, n in zip(start, n_new)]
+        assert torch.equal(k_dev.cpu(), k_ref), (dtype, it)
+        assert torch.equal(v_dev.cpu(), v_ref), (dtype, it)
+        seq_np = np.asarray(start, np.int32)
+        live = [b for b in range(3) if seq_np[b] > 0]
+        ref = oracle.page_stats(k16, page_table[live], seq_np[live], w.logical_page_size)
+        got = stats.cpu()
+        for b in live:
+            for lpage in range(-(-int(seq_np[b]) // w.logical_page_size)):
+                t0 = lpage * w.logical_page_size
+                phys, j = int(page_table[b, t0 // 64]), (t0 % 64) // w.logical_page_size
+                for hk in heads:
+                    assert torch.equal(got[phys, hk, j].float(), ref[phys, hk, j].float()), (dtype, it, b, lpage, hk)
+
+
+QUANT_WORKLOADS = {
+    "tiny_gqa": dict(),
+    "ragged_tail": dict(lengths=(1, 63), decode_steps=3),
+    "mha": dict(num_q_heads=4, num_kv_heads=4, streaming_kv_heads=(1, 3), lengths=(900, 130, 2049), batch=3),
+    "gqa8_bf16": dict(num_q_heads=16, num_kv_heads=2, dtype="bf16", streaming_kv_heads=(1,), lengths=(4100, 700),
+                      budget_tokens=1024),
+    "group3_all_dense": dict(num_q_heads=6, num_kv_heads=2, streaming_kv_heads=(), lengths=(1500, 2600), budget_tokens=512),
+    "group5_bf16": dict(num_q_heads=10, num_kv_heads=2, dtype="bf16", lengths=(333, 1000)),
+}
+
+
+@pytest.mark.parametrize("name", list(QUANT_WORKLOADS))
+def test_decode_loop_over_quantised_pages_matches_the_oracle(name):
+    """Pages are filled through the quantising write-back (the prompt in one call, then a token per step) into
+    pools that start as 0xff bytes (NaN scales in every unused slot); statistics, selection and the decode
+    output are compared at every step, the output against the oracle's decode over code * scale + zero."""
+    from paper_2502_14866_amd.session import DecodeSession
+
+    L = _lib()
+    dev = torch.device("cuda:0")
+    w = small_decode_workload(**dict(dict(decode_steps=4, reuse_interval=2), **QUANT_WORKLOADS[name]))
+    inp = make_decode_inputs(w)
+    dt = inp.k_pool.dtype
+    num_pages = inp.k_pool.shape[0]
+    k_q = torch.full((num_pages, w.num_kv_heads, SLAB), 0xff, dtype=torch.uint8)
+    v_q = k_q.clone()
+    sess = DecodeSession(k_q.to(dev), v_q.to(dev), inp.page_table.to(dev), w.num_q_heads, w.streaming_flags(),
+                         w.sink_tokens, w.local_tokens, w.budget_tokens, logical_page_size=w.logical_page_size,
+                         reuse_interval=w.reuse_interval, want_scores=True, want_lse=True, kv_bits=8, dtype=dt)
+    sess.stats.fill_(float("nan"))
+    flags = w.streaming_flags()
+    have = [0] * w.batch
+    near_ties = 0
+    for step in range(w.decode_steps):
+        seq_cpu = inp.seq_lens_at(step)
+        want = [int(x) for x in seq_cpu]
+        ks, vs = [], []
+        for b in range(w.batch):
+            pos = torch.arange(have[b], want[b])
+            phys = inp.page_table[b].long()[pos // 64]
+            kb, vb = inp.k_pool[phys, :, pos % 64], inp.v_pool[phys, :, pos % 64]  # [n, Hkv, 128]
+            ks.append(kb)
+            vs.append(vb)
+            for hk in range(w.num_kv_heads):
+                _write_rows(k_q, phys, hk, pos % 64, kb[:, hk])
+                _write_rows(v_q, phys, hk, pos % 64, vb[:, hk])
+        n_new = [a - h for a, h in zip(want, have)]
+        cu = np.concatenate([[0], np.cumsum(n_new)]).astype(np.int32)
+        sess.append(torch.cat(ks).contiguous().to(dev), torch.cat(vs).contiguous().to(dev), torch.from_numpy(cu).to(dev),
+                    torch.tensor(have, dtype=torch.int32, device=dev), max(n_new))
+        have = want
+        assert torch.equal(sess.kv.k_pool.cpu(), k_q), (name, step)
+        assert torch.equal(sess.kv.v_pool.cpu(), v_q), (name, step)
+        sess.set_seq_lens(seq_cpu.to(dev))
+        q = inp.q[step].to(dev)
+        stats_ref = oracle.page_stats(inp.k_pool, inp.page_table, seq_cpu, w.logical_page_size)
+        if step % w.reuse_interval == 0:
+            sess.select(q)
+            scores_ref, _ = oracle.page_scores(inp.q[step], stats_ref, inp.page_table, seq_cpu, w.page_size)
+            sel_ref, cnt_ref, ssl_ref = oracle.select_pages(scores_ref, seq_cpu, w.page_size, w.budget_tokens)
+            near_ties += compare_selection(sess.sel_pages.cpu().numpy(), sess.sel_count.cpu().numpy(), sel_ref, cnt_ref,
+                                           scores_ref, flags)
+        out = sess.decode(q)
+        ref, lse_ref = oracle.sparse_decode_values(inp.q[step], _values(k_q), _values(v_q), inp.page_table, seq_cpu,
+                                                   sess.sel_pages.cpu().numpy(), sess.sel_count.cpu().numpy(),
+                                                   sess.sel_seq_len.cpu().numpy(), flags, w.sink_tokens, w.local_tokens)
+        assert_attention_close(out, ref, f"{name} step {step}")
+        assert_lse_close(sess.lse, lse_ref, f"{name} step {step}")
+    assert near_ties <= 1
