@@ -51,6 +51,7 @@ def parse_args():
     ap.add_argument("--no-prefill", action="store_true")
     ap.add_argument("--prefill-tokens", type=int, default=65536)
     ap.add_argument("--no-append", action="store_true", help="skip the KV write-back timing")
+    ap.add_argument("--no-kv8", action="store_true", help="skip the decode timing over quantised (8-bit) pages")
     ap.add_argument("--profile-only", default="", choices=["", "decode", "select", "prefill", "stats"],
                     help="run only a short loop of one entry point (for rocprofv3)")
     return ap.parse_args()
@@ -289,6 +290,11 @@ def main():
             result["append"] = bench_append(torch, L, dev, args.prefill_tokens, w)
         except Exception as e:
             result["append"] = {"error": repr(e)}
+    if not args.no_kv8 and w.page_size == 64:
+        try:
+            result["kv8"] = bench_quantised(torch, L, dev, w, inp, sess, len_table)
+        except Exception as e:
+            result["kv8"] = {"error": repr(e)}
     print(json.dumps(result))
 
 
@@ -468,6 +474,78 @@ def bench_append(torch, L, dev, n_tokens, w_dec):
         "decode_append_us_per_call": us,
         "prefill_over_the_written_pages_ms": paged_ms,
         "note": "not part of `value`: the decode benchmark reads a pre-written cache",
+    }
+
+
+def bench_quantised(torch, L, dev, w, inp, sess, len_table):
+    """Sparse decode over 8-bit pages next to the 16-bit call, same cache contents and same selection: the
+    prompt is written into fresh quantised pools by the write-back entry point, then one decode launch of
+    each kind is timed on the selection the 16-bit session last made."""
+    B, Hkv, D, NP = w.batch, w.num_kv_heads, w.head_dim, w.page_size
+    slab = NP * D + NP * 4
+    num_pages = inp.k_pool.shape[0]
+    k_q = torch.zeros((num_pages, Hkv, slab), dtype=torch.uint8, device=dev)
+    v_q = torch.zeros_like(k_q)
+    stats = torch.zeros_like(sess.stats)
+    lens = inp.prompt_lens.to(dev).to(torch.int32)
+    pad = (B + 4) // 4 * 4
+    cu = torch.zeros((pad,), dtype=torch.int32, device=dev)
+    cu[1:B + 1] = torch.cumsum(lens, 0)
+    seq = torch.zeros((pad,), dtype=torch.int32, device=dev)
+    seq[:B] = lens
+    ks, vs = [], []
+    for b in range(B):
+        pos = torch.arange(int(inp.prompt_lens[b]), device=dev)
+        phys = inp.page_table[b].long()[pos // NP]
+        ks.append(inp.k_pool[phys, :, pos % NP])
+        vs.append(inp.v_pool[phys, :, pos % NP])
+    k_new, v_new = torch.cat(ks).contiguous(), torch.cat(vs).contiguous()
+    del ks, vs
+    kv_q = L.PagedKV(k_q, v_q, stats, inp.page_table, seq[:B], kv_bits=8)
+    zero = torch.zeros((pad,), dtype=torch.int32, device=dev)
+    max_new = int(inp.prompt_lens.max())
+
+    def timed(call, reps):
+        call()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(reps):
+            call()
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / reps
+
+    wb_ms = timed(lambda: L.lserve_append_kv(sess.desc, kv_q, k_new, v_new, cu, zero, max_new), 3)
+    n_tok = int(inp.prompt_lens.sum())
+    wb_bytes = 2 * n_tok * Hkv * (D * 2 + D + 4)  # 16-bit rows read, codes and (scale, zero) written, K and V
+    del k_new, v_new
+    # decode at the prompt lengths with the selection of a selector run at those lengths
+    sess.restart()
+    sess.step(inp.q[0], len_table[1, :B], len_table[0, :B])
+    kv16 = L.PagedKV(inp.k_pool, inp.v_pool, sess.stats, inp.page_table, seq[:B])
+    out = torch.empty_like(sess.out)
+    q = inp.q[0]
+    ms8 = timed(lambda: L.lserve_sparse_decode(sess.desc, kv_q, q, sess.sel_pages, sess.sel_count, sess.sel_seq_len, out,
+                                               None, sess.ws_decode), 200)
+    out8 = out.clone()
+    ms16 = timed(lambda: L.lserve_sparse_decode(sess.desc, kv16, q, sess.sel_pages, sess.sel_count, sess.sel_seq_len, out,
+                                                None, sess.ws_decode), 200)
+    _, pages = decode_bytes_per_launch(w, seq[:B].cpu(), sess.sel_count.cpu(), sess.sel_seq_len.cpu())
+    nbytes = pages * 2 * slab + 2 * B * w.num_q_heads * D * 2 + pages * 8
+    return {
+        "workload": f"{w.name}: the same cache quantised to 8-bit codes with per-token fp16 scale and zero point, "
+                    "eager launches on one selection",
+        "decode_launch_ms": ms8,
+        "decode_launch_ms_16bit_same_selection": ms16,
+        "speedup_over_16bit": ms16 / ms8,
+        "algorithmic_bytes_per_launch": nbytes,
+        "achieved_GBs": nbytes / (ms8 * 1e-3) / 1e9,
+        "frac_of_hbm_peak": nbytes / (ms8 * 1e-3) / 1e9 / HBM_PEAK_GBS,
+        "max_abs_difference_to_16bit_output": float((out8.float() - out.float()).abs().max()),
+        "quantising_write_back": {"tokens": n_tok, "ms": wb_ms, "algorithmic_bytes": wb_bytes,
+                                  "achieved_GBs": wb_bytes / (wb_ms * 1e-3) / 1e9},
+        "note": "not part of `value`",
     }
 
 

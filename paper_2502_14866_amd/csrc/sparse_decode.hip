@@ -539,6 +539,43 @@ __device__ __forceinline__ void end_piece(WaveState<N>& st, DecodeShared<N, NP>&
     flush_block<T, N, NP, BITS>(st, sm, n0 >= lo && n1 <= hi, H, b, hk, out, lse_out, part_o, part_ml, (size_t)blk + list);
 }
 
+// Visits entry IDX of the current batch, whose slabs are in CUR: when the (wave-uniform) list changes the
+// piece of the previous list is ended and the new list's queries are staged; then the quarter page is
+// folded in; real entries beyond the nominal length of a list (rare) are fetched and folded in on the spot,
+// without prefetch (only dense heads outgrow their nominal list, so they are always in the main pool).
+// A macro, not a lambda: with the state captured by reference the compiler keeps 70 more registers live in
+// the 16-bit kernel.
+#define LSERVE_DECODE_VISIT(IDX, CUR)                                                                                \
+    {                                                                                                                \
+        const int list = __builtin_amdgcn_readlane(my_list, (IDX));                                                  \
+        if (list != cur_list) {                                                                                      \
+            if (cur_list >= 0)                                                                                       \
+                end_piece<T, N, NP, BITS>(st, sm, plan, blk, lo, hi, cur_list, lp.H, lp.Hkv, out, lse_out, part_o, part_ml);\
+            cur_list = list;                                                                                         \
+            cur_b = list / lp.Hkv;                                                                                   \
+            cur_hk = list % lp.Hkv;                                                                                  \
+            stage_query<T, N, NP, BITS>(sm, q, cur_b, lp.H, cur_hk);                                                 \
+            st.reset();                                                                                              \
+        }                                                                                                            \
+        const int L = __builtin_amdgcn_readlane(my_L, (IDX));                                                        \
+        const int pos = __builtin_amdgcn_readlane(my_pos, (IDX));                                                    \
+        process_quarter_page<T, N>(st, sm.q, sm.q_sum, sm.p[wave], CUR, L - pos * NP, tok0, lane, lp.sm_scale_log2); \
+        const int extra = __builtin_amdgcn_readlane(my_extra, (IDX));                                                \
+        if (extra > 0) {                                                                                             \
+            const int nominal = plan.first[cur_hk + 1] - plan.first[cur_hk];                                         \
+            const int tail = __builtin_amdgcn_readlane(my_tail, (IDX));                                              \
+            for (int e = 0; e < extra; ++e) {                                                                        \
+                const int epos = tail + nominal + e;                                                                 \
+                const int ephys = kv.page_table[(size_t)cur_b * kv.max_pages + epos];                                \
+                const uint4 *ke, *ve;                                                                                \
+                slab_of(ephys, cur_hk, ke, ve);                                                                      \
+                load_k(CUR, ke, tok0, lane);                                                                         \
+                load_v(CUR, ve, tok0, r, c, lane);                                                                   \
+                process_quarter_page<T, N>(st, sm.q, sm.q_sum, sm.p[wave], CUR, L - epos * NP, tok0, lane, lp.sm_scale_log2);\
+            }                                                                                                        \
+        }                                                                                                            \
+    }
+
 template <class T, int N, int NP, int BITS>
 __global__ __launch_bounds__(kDecodeThreads) void sparse_decode_kernel(
     LayerParams lp, PagedParams kv, DecodePlan plan, const uint4* __restrict__ q, const int* __restrict__ sel_pages,
@@ -616,57 +653,67 @@ __global__ __launch_bounds__(kDecodeThreads) void sparse_decode_kernel(
         }
         unsigned long long todo = __ballot(my_valid);
         if (todo == 0) continue;
-        Slabs<NP, BITS> cur, nxt;
-        {
-            const int idx0 = __builtin_ctzll(todo);
-            const uint4 *k0, *v0;
-            slab_of(__builtin_amdgcn_readlane(my_phys, idx0), __builtin_amdgcn_readlane(my_list, idx0) % lp.Hkv, k0, v0);
-            load_k(cur, k0, tok0, lane);
-            load_v(cur, v0, tok0, r, c, lane);
-        }
-        while (todo) {
-            const int idx = __builtin_ctzll(todo);
-            todo &= todo - 1;
-            if (todo) {
-                const int idx1 = __builtin_ctzll(todo);
-                const uint4 *k1, *v1;
-                slab_of(__builtin_amdgcn_readlane(my_phys, idx1), __builtin_amdgcn_readlane(my_list, idx1) % lp.Hkv, k1, v1);
-                load_k(nxt, k1, tok0, lane);
-                load_v(nxt, v1, tok0, r, c, lane);
+        if constexpr (BITS == 16) {
+            // one page in flight behind the one being worked on
+            Slabs<NP, BITS> cur, nxt;
+            {
+                const int idx0 = __builtin_ctzll(todo);
+                const uint4 *k0, *v0;
+                slab_of(__builtin_amdgcn_readlane(my_phys, idx0), __builtin_amdgcn_readlane(my_list, idx0) % lp.Hkv, k0, v0);
+                load_k(cur, k0, tok0, lane);
+                load_v(cur, v0, tok0, r, c, lane);
             }
-            const int list = __builtin_amdgcn_readlane(my_list, idx);
-            if (list != cur_list) {  // uniform: the range crossed into the next list
-                if (cur_list >= 0)
-                    end_piece<T, N, NP, BITS>(st, sm, plan, blk, lo, hi, cur_list, lp.H, lp.Hkv, out, lse_out, part_o, part_ml);
-                cur_list = list;
-                cur_b = list / lp.Hkv;
-                cur_hk = list % lp.Hkv;
-                stage_query<T, N, NP, BITS>(sm, q, cur_b, lp.H, cur_hk);
-                st.reset();
-            }
-            const int L = __builtin_amdgcn_readlane(my_L, idx);
-            const int pos = __builtin_amdgcn_readlane(my_pos, idx);
-            process_quarter_page<T, N>(st, sm.q, sm.q_sum, sm.p[wave], cur, L - pos * NP, tok0, lane, lp.sm_scale_log2);
-            const int extra = __builtin_amdgcn_readlane(my_extra, idx);
-            if (extra > 0) {  // real entries beyond the nominal length: rare, not prefetched
-                const int nominal = plan.first[cur_hk + 1] - plan.first[cur_hk];
-                const int tail = __builtin_amdgcn_readlane(my_tail, idx);
-                for (int e = 0; e < extra; ++e) {
-                    const int epos = tail + nominal + e;
-                    const int ephys = kv.page_table[(size_t)cur_b * kv.max_pages + epos];
-                    const uint4 *ke, *ve;  // only dense heads outgrow their nominal list: always the main pool
-                    slab_of(ephys, cur_hk, ke, ve);
-                    load_k(cur, ke, tok0, lane);
-                    load_v(cur, ve, tok0, r, c, lane);
-                    process_quarter_page<T, N>(st, sm.q, sm.q_sum, sm.p[wave], cur, L - epos * NP, tok0, lane, lp.sm_scale_log2);
+            while (todo) {
+                const int idx = __builtin_ctzll(todo);
+                todo &= todo - 1;
+                if (todo) {
+                    const int idx1 = __builtin_ctzll(todo);
+                    const uint4 *k1, *v1;
+                    slab_of(__builtin_amdgcn_readlane(my_phys, idx1), __builtin_amdgcn_readlane(my_list, idx1) % lp.Hkv, k1, v1);
+                    load_k(nxt, k1, tok0, lane);
+                    load_v(nxt, v1, tok0, r, c, lane);
                 }
+                LSERVE_DECODE_VISIT(idx, cur)
+                cur = nxt;
             }
-            cur = nxt;
+        } else {
+            // Quantised pages are half the bytes, so two are kept in flight to cover the same latency.  The
+            // three stages rotate by name (a copy of a register whose load is still in flight would wait for it).
+            unsigned long long ahead = todo;  // entries whose slabs have not been requested yet
+#define LSERVE_REQUEST(DST)                                                                                              \
+    {                                                                                                                    \
+        const int nx = __builtin_ctzll(ahead);                                                                           \
+        ahead &= ahead - 1;                                                                                              \
+        const uint4 *k1, *v1;                                                                                            \
+        slab_of(__builtin_amdgcn_readlane(my_phys, nx), __builtin_amdgcn_readlane(my_list, nx) % lp.Hkv, k1, v1);        \
+        load_k(DST, k1, tok0, lane);                                                                                     \
+        load_v(DST, v1, tok0, r, c, lane);                                                                               \
+    }
+#define LSERVE_TURN(CUR, FILL)                                                                                           \
+    {                                                                                                                    \
+        const int idx = __builtin_ctzll(todo);                                                                           \
+        todo &= todo - 1;                                                                                                \
+        if (ahead) LSERVE_REQUEST(FILL)                                                                                  \
+        LSERVE_DECODE_VISIT(idx, CUR)                                                                                    \
+        if (!todo) break;                                                                                                \
+    }
+            Slabs<NP, BITS> s0, s1, s2;
+            LSERVE_REQUEST(s0)
+            if (ahead) LSERVE_REQUEST(s1)
+            for (;;) {
+                LSERVE_TURN(s0, s2)
+                LSERVE_TURN(s1, s0)
+                LSERVE_TURN(s2, s1)
+            }
+#undef LSERVE_TURN
+#undef LSERVE_REQUEST
         }
     }
     if (cur_list < 0) return;  // no real entry in this range
     end_piece<T, N, NP, BITS>(st, sm, plan, blk, lo, hi, cur_list, lp.H, lp.Hkv, out, lse_out, part_o, part_ml);
 }
+
+#undef LSERVE_DECODE_VISIT
 
 // Combines the pieces of every list that was cut by a range boundary, in slot order.
 template <class T, int N>
