@@ -169,3 +169,90 @@ def test_decode_loop_over_quantised_pages_matches_the_oracle(name):
         assert_attention_close(out, ref, f"{name} step {step}")
         assert_lse_close(sess.lse, lse_ref, f"{name} step {step}")
     assert near_ties <= 1
+
+
+def test_two_way_cache_of_quantised_pages_equals_the_one_pool_path_bit_for_bit():
+    """Streaming heads in a bounded ring of quantised pages, dense heads compacted in the main pool (Sec. 3.2):
+    the same bytes land at the other addresses and selection, outputs and log-sum-exp are identical to the
+    one-pool quantised path, which the test above holds against the oracle."""
+    from paper_2502_14866_amd.session import DecodeSession
+
+    L = _lib()
+    dev = torch.device("cuda:0")
+    w = small_decode_workload(batch=3, num_q_heads=8, num_kv_heads=4, streaming_kv_heads=(0, 2),
+                              lengths=(700, 64, 1500), decode_steps=6, reuse_interval=2, budget_tokens=256,
+                              sink_tokens=64, local_tokens=192)
+    inp = make_decode_inputs(w)
+    dt = inp.k_pool.dtype
+    flags = w.streaming_flags()
+    dense = [h for h in range(w.num_kv_heads) if h not in w.streaming_kv_heads]
+    stream = list(w.streaming_kv_heads)
+    s, w_ = -(-w.sink_tokens // 64), -(-w.local_tokens // 64)
+    ring = s + w_
+    g = torch.Generator().manual_seed(9)
+    n_ring_pages = w.batch * ring + 3
+    ring_table = torch.randperm(n_ring_pages, generator=g)[: w.batch * ring].to(torch.int32).reshape(w.batch, ring)
+    num_pages = inp.k_pool.shape[0]
+
+    def session(heads, **kw):
+        return DecodeSession(torch.zeros((num_pages, heads, SLAB), dtype=torch.uint8, device=dev),
+                             torch.zeros((num_pages, heads, SLAB), dtype=torch.uint8, device=dev), inp.page_table.to(dev),
+                             w.num_q_heads, flags, w.sink_tokens, w.local_tokens, w.budget_tokens,
+                             logical_page_size=w.logical_page_size, reuse_interval=w.reuse_interval, want_scores=True,
+                             want_lse=True, kv_bits=8, dtype=dt, **kw)
+
+    one = session(w.num_kv_heads)
+    two = session(len(dense), k_pool_stream=torch.full((n_ring_pages, len(stream), SLAB), 0xff, dtype=torch.uint8, device=dev),
+                  v_pool_stream=torch.full((n_ring_pages, len(stream), SLAB), 0xff, dtype=torch.uint8, device=dev),
+                  ring_table=ring_table.to(dev))
+
+    def append(start, n_new):
+        ks, vs = [], []
+        for b in range(w.batch):
+            pos = torch.arange(start[b], start[b] + n_new[b])
+            phys = inp.page_table[b].long()[pos // 64]
+            ks.append(inp.k_pool[phys, :, pos % 64])
+            vs.append(inp.v_pool[phys, :, pos % 64])
+        cu = torch.from_numpy(np.concatenate([[0], np.cumsum(n_new)]).astype(np.int32)).to(dev)
+        k_new, v_new = torch.cat(ks).contiguous().to(dev), torch.cat(vs).contiguous().to(dev)
+        st = torch.tensor(start, dtype=torch.int32, device=dev)
+        for sess in (one, two):
+            sess.append(k_new, v_new, cu, st, max(max(n_new), 1))
+
+    have = [0] * w.batch
+    for step in range(w.decode_steps):
+        seq_cpu = inp.seq_lens_at(step)
+        want = [int(x) for x in seq_cpu]
+        if step == 0:  # the prompt in two chunks, so that local pages of the first chunk get overwritten
+            mid = [x // 2 for x in want]
+            append(have, mid)
+            append(mid, [a - m for a, m in zip(want, mid)])
+        else:
+            append(have, [a - h for a, h in zip(want, have)])
+        have = want
+        torch.cuda.synchronize()
+        k1, v1 = one.kv.k_pool.cpu(), one.kv.v_pool.cpu()
+        assert torch.equal(two.kv.k_pool.cpu(), k1[:, dense]) and torch.equal(two.kv.v_pool.cpu(), v1[:, dense])
+        kr, vr = two.kv.k_pool_stream.cpu(), two.kv.v_pool_stream.cpu()
+        for b in range(w.batch):
+            P = -(-want[b] // 64)
+            for p in [x for x in range(P) if x < s or x >= P - w_]:
+                n_tok = min(64, want[b] - p * 64)
+                src = int(inp.page_table[b, p])
+                dst = int(ring_table[b, p if p < s else s + (p - s) % w_])
+                for pool_r, pool_1 in ((kr, k1), (vr, v1)):
+                    assert torch.equal(pool_r[dst, :, :128 * n_tok], pool_1[src][stream][:, :128 * n_tok]), (step, b, p)
+                    assert torch.equal(pool_r[dst, :, 8192:8192 + 4 * n_tok], pool_1[src][stream][:, 8192:8192 + 4 * n_tok])
+        seq = seq_cpu.to(dev)
+        q = inp.q[step].to(dev)
+        one.set_seq_lens(seq)
+        two.set_seq_lens(seq)
+        if step % w.reuse_interval == 0:
+            one.select(q)
+            two.select(q)
+            assert torch.equal(one.sel_pages, two.sel_pages) and torch.equal(one.sel_count, two.sel_count)
+            assert torch.equal(one.scores, two.scores)
+        o1 = one.decode(q).clone()
+        o2 = two.decode(q)
+        assert torch.equal(o1.view(torch.int16), o2.view(torch.int16)), step
+        assert torch.equal(one.lse, two.lse)
