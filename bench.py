@@ -52,7 +52,7 @@ def parse_args():
     ap.add_argument("--prefill-tokens", type=int, default=65536)
     ap.add_argument("--no-append", action="store_true", help="skip the KV write-back timing")
     ap.add_argument("--no-kv8", action="store_true", help="skip the decode timing over quantised (8-bit) pages")
-    ap.add_argument("--profile-only", default="", choices=["", "decode", "select", "prefill", "stats"],
+    ap.add_argument("--profile-only", default="", choices=["", "decode", "decode8", "select", "prefill", "stats"],
                     help="run only a short loop of one entry point (for rocprofv3)")
     return ap.parse_args()
 
@@ -477,10 +477,9 @@ def bench_append(torch, L, dev, n_tokens, w_dec):
     }
 
 
-def bench_quantised(torch, L, dev, w, inp, sess, len_table):
-    """Sparse decode over 8-bit pages next to the 16-bit call, same cache contents and same selection: the
-    prompt is written into fresh quantised pools by the write-back entry point, then one decode launch of
-    each kind is timed on the selection the 16-bit session last made."""
+def quantised_cache(torch, L, dev, w, inp, sess, reps=0):
+    """The prompts of the decode workload written into fresh 8-bit pools by the write-back entry point.
+    Returns (PagedKV, slab bytes, write-back ms or None, bytes the write-back moves, tokens)."""
     B, Hkv, D, NP = w.batch, w.num_kv_heads, w.head_dim, w.page_size
     slab = NP * D + NP * 4
     num_pages = inp.k_pool.shape[0]
@@ -516,14 +515,41 @@ def bench_quantised(torch, L, dev, w, inp, sess, len_table):
         torch.cuda.synchronize()
         return e0.elapsed_time(e1) / reps
 
-    wb_ms = timed(lambda: L.lserve_append_kv(sess.desc, kv_q, k_new, v_new, cu, zero, max_new), 3)
+    wb_ms = None
+    if reps:
+        wb_ms = timed(lambda: L.lserve_append_kv(sess.desc, kv_q, k_new, v_new, cu, zero, max_new), reps)
+    else:
+        L.lserve_append_kv(sess.desc, kv_q, k_new, v_new, cu, zero, max_new)
+        torch.cuda.synchronize()
     n_tok = int(inp.prompt_lens.sum())
     wb_bytes = 2 * n_tok * Hkv * (D * 2 + D + 4)  # 16-bit rows read, codes and (scale, zero) written, K and V
-    del k_new, v_new
+    return kv_q, slab, wb_ms, wb_bytes, n_tok
+
+
+def bench_quantised(torch, L, dev, w, inp, sess, len_table):
+    """Sparse decode over 8-bit pages next to the 16-bit call, same cache contents and same selection: the
+    prompt is written into fresh quantised pools by the write-back entry point, then one decode launch of
+    each kind is timed on the selection the 16-bit session last made."""
+    B, D = w.batch, w.head_dim
+    kv_q, slab, wb_ms, wb_bytes, n_tok = quantised_cache(torch, L, dev, w, inp, sess, reps=3)
+    seq = kv_q.seq_lens
+
+    def timed(call, reps):
+        call()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(reps):
+            call()
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / reps
+
     # decode at the prompt lengths with the selection of a selector run at those lengths
     sess.restart()
-    sess.step(inp.q[0], len_table[1, :B], len_table[0, :B])
-    kv16 = L.PagedKV(inp.k_pool, inp.v_pool, sess.stats, inp.page_table, seq[:B])
+    sess.set_seq_lens(len_table[0, :B])
+    sess.select(inp.q[0])
+    kv16 = L.PagedKV(inp.k_pool, inp.v_pool, sess.stats, inp.page_table, seq)
     out = torch.empty_like(sess.out)
     q = inp.q[0]
     ms8 = timed(lambda: L.lserve_sparse_decode(sess.desc, kv_q, q, sess.sel_pages, sess.sel_count, sess.sel_seq_len, out,
@@ -531,7 +557,7 @@ def bench_quantised(torch, L, dev, w, inp, sess, len_table):
     out8 = out.clone()
     ms16 = timed(lambda: L.lserve_sparse_decode(sess.desc, kv16, q, sess.sel_pages, sess.sel_count, sess.sel_seq_len, out,
                                                 None, sess.ws_decode), 200)
-    _, pages = decode_bytes_per_launch(w, seq[:B].cpu(), sess.sel_count.cpu(), sess.sel_seq_len.cpu())
+    _, pages = decode_bytes_per_launch(w, seq.cpu(), sess.sel_count.cpu(), sess.sel_seq_len.cpu())
     nbytes = pages * 2 * slab + 2 * B * w.num_q_heads * D * 2 + pages * 8
     return {
         "workload": f"{w.name}: the same cache quantised to 8-bit codes with per-token fp16 scale and zero point, "
@@ -566,10 +592,18 @@ def run_profile_only(args, torch, L, sess, inp, len_table, w, dev):
     sess.update_stats_tail(len_table[0, :B], 1)
     sess.select(inp.q[0])
     torch.cuda.synchronize()
+    kv_q = None
+    if args.profile_only == "decode8":
+        kv_q = quantised_cache(torch, L, dev, w, inp, sess)[0]
+        sess.set_seq_lens(len_table[0, :B])
+        sess.select(inp.q[0])
     for i in range(20):
         t = i % 4
         sess.set_seq_lens(len_table[t + 1, :B])
-        if args.profile_only == "decode":
+        if args.profile_only == "decode8":  # at the prompt lengths: the quantised cache holds the prompts only
+            L.lserve_sparse_decode(sess.desc, kv_q, inp.q[t], sess.sel_pages, sess.sel_count, sess.sel_seq_len, sess.out,
+                                   None, sess.ws_decode)
+        elif args.profile_only == "decode":
             sess.decode(inp.q[t])
         elif args.profile_only == "select":
             sess.select(inp.q[t], stats_valid_len=len_table[t, :B])  # one stale token per sequence, as in the decode loop
