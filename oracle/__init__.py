@@ -14,6 +14,7 @@ from .reference import (  # noqa: F401
     sparse_decode,
     sparse_decode_values,
     quantize_q8,
+    quantize_kv,
     dequantize_q8,
     sparse_prefill_rows,
     block_mask_prefill_rows,

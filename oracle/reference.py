@@ -174,18 +174,22 @@ def sparse_decode(q: torch.Tensor, k_pool: torch.Tensor, v_pool: torch.Tensor, p
     return out, lse
 
 
-def quantize_q8(x: torch.Tensor):
-    """8-bit asymmetric quantisation of KV features, one (scale, zero point) per token and KV head
-    (Sec. 3.2: scale factors and zero points are stored next to the token features).
+def quantize_kv(x: torch.Tensor, bits: int = 8):
+    """Asymmetric quantisation of KV features to `bits` bits (8 or 4), one (scale, zero point) per token
+    and KV head (Sec. 3.2: scale factors and zero points are stored next to the token features).
 
-    x [..., D] in fp16 / bf16 storage.  With lo / hi the smallest / largest feature of a token:
+    x [..., D] in fp16 / bf16 storage.  With lo / hi the smallest / largest feature of a token and
+    top = 2^bits - 1:
         zero  = fp16(lo)                     (saturating at the largest finite fp16)
-        scale = fp16((hi - zero) / 255)      (same saturation)
-        code  = clamp(rint((x - zero) / scale), 0, 255),   all codes 0 when scale == 0
-    and the stored bytes stand for the value code * scale + zero.  The arithmetic that decides a
+        scale = fp16((hi - zero) / top)      (same saturation)
+        code  = clamp(rint((x - zero) / scale), 0, top),   all codes 0 when scale == 0
+    and the stored code stands for the value code * scale + zero.  The arithmetic that decides a
     code runs in IEEE fp32 with round-to-nearest-even, the precision of the GPU kernel, so codes
     can be compared bit for bit.  Returns (codes uint8 [..., D], scale fp16 [...], zero fp16 [...]).
     """
+    if bits not in (4, 8):
+        raise ValueError("bits must be 4 or 8")
+    top = np.float32(2 ** bits - 1)
     xf = x.detach().cpu().float().numpy().astype(np.float32)
     big = np.float32(65504.0)
     lo = xf.min(axis=-1)
@@ -193,16 +197,21 @@ def quantize_q8(x: torch.Tensor):
     zero = np.clip(lo, -big, big).astype(np.float16)
     zf = zero.astype(np.float32)
     with np.errstate(over="ignore", invalid="ignore", divide="ignore"):
-        scale = np.minimum((hi - zf) / np.float32(255.0), big).astype(np.float16)
+        scale = np.minimum((hi - zf) / top, big).astype(np.float16)
         sf = scale.astype(np.float32)
         t = (xf - zf[..., None]) / sf[..., None]
-        codes = np.clip(np.rint(t), 0.0, 255.0)
+        codes = np.clip(np.rint(t), 0.0, top)
     codes = np.where(sf[..., None] > 0, codes, 0.0).astype(np.uint8)
     return codes, scale, zero
 
 
+def quantize_q8(x: torch.Tensor):
+    """quantize_kv with 8 bits."""
+    return quantize_kv(x, 8)
+
+
 def dequantize_q8(codes: np.ndarray, scale: np.ndarray, zero: np.ndarray) -> np.ndarray:
-    """Values the stored bytes stand for: code * scale + zero, exact in float64."""
+    """Values the stored codes stand for (any bit width): code * scale + zero, exact in float64."""
     return codes.astype(np.float64) * scale.astype(np.float64)[..., None] + zero.astype(np.float64)[..., None]
 
 

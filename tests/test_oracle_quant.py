@@ -1,8 +1,8 @@
-"""Pins for the oracle's 8-bit KV quantiser (Sec. 3.2: one scale factor and zero point per token,
+"""Pins for the oracle's 8-bit and 4-bit KV quantiser (Sec. 3.2: one scale factor and zero point per token,
 stored after the token features) and for decode over the values a quantised cache stands for.
 
 The quantiser is a definition (an encoding), so it is pinned by rows whose codes are known by
-construction, by a row worked by hand, by brute force over all 256 codes, and by the error bound
+construction, by a row worked by hand, by brute force over all codes, and by the error bound
 the definition implies."""
 import numpy as np
 import pytest
@@ -49,15 +49,34 @@ def test_a_row_worked_by_hand():
     assert not codes[6:].any()
 
 
+def test_four_bit_rows_known_by_construction_and_by_hand():
+    # lattice: x_c = 2 + k_c / 8 with every k in 0 .. 15 present: scale = 1 / 8, zero = 2, codes = k
+    k = np.arange(128) % 16
+    x = torch.tensor(2.0 + k / 8.0, dtype=torch.float32).to(torch.bfloat16)
+    codes, scale, zero = oracle.quantize_kv(x, 4)
+    assert float(scale) == 0.125 and float(zero) == 2.0 and np.array_equal(codes, k.astype(np.uint8))
+    assert np.array_equal(oracle.dequantize_q8(codes, scale, zero), x.double().numpy())
+    # by hand: lo = 0, hi = 1: 1 / 15 = 0.0666... lies between the fp16 neighbours 2^-4 (1 + 68 / 1024) = 0.06665039
+    # and 2^-4 (1 + 69 / 1024) = 0.06671143 and is nearer the first.  fp16(0.3) = 0.30004883 -> 4.502 -> 5 (the real
+    # quotient 0.3 / (1 / 15) = 4.5 would tie); 0.5 -> 7.502 -> 8; fp16(0.1) = 1638 / 16384 over the scale 1092 / 16384
+    # is exactly 1.5, a tie that goes to the even code 2; fp16(0.9) -> 13.502 -> 14.
+    x = _row([0.0, 1.0, 0.3, 0.5, 0.1, 0.9], fill=0.0)
+    codes, scale, zero = oracle.quantize_kv(x, 4)
+    assert float(scale) == 2.0 ** -4 * (1 + 68 / 1024) and float(zero) == 0.0
+    assert codes[:6].tolist() == [0, 15, 5, 8, 2, 14] and not codes[6:].any()
+
+
+@pytest.mark.parametrize("bits", [8, 4])
 @pytest.mark.parametrize("dtype", [torch.float16, torch.bfloat16])
-def test_codes_are_the_nearest_of_all_256_and_the_error_stays_inside_the_bound(dtype):
+def test_codes_are_the_nearest_of_all_256_and_the_error_stays_inside_the_bound(dtype, bits):
     g = torch.Generator().manual_seed(5)
+    top = 2 ** bits - 1
     x = (torch.randn((40, 3, 128), generator=g) * torch.rand((40, 3, 1), generator=g) * 6 + 2 * torch.randn((40, 3, 1), generator=g)).to(dtype)
-    codes, scale, zero = oracle.quantize_q8(x)
+    codes, scale, zero = oracle.quantize_kv(x, bits)
     xd = x.double().numpy()
     sc, ze = scale.astype(np.float64), zero.astype(np.float64)
     # brute force: distance of every feature to each of the 256 values a byte can stand for
-    grid = np.arange(256, dtype=np.float64)[None, None, None, :] * sc[..., None, None] + ze[..., None, None]
+    grid = np.arange(top + 1, dtype=np.float64)[None, None, None, :] * sc[..., None, None] + ze[..., None, None]
     dist = np.abs(xd[..., None] - grid)
     chosen = np.take_along_axis(dist, codes[..., None].astype(np.int64), axis=-1)[..., 0]
     # a tie between two neighbouring codes may go either way; fp32 rounding of the quotient can move a
@@ -65,9 +84,9 @@ def test_codes_are_the_nearest_of_all_256_and_the_error_stays_inside_the_bound(d
     assert np.all(chosen <= dist.min(axis=-1) + 1e-6 * sc[..., None])
     # the extremes take the end codes; the range is covered up to the fp16 rounding of the scale
     assert np.all(np.take_along_axis(codes, xd.argmin(-1)[..., None], -1) == 0)
-    assert np.all(np.take_along_axis(codes, xd.argmax(-1)[..., None], -1) == 255)
+    assert np.all(np.take_along_axis(codes, xd.argmax(-1)[..., None], -1) == top)
     span = xd.max(-1) - ze
-    assert np.all(np.abs(255 * sc - span) <= span * 2.0 ** -11)
+    assert np.all(np.abs(top * sc - span) <= span * 2.0 ** -11)
     assert np.all(np.abs(ze - xd.min(-1)) <= np.abs(xd.min(-1)) * 2.0 ** -11)
     # error bound: half a step, plus the part of the range the rounded scale and zero point do not cover
     err = np.abs(oracle.dequantize_q8(codes, scale, zero) - xd)
