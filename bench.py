@@ -51,8 +51,8 @@ def parse_args():
     ap.add_argument("--no-prefill", action="store_true")
     ap.add_argument("--prefill-tokens", type=int, default=65536)
     ap.add_argument("--no-append", action="store_true", help="skip the KV write-back timing")
-    ap.add_argument("--no-kv8", action="store_true", help="skip the decode timing over quantised (8-bit) pages")
-    ap.add_argument("--profile-only", default="", choices=["", "decode", "decode8", "select", "prefill", "stats"],
+    ap.add_argument("--no-kv8", action="store_true", help="skip the decode timing over quantised (8- and 4-bit) pages")
+    ap.add_argument("--profile-only", default="", choices=["", "decode", "decode8", "decode4", "select", "prefill", "stats"],
                     help="run only a short loop of one entry point (for rocprofv3)")
     return ap.parse_args()
 
@@ -292,7 +292,8 @@ def main():
             result["append"] = {"error": repr(e)}
     if not args.no_kv8 and w.page_size == 64:
         try:
-            result["kv8"] = bench_quantised(torch, L, dev, w, inp, sess, len_table)
+            result["kv8"] = bench_quantised(torch, L, dev, w, inp, sess, len_table, 8)
+            result["kv4"] = bench_quantised(torch, L, dev, w, inp, sess, len_table, 4)
         except Exception as e:
             result["kv8"] = {"error": repr(e)}
     print(json.dumps(result))
@@ -477,11 +478,11 @@ def bench_append(torch, L, dev, n_tokens, w_dec):
     }
 
 
-def quantised_cache(torch, L, dev, w, inp, sess, reps=0):
-    """The prompts of the decode workload written into fresh 8-bit pools by the write-back entry point.
+def quantised_cache(torch, L, dev, w, inp, sess, bits, reps=0):
+    """The prompts of the decode workload written into fresh 8- or 4-bit pools by the write-back entry point.
     Returns (PagedKV, slab bytes, write-back ms or None, bytes the write-back moves, tokens)."""
     B, Hkv, D, NP = w.batch, w.num_kv_heads, w.head_dim, w.page_size
-    slab = NP * D + NP * 4
+    slab = NP * D * bits // 8 + NP * 4
     num_pages = inp.k_pool.shape[0]
     k_q = torch.zeros((num_pages, Hkv, slab), dtype=torch.uint8, device=dev)
     v_q = torch.zeros_like(k_q)
@@ -500,7 +501,7 @@ def quantised_cache(torch, L, dev, w, inp, sess, reps=0):
         vs.append(inp.v_pool[phys, :, pos % NP])
     k_new, v_new = torch.cat(ks).contiguous(), torch.cat(vs).contiguous()
     del ks, vs
-    kv_q = L.PagedKV(k_q, v_q, stats, inp.page_table, seq[:B], kv_bits=8)
+    kv_q = L.PagedKV(k_q, v_q, stats, inp.page_table, seq[:B], kv_bits=bits)
     zero = torch.zeros((pad,), dtype=torch.int32, device=dev)
     max_new = int(inp.prompt_lens.max())
 
@@ -522,16 +523,16 @@ def quantised_cache(torch, L, dev, w, inp, sess, reps=0):
         L.lserve_append_kv(sess.desc, kv_q, k_new, v_new, cu, zero, max_new)
         torch.cuda.synchronize()
     n_tok = int(inp.prompt_lens.sum())
-    wb_bytes = 2 * n_tok * Hkv * (D * 2 + D + 4)  # 16-bit rows read, codes and (scale, zero) written, K and V
+    wb_bytes = 2 * n_tok * Hkv * (D * 2 + D * bits // 8 + 4)  # 16-bit rows read, codes and (scale, zero) written, K and V
     return kv_q, slab, wb_ms, wb_bytes, n_tok
 
 
-def bench_quantised(torch, L, dev, w, inp, sess, len_table):
-    """Sparse decode over 8-bit pages next to the 16-bit call, same cache contents and same selection: the
+def bench_quantised(torch, L, dev, w, inp, sess, len_table, bits):
+    """Sparse decode over 8- or 4-bit pages next to the 16-bit call, same cache contents and same selection: the
     prompt is written into fresh quantised pools by the write-back entry point, then one decode launch of
     each kind is timed on the selection the 16-bit session last made."""
     B, D = w.batch, w.head_dim
-    kv_q, slab, wb_ms, wb_bytes, n_tok = quantised_cache(torch, L, dev, w, inp, sess, reps=3)
+    kv_q, slab, wb_ms, wb_bytes, n_tok = quantised_cache(torch, L, dev, w, inp, sess, bits, reps=3)
     seq = kv_q.seq_lens
 
     def timed(call, reps):
@@ -560,7 +561,7 @@ def bench_quantised(torch, L, dev, w, inp, sess, len_table):
     _, pages = decode_bytes_per_launch(w, seq.cpu(), sess.sel_count.cpu(), sess.sel_seq_len.cpu())
     nbytes = pages * 2 * slab + 2 * B * w.num_q_heads * D * 2 + pages * 8
     return {
-        "workload": f"{w.name}: the same cache quantised to 8-bit codes with per-token fp16 scale and zero point, "
+        "workload": f"{w.name}: the same cache quantised to {bits}-bit codes with per-token fp16 scale and zero point, "
                     "eager launches on one selection",
         "decode_launch_ms": ms8,
         "decode_launch_ms_16bit_same_selection": ms16,
@@ -593,14 +594,14 @@ def run_profile_only(args, torch, L, sess, inp, len_table, w, dev):
     sess.select(inp.q[0])
     torch.cuda.synchronize()
     kv_q = None
-    if args.profile_only == "decode8":
-        kv_q = quantised_cache(torch, L, dev, w, inp, sess)[0]
+    if args.profile_only in ("decode8", "decode4"):
+        kv_q = quantised_cache(torch, L, dev, w, inp, sess, int(args.profile_only[-1]))[0]
         sess.set_seq_lens(len_table[0, :B])
         sess.select(inp.q[0])
     for i in range(20):
         t = i % 4
         sess.set_seq_lens(len_table[t + 1, :B])
-        if args.profile_only == "decode8":  # at the prompt lengths: the quantised cache holds the prompts only
+        if kv_q is not None:  # at the prompt lengths: the quantised cache holds the prompts only
             L.lserve_sparse_decode(sess.desc, kv_q, inp.q[t], sess.sel_pages, sess.sel_count, sess.sel_seq_len, sess.out,
                                    None, sess.ws_decode)
         elif args.profile_only == "decode":

@@ -99,13 +99,15 @@ typedef struct lserve_attn_desc {
  * k_pool_stream may also be given next to a main pool that holds every head (pool_heads == Hkv):
  * the streaming heads are then read from and written to the ring only.
  *
- * Quantised pages (kv_bits == 8; Sec. 3.2: scale factors and zero points are stored right after the
+ * Quantised pages (kv_bits == 8 or 4; Sec. 3.2: scale factors and zero points are stored right after the
  * token features; Sec. 3.5: low-bit KV is why the physical page is 64 tokens).  Requires N_P == 64.  Every
- * pool then stores, per (page, head), 64 rows of D one-byte codes followed by 64 pairs (scale, zero) of
- * fp16, 64 * D + 256 bytes in all, and a stored row stands for code * scale + zero.  The quantiser is
- * per token and per KV head, separately for K and V:
- *     zero = fp16(min_c x_c), scale = fp16((max_c x_c - zero) / 255),
- *     code_c = clamp(rint((x_c - zero) / scale), 0, 255), all codes 0 when scale == 0,
+ * pool then stores, per (page, head), 64 rows of D codes of kv_bits bits followed by 64 pairs (scale, zero)
+ * of fp16, 64 * D * kv_bits / 8 + 256 bytes in all, and a stored row stands for code * scale + zero.  8-bit
+ * rows hold channel c in byte c.  4-bit rows are D / 8 words of four bytes, byte j of word g holding channel
+ * 8 g + j in its low half and channel 8 g + 4 + j in its high half.  The quantiser is per token and per KV
+ * head, separately for K and V, with top = 2^kv_bits - 1:
+ *     zero = fp16(min_c x_c), scale = fp16((max_c x_c - zero) / top),
+ *     code_c = clamp(rint((x_c - zero) / scale), 0, top), all codes 0 when scale == 0,
  * in IEEE fp32 with round to nearest even (fp16 conversions saturate at 65504).  lserve_append_kv writes
  * such pages (statistics are taken from the 16-bit keys it is handed) and lserve_sparse_decode reads them;
  * lserve_select_pages works from the statistics alone, so only its rebuild of stale statistics
@@ -113,7 +115,7 @@ typedef struct lserve_attn_desc {
  * LSERVE_ERR_UNSUPPORTED.  The stats array keeps the 16-bit layout.
  */
 typedef struct lserve_paged_kv {
-    void *k_pool;              /* device, [num_pages][pool_heads][N_P][D]; kv_bits == 8: [num_pages][pool_heads][64 * D + 256] bytes */
+    void *k_pool;              /* device, [num_pages][pool_heads][N_P][D]; quantised: [num_pages][pool_heads][64 * D * kv_bits / 8 + 256] bytes */
     void *v_pool;              /* device, same shape as k_pool */
     void *stats;               /* device, [num_pages][pool_heads][g][2][D]; [..][0][:] = max, [..][1][:] = min */
     const int32_t *page_table; /* device, [batch][max_pages_per_seq], physical page ids in [0, num_pages) */
@@ -126,7 +128,7 @@ typedef struct lserve_paged_kv {
     void *v_pool_stream;       /* device, same shape, or NULL (both or neither) */
     const int32_t *ring_table; /* device, [batch][s + w], page ids in [0, num_pages_stream) */
     int32_t num_pages_stream;
-    int32_t kv_bits;           /* 0 or 16: K/V rows in the 16-bit dtype of the layer; 8: quantised pages */
+    int32_t kv_bits;           /* 0 or 16: K/V rows in the 16-bit dtype of the layer; 8 or 4: quantised pages */
 } lserve_paged_kv;
 
 /*

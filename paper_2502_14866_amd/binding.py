@@ -151,7 +151,8 @@ class PagedKV:
     k_pool_stream: Optional[torch.Tensor] = None
     v_pool_stream: Optional[torch.Tensor] = None
     ring_table: Optional[torch.Tensor] = None
-    # 16: pools of the layer's 16-bit dtype [pages, heads, N_P, D]; 8: quantised pages, uint8 [pages, heads, 64 * D + 256]
+    # 16: pools of the layer's 16-bit dtype [pages, heads, N_P, D]; 8 or 4: quantised pages, uint8
+    # [pages, heads, 64 * D * kv_bits / 8 + 256]
     kv_bits: int = 16
 
     def c(self):

@@ -116,13 +116,13 @@ struct PagedParams {
     const void *k_stream, *v_stream;  // bounded pool of the streaming heads (Sec. 3.2), or null
     const int* ring_table;            // [batch][ring]
     int stream_heads, ring;           // heads per page of that pool; ring = s + w slots per sequence
-    int kv_bits;                      // 16: K/V rows in 16-bit storage; 8: quantised pages
+    int kv_bits;                      // 16: K/V rows in 16-bit storage; 8 or 4: quantised pages
 };
 
 // Size of one (page, KV head) slab of a K or V pool, in 16-byte units.  16-bit storage: N_P rows of 256
-// bytes.  Quantised (Sec. 3.2): N_P rows of 128 one-byte codes, then N_P (scale, zero) pairs of fp16.
+// bytes.  Quantised (Sec. 3.2): N_P rows of 128 codes of `bits` bits, then N_P (scale, zero) pairs of fp16.
 __host__ __device__ __forceinline__ constexpr size_t slab_chunks(int NP, int bits) {
-    return bits == 16 ? (size_t)NP * (kHeadDim / 8) : (size_t)NP * (kHeadDim / 16) + NP / 4;
+    return bits == 16 ? (size_t)NP * (kHeadDim / 8) : (size_t)NP * (kHeadDim * bits / 128) + NP / 4;
 }
 
 // Ring slot of the page at position p of a streaming head's sequence: sink pages keep their place,

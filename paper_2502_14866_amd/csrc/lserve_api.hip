@@ -85,9 +85,9 @@ int make_paged(const lserve_paged_kv* kv, const LayerParams& lp, bool need_k, bo
         if (!aligned16(kv->k_pool_stream) || !aligned16(kv->v_pool_stream) || !aligned16(kv->ring_table))
             return LSERVE_ERR_INVALID_ARG;
     }
-    if (kv->kv_bits != 0 && kv->kv_bits != 16 && kv->kv_bits != 8) return LSERVE_ERR_INVALID_ARG;
-    pp->kv_bits = kv->kv_bits == 8 ? 8 : 16;
-    if (pp->kv_bits == 8 && lp.NP != 64) return LSERVE_ERR_UNSUPPORTED;
+    if (kv->kv_bits != 0 && kv->kv_bits != 16 && kv->kv_bits != 8 && kv->kv_bits != 4) return LSERVE_ERR_INVALID_ARG;
+    pp->kv_bits = kv->kv_bits == 0 ? 16 : kv->kv_bits;
+    if (pp->kv_bits != 16 && lp.NP != 64) return LSERVE_ERR_UNSUPPORTED;
     const bool main_holds_all = pp->pool_heads == lp.Hkv;
     if (need_stream && n_stream > 0 && !main_holds_all && !pp->k_stream) return LSERVE_ERR_INVALID_ARG;
     return LSERVE_OK;

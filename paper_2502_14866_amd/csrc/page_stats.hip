@@ -61,13 +61,13 @@ __global__ __launch_bounds__(kWave* kMaxLogical) void page_stats_kernel(LayerPar
     }
 }
 
-// 8-bit asymmetric quantisation of one token row held by the 16 lanes of a DPP row, eight features per
-// lane (Sec. 3.2: scale factor and zero point of a token are stored next to its features):
-//   zero = fp16(min), scale = fp16((max - zero) / 255), code = clamp(rint((x - zero) / scale), 0, 255),
-// every step in IEEE fp32 (true divisions) so that the codes do not depend on the machine.  Returns the
+// Asymmetric quantisation of one token row held by the 16 lanes of a DPP row, eight features per lane
+// (Sec. 3.2: scale factor and zero point of a token are stored next to its features), to codes 0 .. LEVELS:
+//   zero = fp16(min), scale = fp16((max - zero) / LEVELS), code = clamp(rint((x - zero) / scale), 0, LEVELS),
+// every step in IEEE fp32 (true divisions) so that the codes do not depend on the machine.  Yields the
 // lane's eight codes and the token's (scale, zero) pair as two fp16 in one word.
-template <class T>
-__device__ __forceinline__ uint2 quantize_row_q8(const uint4& x, uint32_t& scale_zero) {
+template <class T, int LEVELS>
+__device__ __forceinline__ void quantize_row(const uint4& x, uint32_t (&c)[8], uint32_t& scale_zero) {
     const uint32_t w[4] = {x.x, x.y, x.z, x.w};
     float f[8];
 #pragma unroll
@@ -92,25 +92,33 @@ __device__ __forceinline__ uint2 quantize_row_q8(const uint4& x, uint32_t& scale
     constexpr float kBig = 65504.f;  // largest finite fp16
     const _Float16 zero_h = (_Float16)fminf(fmaxf(lo, -kBig), kBig);
     const float zero = (float)zero_h;
-    const _Float16 scale_h = (_Float16)fminf((hi - zero) / 255.0f, kBig);
+    const _Float16 scale_h = (_Float16)fminf((hi - zero) / (float)LEVELS, kBig);
     const float scale = (float)scale_h;
-    uint32_t c[8];
 #pragma unroll
     for (int i = 0; i < 8; ++i) {
-        const float t = fminf(fmaxf(__builtin_rintf((f[i] - zero) / scale), 0.f), 255.f);
+        const float t = fminf(fmaxf(__builtin_rintf((f[i] - zero) / scale), 0.f), (float)LEVELS);
         c[i] = scale > 0.f ? (uint32_t)t : 0u;
     }
     const half2_t sz = {scale_h, zero_h};
     scale_zero = __builtin_bit_cast(uint32_t, sz);
+}
+// One byte per code, features in order.
+__device__ __forceinline__ uint2 pack_codes8(const uint32_t (&c)[8]) {
     return make_uint2(c[0] | (c[1] << 8) | (c[2] << 16) | (c[3] << 24), c[4] | (c[5] << 8) | (c[6] << 16) | (c[7] << 24));
+}
+// Two codes per byte: byte j of the word holds feature j in its low and feature 4 + j in its high half, so
+// that masking out either half leaves four codes in the byte lanes the 8-bit path uses.
+__device__ __forceinline__ uint32_t pack_codes4(const uint32_t (&c)[8]) {
+    return (c[0] | (c[4] << 4)) | ((c[1] | (c[5] << 4)) << 8) | ((c[2] | (c[6] << 4)) << 16) | ((c[3] | (c[7] << 4)) << 24);
 }
 
 // KV write-back with the statistics updated in the same pass (Sec. 3.2, Sec. 3.5.2): one workgroup per
 // (physical page touched by the new tokens, KV head, sequence), one wavefront per logical page.  New
 // rows are copied into both pools with 16-byte accesses; for non-streaming heads the wave folds the
 // new keys into max / min rows and, when the logical page already held tokens, combines them with the
-// stored rows instead of re-reading the old keys.  BITS = 8 stores the rows quantised (one byte per feature,
-// then the page's (scale, zero) pairs); the statistics are still those of the 16-bit keys handed in.
+// stored rows instead of re-reading the old keys.  BITS = 8 or 4 stores the rows quantised (one byte or half
+// a byte per feature, then the page's (scale, zero) pairs); the statistics are still those of the 16-bit
+// keys handed in.
 template <class T, int BITS>
 __global__ __launch_bounds__(kWave* kMaxLogical) void append_kv_kernel(LayerParams lp, PagedParams kv,
                                                                         const uint4* __restrict__ k_new,
@@ -162,13 +170,19 @@ __global__ __launch_bounds__(kWave* kMaxLogical) void append_kv_kernel(LayerPara
             kdst[dst] = x;
             vdst[dst] = y;
         } else {
-            uint32_t ksz, vsz;
-            const uint2 kc = quantize_row_q8<T>(x, ksz), vc = quantize_row_q8<T>(y, vsz);
-            reinterpret_cast<uint2*>(kdst)[(size_t)slot * (kHeadDim / 8) + c] = kc;
-            reinterpret_cast<uint2*>(vdst)[(size_t)slot * (kHeadDim / 8) + c] = vc;
-            if (c == 0) {
-                reinterpret_cast<uint32_t*>(kdst + lp.NP * (kHeadDim / 16))[slot] = ksz;
-                reinterpret_cast<uint32_t*>(vdst + lp.NP * (kHeadDim / 16))[slot] = vsz;
+            uint32_t ksz, vsz, kc[8], vc[8];
+            quantize_row<T, (1 << BITS) - 1>(x, kc, ksz);
+            quantize_row<T, (1 << BITS) - 1>(y, vc, vsz);
+            if (BITS == 8) {
+                reinterpret_cast<uint2*>(kdst)[(size_t)slot * (kHeadDim / 8) + c] = pack_codes8(kc);
+                reinterpret_cast<uint2*>(vdst)[(size_t)slot * (kHeadDim / 8) + c] = pack_codes8(vc);
+            } else {
+                reinterpret_cast<uint32_t*>(kdst)[(size_t)slot * (kHeadDim / 8) + c] = pack_codes4(kc);
+                reinterpret_cast<uint32_t*>(vdst)[(size_t)slot * (kHeadDim / 8) + c] = pack_codes4(vc);
+            }
+            if (c == 0) {  // the pairs follow the page's code rows
+                reinterpret_cast<uint32_t*>(kdst + lp.NP * (kHeadDim * BITS / 128))[slot] = ksz;
+                reinterpret_cast<uint32_t*>(vdst + lp.NP * (kHeadDim * BITS / 128))[slot] = vsz;
             }
         }
         const uint32_t w[4] = {x.x, x.y, x.z, x.w};
@@ -219,6 +233,11 @@ hipError_t launch_append_kv(int dtype, const LayerParams& lp, const PagedParams&
             hipLaunchKernelGGL((append_kv_kernel<F16, 8>), grid, block, 0, stream, lp, kv, k4, v4, cu_new, start_pos);
         else
             hipLaunchKernelGGL((append_kv_kernel<BF16, 8>), grid, block, 0, stream, lp, kv, k4, v4, cu_new, start_pos);
+    } else if (kv.kv_bits == 4) {
+        if (dtype == 0)
+            hipLaunchKernelGGL((append_kv_kernel<F16, 4>), grid, block, 0, stream, lp, kv, k4, v4, cu_new, start_pos);
+        else
+            hipLaunchKernelGGL((append_kv_kernel<BF16, 4>), grid, block, 0, stream, lp, kv, k4, v4, cu_new, start_pos);
     } else if (dtype == 0) {
         hipLaunchKernelGGL((append_kv_kernel<F16, 16>), grid, block, 0, stream, lp, kv, k4, v4, cu_new, start_pos);
     } else {

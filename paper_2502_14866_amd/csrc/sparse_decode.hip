@@ -94,6 +94,14 @@ template <> struct Slabs<64, 8> {
     uint2 v[4];
     uint32_t ksz, vsz;
 };
+// 4-bit codes: a token row is 64 bytes, byte j of every 4-byte word holding channel 8 g + j in its low and
+// channel 8 g + 4 + j in its high half (g = index of the word).  One 16-byte chunk per key lane, one word per
+// value lane.
+template <> struct Slabs<64, 4> {
+    uint4 k[1];
+    uint32_t v[4];
+    uint32_t ksz, vsz;
+};
 
 template <int NP>
 __device__ __forceinline__ void load_k(Slabs<NP, 16>& s, const uint4* kslab, int tok0, int lane) {
@@ -112,6 +120,17 @@ __device__ __forceinline__ void load_v(Slabs<NP, 16>& s, const uint4* vslab, int
     for (int it = 0; it < KeyMap<NP>::ITS; ++it) s.v[it] = vslab[(size_t)(tok0 + 4 * it + r) * (kHeadDim / 8) + c];
 }
 
+__device__ __forceinline__ void load_k(Slabs<64, 4>& s, const uint4* kslab, int tok0, int lane) {
+    const int tok = tok0 + lane / 4;
+    s.k[0] = kslab[(size_t)tok * (kHeadDim / 32) + lane % 4];
+    s.ksz = reinterpret_cast<const uint32_t*>(kslab + 64 * (kHeadDim / 32))[tok];
+}
+__device__ __forceinline__ void load_v(Slabs<64, 4>& s, const uint4* vslab, int tok0, int r, int c, int lane) {
+    const uint32_t* rows = reinterpret_cast<const uint32_t*>(vslab);
+#pragma unroll
+    for (int it = 0; it < 4; ++it) s.v[it] = rows[(size_t)(tok0 + 4 * it + r) * (kHeadDim / 8) + c];
+    s.vsz = reinterpret_cast<const uint32_t*>(vslab + 64 * (kHeadDim / 32))[tok0 + lane / 4];
+}
 __device__ __forceinline__ void load_k(Slabs<64, 8>& s, const uint4* kslab, int tok0, int lane) {
     const int tok = tok0 + lane / 4;
 #pragma unroll
@@ -261,28 +280,40 @@ __device__ __forceinline__ void process_quarter_page(WaveState<N>& st, const uin
 // to every dot product is taken off again.  For values the weight is folded into the scale,
 //   sum_t p_t v_t = sum_t (p_t scale_t) code_t + sum_t p_t zero_t,
 // and the second sum, which no channel distinguishes, is kept as one number per query head.
-template <class T, int N>
-__device__ __forceinline__ void process_quarter_page(WaveState<N>& st, const uint4* q_lds, const float* q_sum,
-                                                     float* p_lds, Slabs<64, 8>& cur, int valid, int tok0, int lane,
+template <class T, int N, int BITS>
+__device__ __forceinline__ void process_quantised_quarter_page(WaveState<N>& st, const uint4* q_lds, const float* q_sum,
+                                                     float* p_lds, Slabs<64, BITS>& cur, int valid, int tok0, int lane,
                                                      float scale_log2) {
+    static_assert(BITS == 8 || BITS == 4, "quantised pages");
     constexpr int PR = p_row(N);
     const int r = lane / 16;
     float s[N];
 #pragma unroll
     for (int hh = 0; hh < N; ++hh) s[hh] = 0.f;
+    // 16 channels at a time: four bytes-per-code words (two of the 8-bit chunk's words, or the low and the high
+    // halves of two of the 4-bit chunk's words) become eight fp16 pairs and meet two 8-channel query chunks
 #pragma unroll
     for (int j = 0; j < 2; ++j) {
-        const uint32_t kw[4] = {cur.k[j].x, cur.k[j].y, cur.k[j].z, cur.k[j].w};
+        uint32_t kw[4];
+        int qc;  // first of the two query chunks
+        if constexpr (BITS == 8) {
+            kw[0] = cur.k[j].x, kw[1] = cur.k[j].y, kw[2] = cur.k[j].z, kw[3] = cur.k[j].w;
+            qc = 2 * (4 * j + lane % 4);  // 16-byte chunk 4 j + lane % 4 of the row = channels 16 cb .. 16 cb + 15
+        } else {
+            const uint32_t w0 = j == 0 ? cur.k[0].x : cur.k[0].z, w1 = j == 0 ? cur.k[0].y : cur.k[0].w;
+            kw[0] = w0 & 0x0f0f0f0fu, kw[1] = (w0 >> 4) & 0x0f0f0f0fu;  // channels 8 g .. 8 g + 3, 8 g + 4 .. 8 g + 7
+            kw[2] = w1 & 0x0f0f0f0fu, kw[3] = (w1 >> 4) & 0x0f0f0f0fu;
+            qc = 4 * (lane % 4) + 2 * j;  // word g = 4 (lane % 4) + 2 j + {0, 1} of the row = channels 8 g .. 8 g + 7
+        }
         uint32_t kh[8];  // 16 codes as eight fp16 pairs (1024 + code)
 #pragma unroll
         for (int d = 0; d < 4; ++d) {
             kh[2 * d] = __builtin_amdgcn_perm(0x64646464u, kw[d], 0x04010400u);
             kh[2 * d + 1] = __builtin_amdgcn_perm(0x64646464u, kw[d], 0x04030402u);
         }
-        const int cb = 4 * j + lane % 4;  // 16-byte chunk of codes = channels 16 cb .. 16 cb + 15
 #pragma unroll
         for (int hh = 0; hh < N; ++hh) {
-            const uint4 qa = q_lds[hh * 16 + 2 * cb], qb = q_lds[hh * 16 + 2 * cb + 1];
+            const uint4 qa = q_lds[hh * 16 + qc], qb = q_lds[hh * 16 + qc + 1];
             const uint32_t qw[8] = {qa.x, qa.y, qa.z, qa.w, qb.x, qb.y, qb.z, qb.w};
 #pragma unroll
             for (int u = 0; u < 8; ++u) s[hh] = Elem<F16>::dot2(qw[u], kh[u], s[hh]);
@@ -320,7 +351,12 @@ __device__ __forceinline__ void process_quarter_page(WaveState<N>& st, const uin
     __builtin_amdgcn_wave_barrier();
 #pragma unroll
     for (int it = 0; it < 4; ++it) {
-        uint2 vv = cur.v[it];
+        uint2 vv;  // one byte per code, channels in order
+        if constexpr (BITS == 8) {
+            vv = cur.v[it];
+        } else {
+            vv = make_uint2(cur.v[it] & 0x0f0f0f0fu, (cur.v[it] >> 4) & 0x0f0f0f0fu);
+        }
         if (valid < 64 && tok0 + 4 * it + r >= valid) vv = make_uint2(0, 0);
         float pv[PR];
 #pragma unroll
@@ -340,6 +376,15 @@ __device__ __forceinline__ void process_quarter_page(WaveState<N>& st, const uin
             for (int i = 0; i < 8; ++i) st.o[hh][i] = __builtin_fmaf(pv[hh], code[i], st.o[hh][i]);
     }
     __builtin_amdgcn_wave_barrier();
+}
+
+template <class T, int N, int NP, int BITS>
+__device__ __forceinline__ void process_quarter(WaveState<N>& st, const uint4* q_lds, const float* q_sum, float* p_lds,
+                                                Slabs<NP, BITS>& cur, int valid, int tok0, int lane, float scale_log2) {
+    if constexpr (BITS == 16)
+        process_quarter_page<T, N, NP>(st, q_lds, q_sum, p_lds, cur, valid, tok0, lane, scale_log2);
+    else
+        process_quantised_quarter_page<T, N, BITS>(st, q_lds, q_sum, p_lds, cur, valid, tok0, lane, scale_log2);
 }
 
 // Shared memory of a decode workgroup.
@@ -559,7 +604,7 @@ __device__ __forceinline__ void end_piece(WaveState<N>& st, DecodeShared<N, NP>&
         }                                                                                                            \
         const int L = __builtin_amdgcn_readlane(my_L, (IDX));                                                        \
         const int pos = __builtin_amdgcn_readlane(my_pos, (IDX));                                                    \
-        process_quarter_page<T, N>(st, sm.q, sm.q_sum, sm.p[wave], CUR, L - pos * NP, tok0, lane, lp.sm_scale_log2); \
+        process_quarter<T, N, NP, BITS>(st, sm.q, sm.q_sum, sm.p[wave], CUR, L - pos * NP, tok0, lane, lp.sm_scale_log2); \
         const int extra = __builtin_amdgcn_readlane(my_extra, (IDX));                                                \
         if (extra > 0) {                                                                                             \
             const int nominal = plan.first[cur_hk + 1] - plan.first[cur_hk];                                         \
@@ -571,7 +616,7 @@ __device__ __forceinline__ void end_piece(WaveState<N>& st, DecodeShared<N, NP>&
                 slab_of(ephys, cur_hk, ke, ve);                                                                      \
                 load_k(CUR, ke, tok0, lane);                                                                         \
                 load_v(CUR, ve, tok0, r, c, lane);                                                                   \
-                process_quarter_page<T, N>(st, sm.q, sm.q_sum, sm.p[wave], CUR, L - epos * NP, tok0, lane, lp.sm_scale_log2);\
+                process_quarter<T, N, NP, BITS>(st, sm.q, sm.q_sum, sm.p[wave], CUR, L - epos * NP, tok0, lane, lp.sm_scale_log2);\
             }                                                                                                        \
         }                                                                                                            \
     }
@@ -799,6 +844,9 @@ hipError_t launch_decode_np(const LayerParams& lp, const PagedParams& kv, const 
                                                     lse_out, part_o, part_ml, stream);
     if (kv.kv_bits == 8)  // quantised pages are always 64 tokens (checked by the caller)
         return launch_decode_kernels<T, N, 64, 8>(lp, kv, q, sel_pages, sel_count, sel_seq_len, sel_stride, out, lse_out,
+                                                  part_o, part_ml, stream);
+    if (kv.kv_bits == 4)
+        return launch_decode_kernels<T, N, 64, 4>(lp, kv, q, sel_pages, sel_count, sel_seq_len, sel_stride, out, lse_out,
                                                   part_o, part_ml, stream);
     switch (lp.NP) {
         LSERVE_DECODE_NP(16)

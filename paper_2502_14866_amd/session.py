@@ -24,11 +24,12 @@ class DecodeSession:
                  v_pool_stream: Optional[torch.Tensor] = None, ring_table: Optional[torch.Tensor] = None,
                  kv_bits: int = 16, dtype: Optional[torch.dtype] = None):
         """k_pool / v_pool hold every KV head, or only the non-streaming ones when the streaming heads live in
-        the bounded pool k_pool_stream / v_pool_stream behind ring_table (two-way cache).  kv_bits = 8: the pools
-        are uint8 [pages, heads, 64 * 128 + 256] (quantised pages, written by `append`), `dtype` names the 16-bit
-        type of queries, outputs and statistics, and the statistics are kept current by `append` alone."""
+        the bounded pool k_pool_stream / v_pool_stream behind ring_table (two-way cache).  kv_bits = 8 or 4: the
+        pools are uint8 [pages, heads, 64 * 128 * kv_bits / 8 + 256] (quantised pages, written by `append`), `dtype`
+        names the 16-bit type of queries, outputs and statistics, and the statistics are kept current by `append`
+        alone."""
         dev = k_pool.device
-        if kv_bits == 8:
+        if kv_bits != 16:
             num_pages, pool_heads, _ = k_pool.shape
             page_size, head_dim = 64, 128
             if dtype is None:

@@ -147,11 +147,12 @@ def test_invalid_arguments_are_rejected_on_the_host(L):
     assert _rc(lambda: L.lserve_sparse_prefill_paged(desc(page_size=32), kv, q, cu4, 2, 64, out, None, ws, stream)) == -2
     assert _rc(lambda: L.lserve_sparse_prefill_paged(desc(), kv, q, cu4, 2, 64, out, None, ws[:64], stream)) == -3
     assert L.lserve_paged_prefill_workspace_bytes(desc(), 2, 4) == 2 * 2 * 4 * 128 * 64 * 2
-    # quantised pages: only 8 bits and 64-token pages; no statistics from the pages, no paged prefill
+    # quantised pages: only 8 or 4 bits and 64-token pages; no statistics from the pages, no paged prefill
     def q8(bits=8):
         return L.PagedKV(kv.k_pool, kv.v_pool, kv.stats, kv.page_table, kv.seq_lens, kv_bits=bits)
-    assert _rc(lambda: L.lserve_sparse_decode(desc(), q8(4), q, sel, cnt, ssl, out, None, ws, stream)) == -1
     d32 = desc(page_size=32)
+    assert _rc(lambda: L.lserve_sparse_decode(desc(), q8(5), q, sel, cnt, ssl, out, None, ws, stream)) == -1
+    assert _rc(lambda: L.lserve_sparse_decode(d32, q8(4), q, sel, cnt, ssl, out, None, ws, stream)) == -2
     assert _rc(lambda: L.lserve_sparse_decode(d32, q8(), q, sel, cnt, ssl, out, None, ws, stream)) == -2
     assert _rc(lambda: L.lserve_append_kv(d32, q8(), kn, kn, cu4, cu4, 1, stream)) == -2
     assert _rc(lambda: L.lserve_build_page_stats(desc(), q8(), None, 0, stream)) == -2

@@ -12,7 +12,25 @@ from parity import assert_attention_close, assert_lse_close, compare_selection
 
 pytestmark = pytest.mark.gpu
 
-SLAB = 64 * 128 + 256  # bytes of one (page, head): codes, then 64 (scale, zero) pairs of fp16
+def slab_bytes(bits):
+    """Bytes of one (page, head): 64 rows of 128 codes, then 64 (scale, zero) pairs of fp16."""
+    return 64 * 128 * bits // 8 + 256
+
+
+def _pack_rows(codes: np.ndarray, bits: int) -> np.ndarray:
+    """[n, 128] codes -> [n, 128 * bits / 8] bytes in the page's row format (layout only)."""
+    if bits == 8:
+        return codes
+    c = codes.reshape(-1, 16, 2, 4)  # word g, half (channels 8 g + 0..3 / 8 g + 4..7), byte j
+    return (c[:, :, 0, :] | (c[:, :, 1, :] << 4)).reshape(-1, 64).astype(np.uint8)
+
+
+def _unpack_rows(raw: np.ndarray, bits: int) -> np.ndarray:
+    """[..., 128 * bits / 8] bytes -> [..., 128] codes."""
+    if bits == 8:
+        return raw
+    w = raw.reshape(raw.shape[:-1] + (16, 4))
+    return np.stack([w & 0xf, w >> 4], axis=-2).reshape(raw.shape[:-1] + (128,))
 
 
 def _lib():
@@ -22,28 +40,33 @@ def _lib():
     return L
 
 
-def _write_rows(pool_q: torch.Tensor, phys, hk, slot, x_rows: torch.Tensor):
+def _write_rows(pool_q: torch.Tensor, phys, hk, slot, x_rows: torch.Tensor, bits: int):
     """Oracle-quantised rows x_rows [n, 128] into slots (phys[i], hk, slot[i]) of a CPU byte pool."""
-    codes, scale, zero = oracle.quantize_q8(x_rows)
+    codes, scale, zero = oracle.quantize_kv(x_rows, bits)
+    rows = _pack_rows(codes, bits)
+    rb, tail = 128 * bits // 8, 64 * 128 * bits // 8
     sz = np.stack([scale, zero], axis=-1).view(np.uint8).reshape(-1, 4)
     for i in range(x_rows.shape[0]):
         slab = pool_q[int(phys[i]), hk]
-        slab[int(slot[i]) * 128:(int(slot[i]) + 1) * 128] = torch.from_numpy(codes[i])
-        slab[8192 + 4 * int(slot[i]):8192 + 4 * int(slot[i]) + 4] = torch.from_numpy(sz[i])
+        slab[int(slot[i]) * rb:(int(slot[i]) + 1) * rb] = torch.from_numpy(rows[i])
+        slab[tail + 4 * int(slot[i]):tail + 4 * int(slot[i]) + 4] = torch.from_numpy(sz[i])
 
 
-def _values(pool_q: torch.Tensor) -> np.ndarray:
+def _values(pool_q: torch.Tensor, bits: int) -> np.ndarray:
     """[pages, heads, 64, 128] float64 values a CPU byte pool stands for (unwritten slots: whatever they hold)."""
     raw = pool_q.numpy()
-    codes = raw[..., :8192].reshape(raw.shape[0], raw.shape[1], 64, 128)
-    sz = np.ascontiguousarray(raw[..., 8192:]).view(np.float16).reshape(raw.shape[0], raw.shape[1], 64, 2)
+    tail = 64 * 128 * bits // 8
+    codes = _unpack_rows(raw[..., :tail].reshape(raw.shape[0], raw.shape[1], 64, 128 * bits // 8), bits)
+    sz = np.ascontiguousarray(raw[..., tail:]).view(np.float16).reshape(raw.shape[0], raw.shape[1], 64, 2)
     with np.errstate(invalid="ignore", over="ignore"):
         return oracle.dequantize_q8(codes, sz[..., 0], sz[..., 1])
 
 
+@pytest.mark.parametrize("bits", [8, 4])
 @pytest.mark.parametrize("dtype", ["fp16", "bf16"])
-def test_quantising_append_writes_the_oracles_bytes_and_nothing_else(dtype):
+def test_quantising_append_writes_the_oracles_bytes_and_nothing_else(dtype, bits):
     L = _lib()
+    SLAB = slab_bytes(bits)
     dev = torch.device("cuda:0")
     w = small_decode_workload(batch=3, lengths=(1, 1, 1), dtype=dtype)
     dt = torch.float16 if dtype == "fp16" else torch.bfloat16
@@ -72,7 +95,7 @@ def test_quantising_append_writes_the_oracles_bytes_and_nothing_else(dtype):
         v_new[0, 1, 5] = 300.0
         cu = np.concatenate([[0], np.cumsum(n_new)]).astype(np.int32)
         seq = torch.tensor([s + n for s, n in zip(start, n_new)], dtype=torch.int32, device=dev)
-        kv = L.PagedKV(k_dev, v_dev, stats, pt_dev, seq, kv_bits=8)
+        kv = L.PagedKV(k_dev, v_dev, stats, pt_dev, seq, kv_bits=bits)
         pad = torch.zeros((1, w.num_kv_heads, 128), dtype=dt)
         L.lserve_append_kv(desc, kv, torch.cat([k_new, pad]).to(dev), torch.cat([v_new, pad]).to(dev),
                            torch.from_numpy(cu).to(dev), torch.tensor(start, dtype=torch.int32, device=dev),
@@ -82,12 +105,12 @@ def test_quantising_append_writes_the_oracles_bytes_and_nothing_else(dtype):
             pos = np.arange(start[b], start[b] + n_new[b])
             phys = page_table[b].numpy()[pos // 64]
             for hk in range(w.num_kv_heads):
-                _write_rows(k_ref, phys, hk, pos % 64, k_new[cu[b]:cu[b + 1], hk])
-                _write_rows(v_ref, phys, hk, pos % 64, v_new[cu[b]:cu[b + 1], hk])
+                _write_rows(k_ref, phys, hk, pos % 64, k_new[cu[b]:cu[b + 1], hk], bits)
+                _write_rows(v_ref, phys, hk, pos % 64, v_new[cu[b]:cu[b + 1], hk], bits)
                 k16[torch.from_numpy(phys).long(), hk, torch.from_numpy(pos % 64).long()] = k_new[cu[b]:cu[b + 1], hk]
         start = [s + n for s, n in zip(start, n_new)]
-        assert torch.equal(k_dev.cpu(), k_ref), (dtype, it)
-        assert torch.equal(v_dev.cpu(), v_ref), (dtype, it)
+        assert torch.equal(k_dev.cpu(), k_ref), (dtype, bits, it)
+        assert torch.equal(v_dev.cpu(), v_ref), (dtype, bits, it)
         seq_np = np.asarray(start, np.int32)
         live = [b for b in range(3) if seq_np[b] > 0]
         ref = oracle.page_stats(k16, page_table[live], seq_np[live], w.logical_page_size)
@@ -111,8 +134,9 @@ QUANT_WORKLOADS = {
 }
 
 
+@pytest.mark.parametrize("bits", [8, 4])
 @pytest.mark.parametrize("name", list(QUANT_WORKLOADS))
-def test_decode_loop_over_quantised_pages_matches_the_oracle(name):
+def test_decode_loop_over_quantised_pages_matches_the_oracle(name, bits):
     """Pages are filled through the quantising write-back (the prompt in one call, then a token per step) into
     pools that start as 0xff bytes (NaN scales in every unused slot); statistics, selection and the decode
     output are compared at every step, the output against the oracle's decode over code * scale + zero."""
@@ -124,11 +148,11 @@ def test_decode_loop_over_quantised_pages_matches_the_oracle(name):
     inp = make_decode_inputs(w)
     dt = inp.k_pool.dtype
     num_pages = inp.k_pool.shape[0]
-    k_q = torch.full((num_pages, w.num_kv_heads, SLAB), 0xff, dtype=torch.uint8)
+    k_q = torch.full((num_pages, w.num_kv_heads, slab_bytes(bits)), 0xff, dtype=torch.uint8)
     v_q = k_q.clone()
     sess = DecodeSession(k_q.to(dev), v_q.to(dev), inp.page_table.to(dev), w.num_q_heads, w.streaming_flags(),
                          w.sink_tokens, w.local_tokens, w.budget_tokens, logical_page_size=w.logical_page_size,
-                         reuse_interval=w.reuse_interval, want_scores=True, want_lse=True, kv_bits=8, dtype=dt)
+                         reuse_interval=w.reuse_interval, want_scores=True, want_lse=True, kv_bits=bits, dtype=dt)
     sess.stats.fill_(float("nan"))
     flags = w.streaming_flags()
     have = [0] * w.batch
@@ -144,15 +168,15 @@ def test_decode_loop_over_quantised_pages_matches_the_oracle(name):
             ks.append(kb)
             vs.append(vb)
             for hk in range(w.num_kv_heads):
-                _write_rows(k_q, phys, hk, pos % 64, kb[:, hk])
-                _write_rows(v_q, phys, hk, pos % 64, vb[:, hk])
+                _write_rows(k_q, phys, hk, pos % 64, kb[:, hk], bits)
+                _write_rows(v_q, phys, hk, pos % 64, vb[:, hk], bits)
         n_new = [a - h for a, h in zip(want, have)]
         cu = np.concatenate([[0], np.cumsum(n_new)]).astype(np.int32)
         sess.append(torch.cat(ks).contiguous().to(dev), torch.cat(vs).contiguous().to(dev), torch.from_numpy(cu).to(dev),
                     torch.tensor(have, dtype=torch.int32, device=dev), max(n_new))
         have = want
-        assert torch.equal(sess.kv.k_pool.cpu(), k_q), (name, step)
-        assert torch.equal(sess.kv.v_pool.cpu(), v_q), (name, step)
+        assert torch.equal(sess.kv.k_pool.cpu(), k_q), (name, bits, step)
+        assert torch.equal(sess.kv.v_pool.cpu(), v_q), (name, bits, step)
         sess.set_seq_lens(seq_cpu.to(dev))
         q = inp.q[step].to(dev)
         stats_ref = oracle.page_stats(inp.k_pool, inp.page_table, seq_cpu, w.logical_page_size)
@@ -163,21 +187,23 @@ def test_decode_loop_over_quantised_pages_matches_the_oracle(name):
             near_ties += compare_selection(sess.sel_pages.cpu().numpy(), sess.sel_count.cpu().numpy(), sel_ref, cnt_ref,
                                            scores_ref, flags)
         out = sess.decode(q)
-        ref, lse_ref = oracle.sparse_decode_values(inp.q[step], _values(k_q), _values(v_q), inp.page_table, seq_cpu,
+        ref, lse_ref = oracle.sparse_decode_values(inp.q[step], _values(k_q, bits), _values(v_q, bits), inp.page_table, seq_cpu,
                                                    sess.sel_pages.cpu().numpy(), sess.sel_count.cpu().numpy(),
                                                    sess.sel_seq_len.cpu().numpy(), flags, w.sink_tokens, w.local_tokens)
-        assert_attention_close(out, ref, f"{name} step {step}")
-        assert_lse_close(sess.lse, lse_ref, f"{name} step {step}")
+        assert_attention_close(out, ref, f"{name} {bits}-bit step {step}")
+        assert_lse_close(sess.lse, lse_ref, f"{name} {bits}-bit step {step}")
     assert near_ties <= 1
 
 
-def test_two_way_cache_of_quantised_pages_equals_the_one_pool_path_bit_for_bit():
+@pytest.mark.parametrize("bits", [8, 4])
+def test_two_way_cache_of_quantised_pages_equals_the_one_pool_path_bit_for_bit(bits):
     """Streaming heads in a bounded ring of quantised pages, dense heads compacted in the main pool (Sec. 3.2):
     the same bytes land at the other addresses and selection, outputs and log-sum-exp are identical to the
     one-pool quantised path, which the test above holds against the oracle."""
     from paper_2502_14866_amd.session import DecodeSession
 
     L = _lib()
+    SLAB, rb, tail = slab_bytes(bits), 128 * bits // 8, 64 * 128 * bits // 8
     dev = torch.device("cuda:0")
     w = small_decode_workload(batch=3, num_q_heads=8, num_kv_heads=4, streaming_kv_heads=(0, 2),
                               lengths=(700, 64, 1500), decode_steps=6, reuse_interval=2, budget_tokens=256,
@@ -199,7 +225,7 @@ def test_two_way_cache_of_quantised_pages_equals_the_one_pool_path_bit_for_bit()
                              torch.zeros((num_pages, heads, SLAB), dtype=torch.uint8, device=dev), inp.page_table.to(dev),
                              w.num_q_heads, flags, w.sink_tokens, w.local_tokens, w.budget_tokens,
                              logical_page_size=w.logical_page_size, reuse_interval=w.reuse_interval, want_scores=True,
-                             want_lse=True, kv_bits=8, dtype=dt, **kw)
+                             want_lse=True, kv_bits=bits, dtype=dt, **kw)
 
     one = session(w.num_kv_heads)
     two = session(len(dense), k_pool_stream=torch.full((n_ring_pages, len(stream), SLAB), 0xff, dtype=torch.uint8, device=dev),
@@ -241,8 +267,8 @@ def test_two_way_cache_of_quantised_pages_equals_the_one_pool_path_bit_for_bit()
                 src = int(inp.page_table[b, p])
                 dst = int(ring_table[b, p if p < s else s + (p - s) % w_])
                 for pool_r, pool_1 in ((kr, k1), (vr, v1)):
-                    assert torch.equal(pool_r[dst, :, :128 * n_tok], pool_1[src][stream][:, :128 * n_tok]), (step, b, p)
-                    assert torch.equal(pool_r[dst, :, 8192:8192 + 4 * n_tok], pool_1[src][stream][:, 8192:8192 + 4 * n_tok])
+                    assert torch.equal(pool_r[dst, :, :rb * n_tok], pool_1[src][stream][:, :rb * n_tok]), (step, b, p)
+                    assert torch.equal(pool_r[dst, :, tail:tail + 4 * n_tok], pool_1[src][stream][:, tail:tail + 4 * n_tok])
         seq = seq_cpu.to(dev)
         q = inp.q[step].to(dev)
         one.set_seq_lens(seq)
