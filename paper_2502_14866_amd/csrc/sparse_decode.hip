@@ -399,18 +399,29 @@ template <int N, int NP> struct DecodeShared {
 // Loads the n queries of KV head hk into shared memory.  Called by the whole workgroup.
 // For quantised pages the queries are converted to fp16 (exact for every bf16 value of magnitude between
 // 2^-14 and 65504; larger ones saturate) and their channel sums are taken, from the converted values.
+// A workgroup's range starts inside a list that is known from the launch plan alone, so the queries of that
+// list and of the one after it are requested at the very start of the kernel, in parallel with the table
+// look-ups, and are at hand when the first page (or the first page after a list boundary) arrives: the load
+// would otherwise sit exposed between two workgroup barriers.
+struct QueryAhead {
+    int list;      // first list of the range; list + 1 is held too
+    uint4 x[2];    // this thread's 16-byte chunk of the group's queries (threads below N * 16)
+};
+
 template <class T, int N, int NP, int BITS>
-__device__ __forceinline__ void stage_query(DecodeShared<N, NP>& sm, const uint4* q, int b, int H, int hk) {
+__device__ __forceinline__ void stage_query(DecodeShared<N, NP>& sm, const uint4* q, int b, int H, int hk, int list,
+                                            const QueryAhead& ahead) {
+    static_assert(N * 16 <= kDecodeThreads, "one pass");
+    const int i = threadIdx.x;  // chunk i of the group: the 16 chunks of a query are the 16 lanes of a DPP row
+    uint4 x = ahead.x[0];
+    if (list == ahead.list + 1) x = ahead.x[1];
+    if ((list < ahead.list || list > ahead.list + 1) && i < N * 16) x = q[((size_t)b * H + hk * N) * (kHeadDim / 8) + i];
     __syncthreads();  // earlier readers of sm.q are done
     if (BITS == 16) {
-        for (int i = threadIdx.x; i < N * 16; i += kDecodeThreads)
-            sm.q[i] = q[((size_t)b * H + hk * N) * (kHeadDim / 8) + i];
+        if (i < N * 16) sm.q[i] = x;
     } else {
-        static_assert(N * 16 <= kDecodeThreads, "one pass");
-        const int i = threadIdx.x;  // chunk i of the group: the 16 chunks of a query are the 16 lanes of a DPP row
         float part = 0.f;
         if (i < N * 16) {
-            const uint4 x = q[((size_t)b * H + hk * N) * (kHeadDim / 8) + i];
             const uint32_t w[4] = {x.x, x.y, x.z, x.w};
             uint32_t o[4];
 #pragma unroll
@@ -599,7 +610,7 @@ __device__ __forceinline__ void end_piece(WaveState<N>& st, DecodeShared<N, NP>&
             cur_list = list;                                                                                         \
             cur_b = list / lp.Hkv;                                                                                   \
             cur_hk = list % lp.Hkv;                                                                                  \
-            stage_query<T, N, NP, BITS>(sm, q, cur_b, lp.H, cur_hk);                                                 \
+            stage_query<T, N, NP, BITS>(sm, q, cur_b, lp.H, cur_hk, list, q_ahead);                                  \
             st.reset();                                                                                              \
         }                                                                                                            \
         const int L = __builtin_amdgcn_readlane(my_L, (IDX));                                                        \
@@ -647,6 +658,20 @@ __global__ __launch_bounds__(kDecodeThreads) void sparse_decode_kernel(
         kslab = (ring ? kstream : kpool) + o;
         vslab = (ring ? vstream : vpool) + o;
     };
+
+    QueryAhead q_ahead;
+    {
+        const int b0 = lo / plan.per_seq;
+        q_ahead.list = b0 * lp.Hkv + head_of_entry(plan, lp.Hkv, lo % plan.per_seq);
+        const int last = kv.batch * lp.Hkv - 1;
+#pragma unroll
+        for (int u = 0; u < 2; ++u) {
+            const int list = min(q_ahead.list + u, last);
+            q_ahead.x[u] = make_uint4(0, 0, 0, 0);
+            if (threadIdx.x < N * 16)
+                q_ahead.x[u] = q[((size_t)(list / lp.Hkv) * lp.H + (list % lp.Hkv) * N) * (kHeadDim / 8) + threadIdx.x];
+        }
+    }
 
     WaveState<N> st;
     int cur_list = -1, cur_b = 0, cur_hk = 0;
