@@ -659,15 +659,19 @@ __global__ __launch_bounds__(kDecodeThreads) void sparse_decode_kernel(
         vslab = (ring ? vstream : vpool) + o;
     };
 
+    // Only where the eight registers do not cost a resident workgroup (measured: 128-token pages and the
+    // quantised kernels lose more than the early queries gain).
+    constexpr bool kQueriesAhead = BITS == 16 && NP <= 64;
     QueryAhead q_ahead;
-    {
+    q_ahead.list = -4;  // matches no list
+    q_ahead.x[0] = q_ahead.x[1] = make_uint4(0, 0, 0, 0);
+    if constexpr (kQueriesAhead) {
         const int b0 = lo / plan.per_seq;
         q_ahead.list = b0 * lp.Hkv + head_of_entry(plan, lp.Hkv, lo % plan.per_seq);
         const int last = kv.batch * lp.Hkv - 1;
 #pragma unroll
         for (int u = 0; u < 2; ++u) {
             const int list = min(q_ahead.list + u, last);
-            q_ahead.x[u] = make_uint4(0, 0, 0, 0);
             if (threadIdx.x < N * 16)
                 q_ahead.x[u] = q[((size_t)(list / lp.Hkv) * lp.H + (list % lp.Hkv) * N) * (kHeadDim / 8) + threadIdx.x];
         }
