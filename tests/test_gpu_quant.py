@@ -282,3 +282,91 @@ def test_two_way_cache_of_quantised_pages_equals_the_one_pool_path_bit_for_bit(b
         o2 = two.decode(q)
         assert torch.equal(o1.view(torch.int16), o2.view(torch.int16)), step
         assert torch.equal(one.lse, two.lse)
+
+
+@pytest.mark.parametrize("bits", [8, 4])
+def test_cfg2_full_size_quantised_cache_sampled_sequences(bits):
+    """The benchmark's decode shape (16 x 32768 tokens, 32 / 8 heads): every prompt is written through the
+    quantising write-back in one call, the selector runs on the statistics that call left, and decode runs over
+    the quantised pages; three sequences are checked against the oracle (their pages gathered into a small pool:
+    bytes bit for bit against the oracle's quantiser, selection, outputs)."""
+    from paper_2502_14866_amd.session import DecodeSession
+    from workloads import get_config
+
+    from helpers import sub_problem
+
+    L = _lib()
+    dev = torch.device("cuda:0")
+    w = get_config("cfg2")
+    inp = make_decode_inputs(w, device=dev)
+    B, Hkv = w.batch, w.num_kv_heads
+    num_pages = inp.k_pool.shape[0]
+    SLAB = slab_bytes(bits)
+    sess = DecodeSession(torch.zeros((num_pages, Hkv, SLAB), dtype=torch.uint8, device=dev),
+                         torch.zeros((num_pages, Hkv, SLAB), dtype=torch.uint8, device=dev), inp.page_table, w.num_q_heads,
+                         w.streaming_flags(), w.sink_tokens, w.local_tokens, w.budget_tokens,
+                         logical_page_size=w.logical_page_size, reuse_interval=w.reuse_interval, want_scores=True,
+                         kv_bits=bits, dtype=inp.k_pool.dtype)
+    lens = inp.prompt_lens.to(dev).to(torch.int32)
+    pad = (B + 4) // 4 * 4
+    cu = torch.zeros((pad,), dtype=torch.int32, device=dev)
+    cu[1:B + 1] = torch.cumsum(lens, 0)
+    seq = torch.zeros((pad,), dtype=torch.int32, device=dev)
+    seq[:B] = lens
+    ks, vs = [], []
+    for b in range(B):
+        pos = torch.arange(int(inp.prompt_lens[b]), device=dev)
+        phys = inp.page_table[b].long()[pos // 64]
+        ks.append(inp.k_pool[phys, :, pos % 64])
+        vs.append(inp.v_pool[phys, :, pos % 64])
+    sess.set_seq_lens(seq[:B])
+    sess.append(torch.cat(ks).contiguous(), torch.cat(vs).contiguous(), cu, torch.zeros((pad,), dtype=torch.int32, device=dev),
+                int(inp.prompt_lens.max()))
+    del ks, vs
+    q = inp.q[0]
+    sess.select(q)
+    out = sess.decode(q)
+    torch.cuda.synchronize()
+
+    seqs = (0, 7, 15)
+    sub = sub_problem(inp, seqs)  # 16-bit pages of the sampled sequences, renumbered
+    sw = sub.workload
+    seq_cpu = sub.prompt_lens.to(torch.int32)
+    flags = w.streaming_flags()
+    # the same pages of the quantised pools, in the sub-problem's numbering
+    rows = []
+    for b in seqs:
+        n_pages = (int(inp.prompt_lens[b]) + max(1, w.decode_steps) + 63) // 64
+        rows.append(inp.page_table[b, :n_pages].long())
+    idx = torch.cat(rows)
+    k_q, v_q = sess.kv.k_pool[idx].cpu(), sess.kv.v_pool[idx].cpu()
+    # bytes: every token of the three prompts against the oracle's quantiser
+    for i, b in enumerate(seqs):
+        Lb = int(seq_cpu[i])
+        P = -(-Lb // 64)
+        pages = sub.page_table[i, :P].long()
+        for pool16, pool_q in ((sub.k_pool, k_q), (sub.v_pool, v_q)):
+            x = pool16[pages].permute(1, 0, 2, 3).reshape(Hkv, P * 64, 128)[:, :Lb]  # [Hkv, Lb, 128]
+            codes, scale, zero = oracle.quantize_kv(x, bits)
+            got = pool_q[pages].numpy()  # [P, Hkv, SLAB]
+            tail = 64 * 128 * bits // 8
+            got_codes = _unpack_rows(got[..., :tail].reshape(P, Hkv, 64, 128 * bits // 8), bits)
+            got_codes = np.transpose(got_codes, (1, 0, 2, 3)).reshape(Hkv, P * 64, 128)[:, :Lb]
+            assert np.array_equal(got_codes, codes), (bits, b)
+            sz = np.ascontiguousarray(got[..., tail:]).view(np.float16).reshape(P, Hkv, 64, 2)
+            sz = np.transpose(sz, (1, 0, 2, 3)).reshape(Hkv, P * 64, 2)[:, :Lb]
+            assert np.array_equal(sz[..., 0].view(np.uint16), scale.view(np.uint16)), (bits, b)
+            assert np.array_equal(sz[..., 1].view(np.uint16), zero.view(np.uint16)), (bits, b)
+    # selection from the statistics the write-back left
+    stats = oracle.page_stats(sub.k_pool, sub.page_table, seq_cpu, sw.logical_page_size)
+    scores, _ = oracle.page_scores(sub.q[0], stats, sub.page_table, seq_cpu, sw.page_size)
+    sel_ref, cnt_ref, ssl_ref = oracle.select_pages(scores, seq_cpu, sw.page_size, sw.budget_tokens)
+    sel_gpu = sess.sel_pages.cpu().numpy()[list(seqs)]
+    cnt_gpu = sess.sel_count.cpu().numpy()[list(seqs)]
+    ssl_gpu = sess.sel_seq_len.cpu().numpy()[list(seqs)]
+    assert compare_selection(sel_gpu, cnt_gpu, sel_ref, cnt_ref, scores, flags) <= 1
+    assert np.array_equal(ssl_gpu, ssl_ref)
+    # decode over the values the bytes stand for
+    ref, _ = oracle.sparse_decode_values(sub.q[0], _values(k_q, bits), _values(v_q, bits), sub.page_table, seq_cpu,
+                                         sel_gpu, cnt_gpu, ssl_gpu, flags, w.sink_tokens, w.local_tokens)
+    assert_attention_close(out[list(seqs)], ref, f"cfg2 {bits}-bit pages")
