@@ -16,6 +16,10 @@
 // result (the list lies inside the range) or a partial (max, sum, unnormalised output) at slot
 // workgroup + list index, which a small merge kernel combines in slot order.  Reduction orders are
 // fixed, so results are deterministic.
+//
+// Pages may also hold quantised rows (Sec. 3.2: 8- or 4-bit codes with one fp16 scale and zero point per
+// token, stored after the page's rows).  The kernel is the same with the slab loads and the per-page
+// arithmetic swapped (template parameter BITS); see process_quantised_quarter_page.
 #include <cstdlib>
 
 #include "kernels.h"
