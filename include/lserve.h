@@ -159,7 +159,9 @@ int lserve_build_page_stats(const lserve_attn_desc *desc, const lserve_paged_kv 
  * kv->stats to be current for positions below start_pos[b]; a logical page whose first token is new
  * is computed from the new keys alone.  kv->seq_lens must be a valid pointer as in every call but is
  * neither read nor written (the caller bumps the lengths).  kv->stats may be NULL when every KV head is
- * streaming.
+ * streaming.  With kv->kv_bits == 8 or 4 the rows are quantised on the way in (see lserve_paged_kv: one
+ * scale and zero point per token, KV head and pool, written behind the page's rows); the statistics are
+ * those of the 16-bit keys handed in, exactly as for a 16-bit cache.
  *
  *   k_new, v_new   device [total_new][Hkv][D], tokens of all sequences concatenated
  *   cu_new         device [batch + 1], cu_new[0] = 0
@@ -297,6 +299,9 @@ size_t lserve_masked_prefill_workspace_bytes(const lserve_attn_desc *desc, int32
  *                   p >= ceil(sel_seq_len[b] / N_P), i.e. pages created since the selection
  *                   (reusable page selection, Sec. 3.5.3).
  * All n query heads of the group attend the valid tokens (u < L_b) of the listed pages.
+ * Over quantised pages (kv->kv_bits == 8 or 4) the keys and values are the numbers the stored codes stand
+ * for, code * scale + zero; the queries are then taken in fp16 (a bf16 query beyond 65504 in magnitude
+ * saturates).
  *
  *   q            device [batch][H][D]
  *   sel_pages    device [batch][Hkv][sel_stride], sel_count device [batch][Hkv],
