@@ -24,7 +24,8 @@ __device__ __forceinline__ unsigned orderable(float s) {
     return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
 }
 
-template <class T, int N>
+// GMAX: upper bound of the logical pages per physical page (4 or kMaxLogical), sizes the row registers.
+template <class T, int N, int GMAX>
 __global__ __launch_bounds__(kScoreThreads) void page_score_kernel(LayerParams lp, PagedParams kv,
                                                                     const uint4* __restrict__ q,
                                                                     const int* __restrict__ stats_valid_len,
@@ -64,60 +65,82 @@ __global__ __launch_bounds__(kScoreThreads) void page_score_kernel(LayerParams l
     const size_t ph = (size_t)phys * kv.pool_heads + pool_rank(lp, kv, hk, false);  // (page, head) index inside the main pool
     uint4* st = reinterpret_cast<uint4*>(kv.stats) + ph * lp.g * 2 * (kHeadDim / 8);
     const int fresh_below = stats_valid_len ? stats_valid_len[b] : L;  // stored statistics cover tokens below this
-    float best = -INFINITY;
-    for (int j = 0; j < lp.g; ++j) {
-        const int lo = p * lp.NP + j * lp.NL;
-        if (lo >= L) break;  // logical pages without a valid token
-        uint4 mx, mn;
-        if (min(lo + lp.NL, L) > fresh_below) {
-            // tokens arrived since the statistics were last brought up to date: rebuild this logical
-            // page's rows from its keys (lane c owns channels 8c .. 8c+7), use them and store them
-            const uint4* keys = reinterpret_cast<const uint4*>(kv.k_pool) +
-                                (ph * lp.NP + (lo - p * lp.NP)) * (kHeadDim / 8) + c;
-            float vmax[8], vmin[8];
+    // Rows of every logical page with a valid token.  All stored rows are requested before any is used, so a
+    // wavefront has its whole 2 KiB per pair in flight at once: with one logical page at a time the loads in
+    // flight per compute unit capped the scan near half the memory bandwidth.  Logical pages that received
+    // tokens since the statistics were last brought up to date (at most the tail of the sequence) are rebuilt
+    // from their keys afterwards (lane c owns channels 8c .. 8c+7), used and stored.
+    const int n_log = min(lp.g, ceil_div(L - p * lp.NP, lp.NL));
+    uint4 mx[GMAX], mn[GMAX];
+    bool any_stale = false;
 #pragma unroll
-            for (int i = 0; i < 8; ++i) {
-                vmax[i] = -INFINITY;
-                vmin[i] = INFINITY;
+    for (int j = 0; j < GMAX; ++j) {
+        if (j < n_log) {
+            const int lo = p * lp.NP + j * lp.NL;
+            if (min(lo + lp.NL, L) > fresh_below) {
+                any_stale = true;
+            } else {
+                mx[j] = st[(size_t)(j * 2) * (kHeadDim / 8) + c];
+                mn[j] = st[(size_t)(j * 2 + 1) * (kHeadDim / 8) + c];
             }
-            const int cnt = min(lp.NL, L - lo);
-            for (int t0 = 0; t0 < cnt; t0 += 8) {  // eight rows requested together
-                uint4 x[8];
+        }
+    }
+    if (any_stale) {
 #pragma unroll
-                for (int u = 0; u < 8; ++u) x[u] = keys[(size_t)min(t0 + u, cnt - 1) * (kHeadDim / 8)];  // a repeated row changes nothing
+        for (int j = 0; j < GMAX; ++j) {
+            const int lo = p * lp.NP + j * lp.NL;
+            if (j < n_log && min(lo + lp.NL, L) > fresh_below) {
+                const uint4* keys = reinterpret_cast<const uint4*>(kv.k_pool) +
+                                    (ph * lp.NP + (lo - p * lp.NP)) * (kHeadDim / 8) + c;
+                float vmax[8], vmin[8];
 #pragma unroll
-                for (int u = 0; u < 8; ++u) {
-                    const uint32_t w[4] = {x[u].x, x[u].y, x[u].z, x[u].w};
+                for (int i = 0; i < 8; ++i) {
+                    vmax[i] = -INFINITY;
+                    vmin[i] = INFINITY;
+                }
+                const int cnt = min(lp.NL, L - lo);
+                for (int t0 = 0; t0 < cnt; t0 += 8) {  // eight rows requested together
+                    uint4 x[8];
 #pragma unroll
-                    for (int i = 0; i < 4; ++i) {
-                        const float a = Elem<T>::lo(w[i]), d = Elem<T>::hi(w[i]);
-                        vmax[2 * i] = fmaxf(vmax[2 * i], a);
-                        vmin[2 * i] = fminf(vmin[2 * i], a);
-                        vmax[2 * i + 1] = fmaxf(vmax[2 * i + 1], d);
-                        vmin[2 * i + 1] = fminf(vmin[2 * i + 1], d);
+                    for (int u = 0; u < 8; ++u)
+                        x[u] = keys[(size_t)min(t0 + u, cnt - 1) * (kHeadDim / 8)];  // a repeated row changes nothing
+#pragma unroll
+                    for (int u = 0; u < 8; ++u) {
+                        const uint32_t w[4] = {x[u].x, x[u].y, x[u].z, x[u].w};
+#pragma unroll
+                        for (int i = 0; i < 4; ++i) {
+                            const float a = Elem<T>::lo(w[i]), d = Elem<T>::hi(w[i]);
+                            vmax[2 * i] = fmaxf(vmax[2 * i], a);
+                            vmin[2 * i] = fminf(vmin[2 * i], a);
+                            vmax[2 * i + 1] = fmaxf(vmax[2 * i + 1], d);
+                            vmin[2 * i + 1] = fminf(vmin[2 * i + 1], d);
+                        }
                     }
                 }
+                mx[j] = make_uint4(Elem<T>::pack(vmax[0], vmax[1]), Elem<T>::pack(vmax[2], vmax[3]),
+                                   Elem<T>::pack(vmax[4], vmax[5]), Elem<T>::pack(vmax[6], vmax[7]));
+                mn[j] = make_uint4(Elem<T>::pack(vmin[0], vmin[1]), Elem<T>::pack(vmin[2], vmin[3]),
+                                   Elem<T>::pack(vmin[4], vmin[5]), Elem<T>::pack(vmin[6], vmin[7]));
+                st[(size_t)(j * 2) * (kHeadDim / 8) + c] = mx[j];
+                st[(size_t)(j * 2 + 1) * (kHeadDim / 8) + c] = mn[j];
             }
-            mx = make_uint4(Elem<T>::pack(vmax[0], vmax[1]), Elem<T>::pack(vmax[2], vmax[3]),
-                            Elem<T>::pack(vmax[4], vmax[5]), Elem<T>::pack(vmax[6], vmax[7]));
-            mn = make_uint4(Elem<T>::pack(vmin[0], vmin[1]), Elem<T>::pack(vmin[2], vmin[3]),
-                            Elem<T>::pack(vmin[4], vmin[5]), Elem<T>::pack(vmin[6], vmin[7]));
-            st[(size_t)(j * 2) * (kHeadDim / 8) + c] = mx;
-            st[(size_t)(j * 2 + 1) * (kHeadDim / 8) + c] = mn;
-        } else {
-            mx = st[(size_t)(j * 2) * (kHeadDim / 8) + c];
-            mn = st[(size_t)(j * 2 + 1) * (kHeadDim / 8) + c];
         }
-        const uint32_t wx[4] = {mx.x, mx.y, mx.z, mx.w};
-        const uint32_t wn[4] = {mn.x, mn.y, mn.z, mn.w};
+    }
+    float best = -INFINITY;
 #pragma unroll
-        for (int hh = 0; hh < N; ++hh) {
-            float s = 0.f;
+    for (int j = 0; j < GMAX; ++j) {
+        if (j < n_log) {
+            const uint32_t wx[4] = {mx[j].x, mx[j].y, mx[j].z, mx[j].w};
+            const uint32_t wn[4] = {mn[j].x, mn[j].y, mn[j].z, mn[j].w};
 #pragma unroll
-            for (int i = 0; i < 4; ++i) s = Elem<T>::dot2(qpos[hh][i], wx[i], s);
+            for (int hh = 0; hh < N; ++hh) {
+                float s = 0.f;
 #pragma unroll
-            for (int i = 0; i < 4; ++i) s = Elem<T>::dot2(qneg[hh][i], wn[i], s);
-            best = fmaxf(best, row16_sum(s));
+                for (int i = 0; i < 4; ++i) s = Elem<T>::dot2(qpos[hh][i], wx[i], s);
+#pragma unroll
+                for (int i = 0; i < 4; ++i) s = Elem<T>::dot2(qneg[hh][i], wn[i], s);
+                best = fmaxf(best, row16_sum(s));
+            }
         }
     }
     if (c == 0) *dst = best + 0.f;  // +0 canonicalises a negative zero
@@ -288,8 +311,12 @@ hipError_t launch_score(const LayerParams& lp, const PagedParams& kv, const void
     const uint4* q4 = reinterpret_cast<const uint4*>(q);
 #define LSERVE_SCORE_CASE(N)                                                                                   \
     case N:                                                                                                    \
-        hipLaunchKernelGGL((page_score_kernel<T, N>), grid, block, 0, stream, lp, kv, q4, stats_valid_len, scores, \
-                           selecting);                                                                     \
+        if (lp.g <= 4)                                                                                         \
+            hipLaunchKernelGGL((page_score_kernel<T, N, 4>), grid, block, 0, stream, lp, kv, q4, stats_valid_len,  \
+                               scores, selecting);                                                             \
+        else                                                                                                   \
+            hipLaunchKernelGGL((page_score_kernel<T, N, kMaxLogical>), grid, block, 0, stream, lp, kv, q4,         \
+                               stats_valid_len, scores, selecting);                                            \
         break;
     switch (lp.group) {
         LSERVE_SCORE_CASE(1)
