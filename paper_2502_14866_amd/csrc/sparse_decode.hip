@@ -778,6 +778,10 @@ __global__ __launch_bounds__(kDecodeThreads) void sparse_decode_kernel(
         const int idx = __builtin_ctzll(todo);                                                                           \
         todo &= todo - 1;                                                                                                \
         if (ahead) LSERVE_REQUEST(FILL)                                                                                  \
+        if ((__builtin_popcountll(todo) + (blk >= (int)gridDim.x / 2)) & 1)                                              \
+            __builtin_amdgcn_s_setprio(1);                                                                               \
+        else                                                                                                             \
+            __builtin_amdgcn_s_setprio(0);                                                                               \
         LSERVE_DECODE_VISIT(idx, CUR)                                                                                    \
         if (!todo) break;                                                                                                \
     }
