@@ -20,6 +20,7 @@
 // Pages may also hold quantised rows (Sec. 3.2: 8- or 4-bit codes with one fp16 scale and zero point per
 // token, stored after the page's rows).  The kernel is the same with the slab loads and the per-page
 // arithmetic swapped (template parameter BITS); see process_quantised_quarter_page.
+#include <algorithm>
 #include <cstdlib>
 
 #include "kernels.h"
@@ -544,15 +545,14 @@ __device__ __forceinline__ int head_of_entry(const DecodePlan& plan, int Hkv, in
     return hk;
 }
 
-// Folds the pieces of one list, in slot order, eight at a time so that their loads are in flight
-// together.  Every range between j0 and j1 wrote a piece (ranges there are never empty: an empty
+// Folds the pieces of one list, in slot order, kBatch at a time so that their loads are in flight
+// together (8, or 32 when the lists of a launch are cut into more pieces than that).  Every range between j0 and j1 wrote a piece (ranges there are never empty: an empty
 // range implies quot = 0, and then no list spans two ranges); a range that held only nominal
 // entries past the list's real length wrote a neutral piece (max = -inf), whose output is skipped.
-template <class T, int N>
+template <class T, int N, int kBatch>
 __device__ __forceinline__ void fold_pieces(int list, int j0, int j1, int hh, int ch, int H, int b, int hk,
                                             uint16_t* out, float* lse_out, const float* part_o,
                                             const float* part_ml) {
-    constexpr int kBatch = 8;
     float M = -INFINITY, lt = 0.f, acc = 0.f;
     for (int jb = j0; jb <= j1; jb += kBatch) {
         float pm[kBatch], pl[kBatch], po[kBatch];
@@ -804,7 +804,7 @@ __global__ __launch_bounds__(kDecodeThreads) void sparse_decode_kernel(
 #undef LSERVE_DECODE_VISIT
 
 // Combines the pieces of every list that was cut by a range boundary, in slot order.
-template <class T, int N>
+template <class T, int N, int kBatch>
 __global__ __launch_bounds__(N* kHeadDim) void decode_merge_kernel(
     LayerParams lp, DecodePlan plan, uint16_t* __restrict__ out, float* __restrict__ lse_out,
     const float* __restrict__ part_o, const float* __restrict__ part_ml) {
@@ -813,8 +813,8 @@ __global__ __launch_bounds__(N* kHeadDim) void decode_merge_kernel(
     // workgroups whose ranges hold the first and the last nominal entry of the list
     const int j0 = range_of(plan, n0), j1 = range_of(plan, n1 - 1);
     if (j0 == j1) return;  // the list lay inside one range: the decode kernel wrote the final rows
-    fold_pieces<T, N>(list, j0, j1, threadIdx.x / kHeadDim, threadIdx.x % kHeadDim, lp.H, b, hk, out, lse_out, part_o,
-                      part_ml);
+    fold_pieces<T, N, kBatch>(list, j0, j1, threadIdx.x / kHeadDim, threadIdx.x % kHeadDim, lp.H, b, hk, out, lse_out,
+                              part_o, part_ml);
 }
 
 // ---- host side -----------------------------------------------------------------------------------
@@ -872,8 +872,16 @@ hipError_t launch_decode_kernels(const LayerParams& lp, const PagedParams& kv, c
                        sel_pages, sel_count, sel_seq_len, sel_stride, o16, lse_out, part_o, part_ml);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
-    hipLaunchKernelGGL((decode_merge_kernel<T, N>), dim3(lp.Hkv, kv.batch), dim3(N * kHeadDim), 0, stream, lp, plan, o16,
-                       lse_out, part_o, part_ml);
+    // pieces of the longest list: with few sequences a list is cut into dozens of short ranges
+    int longest = 0;
+    for (int hk = 0; hk < lp.Hkv; ++hk) longest = std::max(longest, (int)plan.first[hk + 1] - (int)plan.first[hk]);
+    const int pieces = plan.quot > 0 ? longest / plan.quot + 2 : 1;
+    if (pieces > 16)
+        hipLaunchKernelGGL((decode_merge_kernel<T, N, 32>), dim3(lp.Hkv, kv.batch), dim3(N * kHeadDim), 0, stream, lp,
+                           plan, o16, lse_out, part_o, part_ml);
+    else
+        hipLaunchKernelGGL((decode_merge_kernel<T, N, 8>), dim3(lp.Hkv, kv.batch), dim3(N * kHeadDim), 0, stream, lp,
+                           plan, o16, lse_out, part_o, part_ml);
     return hipGetLastError();
 }
 
