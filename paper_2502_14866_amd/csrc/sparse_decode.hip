@@ -866,8 +866,15 @@ hipError_t launch_decode_kernels(const LayerParams& lp, const PagedParams& kv, c
             if (v >= 1 && v <= nb && v <= kMaxBlocksPerCU) per_cu = v;
         }
     }
-    const int G = num_compute_units() * per_cu;
-    const DecodePlan plan = make_plan(lp, kv.batch, sel_stride, G);
+    // two workgroups per compute unit, unless that leaves fewer than four entries each: a small launch is all
+    // start-up, fold and merge, and half as many workgroups with twice the pages do less of each (measured)
+    int G = num_compute_units() * per_cu;
+    DecodePlan plan = make_plan(lp, kv.batch, sel_stride, G);
+    static const bool fixed_per_cu = getenv("LSERVE_DECODE_BLOCKS_PER_CU") != nullptr;
+    if (per_cu > 1 && plan.quot < 4 && !fixed_per_cu) {
+        G = num_compute_units();
+        plan = make_plan(lp, kv.batch, sel_stride, G);
+    }
     hipLaunchKernelGGL((sparse_decode_kernel<T, N, NP, BITS>), dim3(G), dim3(kDecodeThreads), 0, stream, lp, kv, plan, q4,
                        sel_pages, sel_count, sel_seq_len, sel_stride, o16, lse_out, part_o, part_ml);
     hipError_t e = hipGetLastError();
