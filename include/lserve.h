@@ -15,8 +15,15 @@
  *
  * Conventions common to every call
  *   - "device" pointers are HIP device memory owned by the caller; "host" pointers are ordinary
- *     host memory.  The library allocates nothing, frees nothing and keeps no state between calls.
+ *     host memory.  The library allocates nothing, frees nothing and keeps no state that a result
+ *     depends on.  What it does keep, per process, are properties of the GPU read on first use (the
+ *     number of compute units of the device that is current at the first call, and for each decode
+ *     kernel variant how many of its workgroups fit a compute unit); they fix the work split, so all
+ *     calls of a process must run on GPUs of one kind.  No environment variable is read.
  *     Buffers are borrowed until the work enqueued by the call has completed on `stream`.
+ *   - The first call that launches a kernel loads the library's code objects onto the device, which is
+ *     not allowed while `stream` is being captured into a HIP graph: call lserve_init() (or run each
+ *     entry point once eagerly) before capturing.  After that every call may be captured.
  *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Calls validate their
  *     arguments on the host, enqueue kernels and return; they never synchronise.
  *   - Return value: LSERVE_OK (0) or a negative LSERVE_ERR_* code.  Nothing is printed, nothing
@@ -45,7 +52,7 @@ extern "C" {
 
 #define LSERVE_OK 0
 #define LSERVE_ERR_INVALID_ARG (-1) /* null / misaligned pointer, non-positive size, bad page sizes, budget < N_P */
-#define LSERVE_ERR_UNSUPPORTED (-2) /* head_dim != 128, unknown dtype, H % Hkv != 0, Hkv > 64, n > 8, g > 8 */
+#define LSERVE_ERR_UNSUPPORTED (-2) /* head_dim != 128, unknown dtype, H % Hkv != 0, Hkv > 64, n > 8, g > 8, batch > 65535 */
 #define LSERVE_ERR_WORKSPACE (-3)   /* workspace missing or smaller than lserve_workspace_bytes() */
 #define LSERVE_ERR_HIP (-4)         /* a HIP call failed; see lserve_last_hip_error() */
 
@@ -309,6 +316,8 @@ size_t lserve_masked_prefill_workspace_bytes(const lserve_attn_desc *desc, int32
  *   out          device [batch][H][D]
  *   lse_out      device [batch][H] fp32 or NULL
  *   workspace    device, >= lserve_workspace_bytes(LSERVE_CALL_SPARSE_DECODE, ...)
+ * LSERVE_ERR_UNSUPPORTED when batch * (index-table entries per sequence) exceeds 2^31 - 1, an entry count
+ * being s + w per streaming head and sel_stride + 1 per selecting head.
  */
 int lserve_sparse_decode(const lserve_attn_desc *desc, const lserve_paged_kv *kv, const void *q,
                          const int32_t *sel_pages, const int32_t *sel_count,
@@ -325,6 +334,13 @@ int lserve_sparse_decode(const lserve_attn_desc *desc, const lserve_paged_kv *kv
 size_t lserve_workspace_bytes(int which_call, const lserve_attn_desc *desc, int32_t batch,
                               int32_t max_pages_per_seq, int32_t sel_stride_or_budget_pages,
                               int32_t total_tokens);
+
+/*
+ * Optional set-up for the device that is current on the calling thread: loads the library's code objects
+ * onto it, so that later calls do no loading and may run under stream capture.  Safe to call more than once and
+ * from several threads; launches nothing.  Returns LSERVE_OK or LSERVE_ERR_HIP.
+ */
+int lserve_init(void);
 
 /* Human-readable text for a return code (static storage). */
 const char *lserve_strerror(int code);

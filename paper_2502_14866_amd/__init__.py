@@ -22,6 +22,7 @@ from .binding import (  # noqa: F401
     lserve_paged_prefill_workspace_bytes,
     lserve_sparse_prefill_paged,
     lserve_build_page_stats,
+    lserve_init,
     lserve_last_hip_error,
     lserve_select_pages,
     lserve_sparse_decode,

@@ -32,6 +32,7 @@ EXPORTED_SYMBOLS = (
     "lserve_workspace_bytes",
     "lserve_strerror",
     "lserve_last_hip_error",
+    "lserve_init",
 )
 
 
@@ -105,6 +106,8 @@ def load_library():
         lib.lserve_strerror.argtypes = [ctypes.c_int]
         lib.lserve_strerror.restype = ctypes.c_char_p
         lib.lserve_last_hip_error.restype = ctypes.c_int
+        lib.lserve_init.argtypes = []
+        lib.lserve_init.restype = ctypes.c_int
         for name in ("lserve_build_page_stats", "lserve_select_pages", "lserve_sparse_prefill",
                      "lserve_sparse_decode"):
             getattr(lib, name).restype = ctypes.c_int
@@ -193,6 +196,10 @@ def lserve_strerror(code: int) -> str:
 
 def lserve_last_hip_error() -> int:
     return int(load_library().lserve_last_hip_error())
+
+
+def lserve_init() -> None:
+    _check(load_library().lserve_init(), "lserve_init")
 
 
 def lserve_workspace_bytes(which_call: int, desc: AttnDesc, batch: int = 0, max_pages_per_seq: int = 0,

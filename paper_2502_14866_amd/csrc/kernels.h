@@ -30,6 +30,16 @@ hipError_t launch_sparse_prefill_paged(int dtype, const LayerParams& lp, const P
 
 size_t decode_workspace_bytes(const LayerParams& lp, int batch, int sel_stride);
 
+// Nominal index-table entries per sequence of a decode launch: s + w per streaming head, sel_stride + 1 per
+// selecting head.  The launch plan indexes batch * this many entries with 32-bit integers.
+long long decode_nominal_entries(const LayerParams& lp, int sel_stride);
+
+// Each forces the code object of its translation unit onto the current device (HIP loads them on first use).
+hipError_t preload_decode_kernels();
+hipError_t preload_select_kernels();
+hipError_t preload_stats_kernels();
+hipError_t preload_prefill_kernels();
+
 hipError_t launch_sparse_decode(int dtype, const LayerParams& lp, const PagedParams& kv, const void* q,
                                 const int* sel_pages, const int* sel_count, const int* sel_seq_len,
                                 int sel_stride, void* out, float* lse_out, void* workspace, hipStream_t stream);

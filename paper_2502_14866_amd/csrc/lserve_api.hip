@@ -146,7 +146,7 @@ int lserve_select_pages(const lserve_attn_desc* desc, const lserve_paged_kv* kv,
     PagedParams pp;
     int rc = make_layer(desc, &lp);
     if (rc) return rc;
-    rc = make_paged(kv, lp, stats_valid_len != nullptr, false, true, false, &pp);
+    rc = make_paged(kv, lp, stats_valid_len != nullptr, false, selecting_heads(lp).count > 0, false, &pp);
     if (rc) return rc;
     if (stats_valid_len && pp.kv_bits != 16) return LSERVE_ERR_UNSUPPORTED;  // no 16-bit keys to rebuild from
     if (!q || !sel_pages || !sel_count || !sel_seq_len) return LSERVE_ERR_INVALID_ARG;
@@ -257,23 +257,37 @@ size_t lserve_masked_prefill_workspace_bytes(const lserve_attn_desc* desc, int32
     return masked_prefill_workspace_bytes(lp, total_tokens, batch, max_seqlen, num_masks, nnz);
 }
 
+namespace {
+// Everything lserve_sparse_decode checks except the workspace.
+int check_decode_args(const lserve_attn_desc* desc, const lserve_paged_kv* kv, const void* q, const int32_t* sel_pages,
+                      const int32_t* sel_count, const int32_t* sel_seq_len, int32_t sel_stride, const void* out,
+                      const float* lse_out, LayerParams* lp, PagedParams* pp) {
+    int rc = make_layer(desc, lp);
+    if (rc) return rc;
+    rc = make_paged(kv, *lp, true, true, false, true, pp);
+    if (rc) return rc;
+    if (!q || !out) return LSERVE_ERR_INVALID_ARG;
+    const bool any_selecting = selecting_heads(*lp).count > 0;
+    if (any_selecting && (!sel_pages || !sel_count || !sel_seq_len || sel_stride <= 0)) return LSERVE_ERR_INVALID_ARG;
+    if (sel_stride < 0) return LSERVE_ERR_INVALID_ARG;
+    if (!aligned16(q) || !aligned16(out) || !aligned16(sel_pages) || !aligned16(sel_count) || !aligned16(sel_seq_len) ||
+        !aligned16(lse_out))
+        return LSERVE_ERR_INVALID_ARG;
+    // the launch plan numbers the nominal index-table entries of the whole batch with 32-bit integers
+    if ((long long)pp->batch * decode_nominal_entries(*lp, sel_stride) > 0x7fffffffLL) return LSERVE_ERR_UNSUPPORTED;
+    return LSERVE_OK;
+}
+}  // namespace
+
 int lserve_sparse_decode(const lserve_attn_desc* desc, const lserve_paged_kv* kv, const void* q,
                          const int32_t* sel_pages, const int32_t* sel_count, const int32_t* sel_seq_len,
                          int32_t sel_stride, void* out, float* lse_out, void* workspace, size_t workspace_bytes,
                          void* stream) {
     LayerParams lp;
     PagedParams pp;
-    int rc = make_layer(desc, &lp);
+    int rc = check_decode_args(desc, kv, q, sel_pages, sel_count, sel_seq_len, sel_stride, out, lse_out, &lp, &pp);
     if (rc) return rc;
-    rc = make_paged(kv, lp, true, true, false, true, &pp);
-    if (rc) return rc;
-    if (!q || !out) return LSERVE_ERR_INVALID_ARG;
-    const bool any_selecting = selecting_heads(lp).count > 0;
-    if (any_selecting && (!sel_pages || !sel_count || !sel_seq_len || sel_stride <= 0)) return LSERVE_ERR_INVALID_ARG;
-    if (sel_stride < 0) return LSERVE_ERR_INVALID_ARG;
-    if (!aligned16(q) || !aligned16(out) || !aligned16(sel_pages) || !aligned16(sel_count) || !aligned16(sel_seq_len) ||
-        !aligned16(lse_out) || !aligned16(workspace))
-        return LSERVE_ERR_INVALID_ARG;
+    if (!aligned16(workspace)) return LSERVE_ERR_INVALID_ARG;
     if (!workspace || workspace_bytes < decode_workspace_bytes(lp, pp.batch, sel_stride)) return LSERVE_ERR_WORKSPACE;
     hipError_t e = launch_sparse_decode(desc->dtype, lp, pp, q, sel_pages, sel_count, sel_seq_len, sel_stride, out,
                                         lse_out, workspace, (hipStream_t)stream);
@@ -296,6 +310,14 @@ size_t lserve_workspace_bytes(int which_call, const lserve_attn_desc* desc, int3
         default:
             return 0;
     }
+}
+
+int lserve_init(void) {
+    hipError_t e = preload_stats_kernels();
+    if (e == hipSuccess) e = preload_select_kernels();
+    if (e == hipSuccess) e = preload_prefill_kernels();
+    if (e == hipSuccess) e = preload_decode_kernels();
+    return e == hipSuccess ? LSERVE_OK : fail_hip(e);
 }
 
 const char* lserve_strerror(int code) {

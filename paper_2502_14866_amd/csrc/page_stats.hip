@@ -246,6 +246,11 @@ hipError_t launch_append_kv(int dtype, const LayerParams& lp, const PagedParams&
     return hipGetLastError();
 }
 
+hipError_t preload_stats_kernels() {
+    hipFuncAttributes attr;
+    return hipFuncGetAttributes(&attr, reinterpret_cast<const void*>(&page_stats_kernel<F16>));
+}
+
 hipError_t launch_page_stats(int dtype, const LayerParams& lp, const PagedParams& kv, const int* start_pos,
                              int tail_pages, const HeadList& heads, hipStream_t stream) {
     if (heads.count == 0) return hipSuccess;

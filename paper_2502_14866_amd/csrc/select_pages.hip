@@ -336,6 +336,11 @@ hipError_t launch_score(const LayerParams& lp, const PagedParams& kv, const void
 
 }  // namespace
 
+hipError_t preload_select_kernels() {
+    hipFuncAttributes attr;
+    return hipFuncGetAttributes(&attr, reinterpret_cast<const void*>(&topk_pages_kernel));
+}
+
 hipError_t launch_select_pages(int dtype, const LayerParams& lp, const PagedParams& kv, const void* q,
                                const int* stats_valid_len, int budget_pages, int* sel_pages, int* sel_count, int* sel_seq_len,
                                float* scores, bool scores_is_user_buffer, const HeadList& selecting,

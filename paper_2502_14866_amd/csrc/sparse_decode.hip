@@ -21,7 +21,6 @@
 // token, stored after the page's rows).  The kernel is the same with the slab loads and the per-page
 // arithmetic swapped (template parameter BITS); see process_quantised_quarter_page.
 #include <algorithm>
-#include <cstdlib>
 
 #include "kernels.h"
 
@@ -525,7 +524,7 @@ struct DecodePlan {
     int per_seq;               // nominal entries per sequence
     int total;                 // batch * per_seq
     int quot, rem;             // total = G * quot + rem: the first `rem` ranges hold quot + 1 entries
-    unsigned short first[65];  // first nominal entry of KV head hk inside a sequence; first[Hkv] = per_seq
+    int first[65];             // first nominal entry of KV head hk inside a sequence; first[Hkv] = per_seq
 };
 
 // Range of workgroup j is [range_begin(j), range_begin(j + 1)); no division on the device.
@@ -541,7 +540,7 @@ __device__ __forceinline__ int range_of(const DecodePlan& plan, int x) {
 // independent scalar loads instead of a chain of dependent ones.
 __device__ __forceinline__ int head_of_entry(const DecodePlan& plan, int Hkv, int y) {
     int hk = 0;
-    for (int h = 1; h < Hkv; ++h) hk += y >= (int)plan.first[h];
+    for (int h = 1; h < Hkv; ++h) hk += y >= plan.first[h];
     return hk;
 }
 
@@ -833,11 +832,11 @@ DecodePlan make_plan(const LayerParams& lp, int batch, int sel_stride, int G) {
     DecodePlan plan;
     int acc = 0;
     for (int hk = 0; hk < lp.Hkv; ++hk) {
-        plan.first[hk] = (unsigned short)acc;
+        plan.first[hk] = acc;
         const bool streaming = (lp.streaming_mask >> hk) & 1ull;
         acc += streaming ? lp.sink_pages + lp.local_pages : sel_stride + 1;
     }
-    for (int hk = lp.Hkv; hk <= 64; ++hk) plan.first[hk] = (unsigned short)acc;
+    for (int hk = lp.Hkv; hk <= 64; ++hk) plan.first[hk] = acc;
     plan.per_seq = acc;
     plan.total = batch * acc;
     plan.quot = plan.total / G;
@@ -855,23 +854,22 @@ hipError_t launch_decode_kernels(const LayerParams& lp, const PagedParams& kv, c
                                  float* lse_out, float* part_o, float* part_ml, hipStream_t stream) {
     const uint4* q4 = reinterpret_cast<const uint4*>(q);
     uint16_t* o16 = reinterpret_cast<uint16_t*>(out);
-    static int per_cu = 0;  // resident workgroups per compute unit of this instantiation
-    if (per_cu == 0) {
+    // Resident workgroups per compute unit of this instantiation: a property of the binary and the device, asked
+    // once (thread-safe initialisation of a function-local static); a failed query counts as one.
+    static const int per_cu = [] {
         int nb = 0;
-        hipError_t e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&nb, sparse_decode_kernel<T, N, NP, BITS>, kDecodeThreads, 0);
-        if (e != hipSuccess) return e;
-        per_cu = nb < 1 ? 1 : (nb > kBlocksPerCU ? kBlocksPerCU : nb);
-        if (const char* e = getenv("LSERVE_DECODE_BLOCKS_PER_CU")) {  // tuning override
-            const int v = atoi(e);
-            if (v >= 1 && v <= nb && v <= kMaxBlocksPerCU) per_cu = v;
+        if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&nb, sparse_decode_kernel<T, N, NP, BITS>, kDecodeThreads, 0) !=
+            hipSuccess) {
+            (void)hipGetLastError();
+            return 1;
         }
-    }
+        return nb < 1 ? 1 : (nb > kBlocksPerCU ? kBlocksPerCU : nb);
+    }();
     // two workgroups per compute unit, unless that leaves fewer than four entries each: a small launch is all
     // start-up, fold and merge, and half as many workgroups with twice the pages do less of each (measured)
     int G = num_compute_units() * per_cu;
     DecodePlan plan = make_plan(lp, kv.batch, sel_stride, G);
-    static const bool fixed_per_cu = getenv("LSERVE_DECODE_BLOCKS_PER_CU") != nullptr;
-    if (per_cu > 1 && plan.quot < 4 && !fixed_per_cu) {
+    if (per_cu > 1 && plan.quot < 4) {
         G = num_compute_units();
         plan = make_plan(lp, kv.batch, sel_stride, G);
     }
@@ -881,7 +879,7 @@ hipError_t launch_decode_kernels(const LayerParams& lp, const PagedParams& kv, c
     if (e != hipSuccess) return e;
     // pieces of the longest list: with few sequences a list is cut into dozens of short ranges
     int longest = 0;
-    for (int hk = 0; hk < lp.Hkv; ++hk) longest = std::max(longest, (int)plan.first[hk + 1] - (int)plan.first[hk]);
+    for (int hk = 0; hk < lp.Hkv; ++hk) longest = std::max(longest, plan.first[hk + 1] - plan.first[hk]);
     const int pieces = plan.quot > 0 ? longest / plan.quot + 2 : 1;
     if (pieces > 16)
         hipLaunchKernelGGL((decode_merge_kernel<T, N, 32>), dim3(lp.Hkv, kv.batch), dim3(N * kHeadDim), 0, stream, lp,
@@ -944,9 +942,21 @@ hipError_t launch_decode(const LayerParams& lp, const PagedParams& kv, const voi
 
 }  // namespace
 
+long long decode_nominal_entries(const LayerParams& lp, int sel_stride) {
+    long long acc = 0;
+    for (int hk = 0; hk < lp.Hkv; ++hk)
+        acc += ((lp.streaming_mask >> hk) & 1ull) ? (long long)lp.sink_pages + lp.local_pages : (long long)sel_stride + 1;
+    return acc;
+}
+
 size_t decode_workspace_bytes(const LayerParams& lp, int batch, int sel_stride) {
     (void)sel_stride;
     return partial_slots(lp, batch) * lp.group * (kHeadDim + 2) * sizeof(float);
+}
+
+hipError_t preload_decode_kernels() {
+    hipFuncAttributes attr;
+    return hipFuncGetAttributes(&attr, reinterpret_cast<const void*>(&sparse_decode_kernel<F16, 1, 64, 16>));
 }
 
 hipError_t launch_sparse_decode(int dtype, const LayerParams& lp, const PagedParams& kv, const void* q,

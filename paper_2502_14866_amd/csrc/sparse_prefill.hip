@@ -647,6 +647,11 @@ hipError_t launch_prefill_paged(const LayerParams& lp, const PagedParams& kv, co
 
 }  // namespace
 
+hipError_t preload_prefill_kernels() {
+    hipFuncAttributes attr;
+    return hipFuncGetAttributes(&attr, reinterpret_cast<const void*>(&merge_mask_rows_kernel));
+}
+
 size_t paged_prefill_workspace_bytes(const LayerParams& lp, int batch, int max_pages) {
     return (size_t)lp.Hkv * batch * max_pages * kHeadDim * kTile * sizeof(uint16_t);
 }

@@ -27,21 +27,27 @@ def assert_attention_close(got: torch.Tensor, ref: np.ndarray, what: str = ""):
     max_rel = rel.max() if rel.size else 0.0
     assert max_abs <= ABS_TOL[got.dtype], f"{what}: max abs error {max_abs:.3e} > {ABS_TOL[got.dtype]}"
     assert max_rel <= ROW_REL_TOL, f"{what}: max row-relative error {max_rel:.3e} > {ROW_REL_TOL}"
+    OBSERVED.append((what, "out", float(max_abs), float(max_rel)))
     return max_abs, max_rel
 
 
 # Log-sum-exp.  Decode keeps the query exact: 2e-3.  Prefill rounds the query times the softmax scale to the
 # storage type (unit roundoff u = 2^-11 for fp16, 2^-8 for bf16), which moves a logit of 128 N(0,1) products by
 # about 0.58 u (one sigma) and the log-sum-exp by at most the largest logit move: four sigma is 1.1e-3 for fp16
-# and 9e-3 for bf16.
+# and 9e-3 for bf16, and the bound is that four-sigma figure (fp16 keeps the 2e-3 of the output bound).
 LSE_TOL_DECODE = 2e-3
-LSE_TOL_PREFILL = {"fp16": 2e-3, "bf16": 1.6e-2}
+LSE_TOL_PREFILL = {"fp16": 2e-3, "bf16": 9e-3}
+
+# Largest errors seen by the assertions of the running test: (what, kind, max abs, max row-relative or 0).
+# tests/conftest.py prints them after each test so that a run's log records the margins, not only pass / fail.
+OBSERVED = []
 
 
 def assert_lse_close(got: torch.Tensor, ref: np.ndarray, what: str = "", tol: float = LSE_TOL_DECODE):
     g = got.detach().to(torch.float64).cpu().numpy().reshape(ref.shape)
     err = np.abs(g - ref).max() if ref.size else 0.0
     assert err <= tol, f"{what}: lse error {err:.3e} > {tol}"
+    OBSERVED.append((what, "lse", float(err), 0.0))
 
 
 def compare_selection(sel_gpu, cnt_gpu, sel_ref, cnt_ref, scores_ref, streaming_flags):

@@ -160,6 +160,54 @@ def test_invalid_arguments_are_rejected_on_the_host(L):
     assert _rc(lambda: L.lserve_sparse_prefill_paged(desc(), q8(), q, cu4, 2, 64, out, None, ws, stream)) == -2
 
 
+def test_decode_rejects_an_index_space_beyond_32_bits_and_accepts_wide_tables(L):
+    """The launch plan numbers batch * (entries per sequence) with 32-bit integers: beyond that the call is
+    refused on the host (pointers are never dereferenced before validation, so one small buffer stands in
+    for all of them).  Entries per sequence above 65535 are fine."""
+    lib = L.load_library()
+    hkv = 64
+    d = L.AttnDesc(64, hkv, [0] * hkv)
+    batch = 65535
+    pt = torch.zeros((batch, 1), dtype=torch.int32)
+    sl = torch.ones((batch,), dtype=torch.int32)
+    k = torch.zeros((1, hkv, 64, 128), dtype=torch.float16)
+    kv = L.PagedKV(k, k, None, pt, sl)
+    p = ctypes.c_void_p(k.data_ptr())
+    ws_bytes = ctypes.c_size_t(1 << 40)
+
+    def call(sel_stride):
+        return lib.lserve_sparse_decode(d.c(), kv.c(), p, p, p, p, sel_stride, p, None, p, ws_bytes, None)
+
+    assert 65535 * 64 * 601 > 2 ** 31
+    assert call(600) == -2
+    assert L.lserve_workspace_bytes(L.LSERVE_CALL_SPARSE_DECODE, d, batch, 1, 600, 0) > 0
+    # 64 selecting heads x 2049 entries = 131136 entries per sequence: above 16 bits, accepted by the host checks
+    # (a workspace of 16 bytes is what stops this call before any launch)
+    kv1 = L.PagedKV(k, k, None, pt[:1], sl[:4][:1])
+    assert lib.lserve_sparse_decode(d.c(), kv1.c(), p, p, p, p, 2048, p, None, p, ctypes.c_size_t(16), None) == -3
+
+
+def test_selector_needs_no_statistics_when_every_head_is_streaming(L):
+    lib = L.load_library()
+    d = L.AttnDesc(4, 2, [1, 1])
+    k = torch.zeros((8, 2, 64, 128), dtype=torch.float16)
+    pt = torch.zeros((2, 4), dtype=torch.int32)
+    sl = torch.ones((4,), dtype=torch.int32)[:2]
+    kv = L.PagedKV(k, k, None, pt, sl)
+    p = ctypes.c_void_p(k.data_ptr())
+    # passes the statistics check and is stopped by the last host check (workspace too small) ...
+    assert lib.lserve_select_pages(d.c(), kv.c(), p, 256, None, p, p, p, None, p, ctypes.c_size_t(16), None) == -3
+    # ... whereas a selecting head without statistics is an invalid argument
+    d2 = L.AttnDesc(4, 2, [1, 0])
+    assert lib.lserve_select_pages(d2.c(), kv.c(), p, 256, None, p, p, p, None, p, ctypes.c_size_t(16), None) == -1
+
+
+def test_library_reads_no_environment_variable():
+    csrc = os.path.join(ROOT, "paper_2502_14866_amd", "csrc")
+    for f in os.listdir(csrc):
+        assert "getenv" not in open(os.path.join(csrc, f)).read(), f
+
+
 def test_product_path_does_not_reach_for_the_oracle():
     pkg = os.path.join(ROOT, "paper_2502_14866_amd")
     for dirpath, _, files in os.walk(pkg):
