@@ -325,6 +325,28 @@ int lserve_sparse_decode(const lserve_attn_desc *desc, const lserve_paged_kv *kv
                          void *workspace, size_t workspace_bytes, void *stream);
 
 /*
+ * lserve_sparse_decode for callers that cannot allocate device memory (code under HIP graph capture, serving
+ * loops and harnesses that forbid hipMalloc) and so have no workspace to hand over: the partial results go to a
+ * fixed scratch array of LSERVE_NOALLOC_SCRATCH_BYTES inside the library's device image, one copy per GPU, held
+ * until the process ends.  Same arguments, same kernels and bit-identical results as lserve_sparse_decode, minus
+ * the workspace.  Neither this call nor anything it uses allocates or frees memory.
+ *   - LSERVE_ERR_WORKSPACE when lserve_workspace_bytes(LSERVE_CALL_SPARSE_DECODE, ...) for these arguments exceeds
+ *     LSERVE_NOALLOC_SCRATCH_BYTES (on a 256-CU device with n = 4: batch * Hkv > 3008 lists); every other error as
+ *     in lserve_sparse_decode.
+ *   - All calls on one GPU share that GPU's scratch: two calls whose kernels may run at the same time on one GPU
+ *     (different streams, different threads) race and give undefined results; calls ordered on one stream are fine.
+ *     The scratch keeps the last call's partials; each call writes every slot it reads, nothing has to be cleared.
+ *   - The address of the scratch is resolved once per device, at lserve_init() or at the first call on that device
+ *     (with that device current).  Call lserve_init() before capturing a stream if the first call would otherwise
+ *     happen under capture.
+ */
+#define LSERVE_NOALLOC_SCRATCH_BYTES (8u << 20)
+int lserve_sparse_decode_noalloc(const lserve_attn_desc *desc, const lserve_paged_kv *kv, const void *q,
+                                 const int32_t *sel_pages, const int32_t *sel_count,
+                                 const int32_t *sel_seq_len, int32_t sel_stride, void *out, float *lse_out,
+                                 void *stream);
+
+/*
  * Bytes of device workspace a call needs (Sec. 3.6 / 3.5.2 calls keep partial results there).
  *   batch, max_pages_per_seq: as in lserve_paged_kv (ignored for prefill)
  *   sel_stride_or_budget_pages: K for select, sel_stride for decode (ignored otherwise)

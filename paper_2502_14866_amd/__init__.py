@@ -26,6 +26,7 @@ from .binding import (  # noqa: F401
     lserve_last_hip_error,
     lserve_select_pages,
     lserve_sparse_decode,
+    lserve_sparse_decode_noalloc,
     lserve_sparse_prefill,
     lserve_strerror,
     lserve_workspace_bytes,

@@ -33,6 +33,7 @@ EXPORTED_SYMBOLS = (
     "lserve_strerror",
     "lserve_last_hip_error",
     "lserve_init",
+    "lserve_sparse_decode_noalloc",
 )
 
 
@@ -106,6 +107,8 @@ def load_library():
         lib.lserve_strerror.argtypes = [ctypes.c_int]
         lib.lserve_strerror.restype = ctypes.c_char_p
         lib.lserve_last_hip_error.restype = ctypes.c_int
+        lib.lserve_sparse_decode_noalloc.argtypes = [dp, kp, vp, vp, vp, vp, i32, vp, vp, vp]
+        lib.lserve_sparse_decode_noalloc.restype = ctypes.c_int
         lib.lserve_init.argtypes = []
         lib.lserve_init.restype = ctypes.c_int
         for name in ("lserve_build_page_stats", "lserve_select_pages", "lserve_sparse_prefill",
@@ -304,3 +307,12 @@ def lserve_sparse_decode(desc: AttnDesc, kv: PagedKV, q: torch.Tensor, sel_pages
     _check(load_library().lserve_sparse_decode(desc.c(), kv.c(), _ptr(q), _ptr(sel_pages), _ptr(sel_count),
                                                _ptr(sel_seq_len), sel_stride, _ptr(out), _ptr(lse_out),
                                                _ptr(workspace), ws_bytes, _stream(stream)), "lserve_sparse_decode")
+
+
+def lserve_sparse_decode_noalloc(desc: AttnDesc, kv: PagedKV, q: torch.Tensor, sel_pages: Optional[torch.Tensor],
+                                 sel_count: Optional[torch.Tensor], sel_seq_len: Optional[torch.Tensor],
+                                 out: torch.Tensor, lse_out: Optional[torch.Tensor] = None, stream=None) -> None:
+    sel_stride = 0 if sel_pages is None else sel_pages.shape[-1]
+    _check(load_library().lserve_sparse_decode_noalloc(desc.c(), kv.c(), _ptr(q), _ptr(sel_pages), _ptr(sel_count),
+                                                       _ptr(sel_seq_len), sel_stride, _ptr(out), _ptr(lse_out),
+                                                       _stream(stream)), "lserve_sparse_decode_noalloc")

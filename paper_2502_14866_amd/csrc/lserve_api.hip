@@ -4,20 +4,49 @@
 #include "../../include/lserve.h"
 
 #include <cmath>
+#include <mutex>
 
 #include "kernels.h"
 
 using namespace lserve;
 
+// Scratch of lserve_sparse_decode_noalloc: the partial results the decode kernels exchange, which the other
+// decode entry point keeps in the caller's workspace.  One copy per GPU for the life of the process.  In host code
+// the name is only a handle: the address on a device comes from hipGetSymbolAddress (scratch_on_current_device).
+constexpr size_t kScratchBytes = LSERVE_NOALLOC_SCRATCH_BYTES;
+static __device__ __align__(256) unsigned char scratch[kScratchBytes];
+
 namespace {
 
 thread_local int g_last_hip_error = 0;
+
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+void* g_scratch_ptr[kMaxDevices] = {};  // device address of `scratch`, per device, once resolved
 
 bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
 int fail_hip(hipError_t e) {
     g_last_hip_error = (int)e;
     return LSERVE_ERR_HIP;
+}
+
+// Address of `scratch` on the device that is current on the calling thread; resolved once per device.
+int scratch_on_current_device(void** ptr) {
+    int dev = -1;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return fail_hip(e);
+    if (dev < 0 || dev >= kMaxDevices) return LSERVE_ERR_UNSUPPORTED;
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+        void* p = nullptr;
+        e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (e != hipSuccess) return fail_hip(e);
+        if (!p) return fail_hip(hipErrorInvalidSymbol);
+        g_scratch_ptr[dev] = p;
+    }
+    *ptr = g_scratch_ptr[dev];
+    return LSERVE_OK;
 }
 
 // Validates the layer description and fills the kernel parameter block.
@@ -294,6 +323,23 @@ int lserve_sparse_decode(const lserve_attn_desc* desc, const lserve_paged_kv* kv
     return e == hipSuccess ? LSERVE_OK : fail_hip(e);
 }
 
+int lserve_sparse_decode_noalloc(const lserve_attn_desc* desc, const lserve_paged_kv* kv, const void* q,
+                                 const int32_t* sel_pages, const int32_t* sel_count, const int32_t* sel_seq_len,
+                                 int32_t sel_stride, void* out, float* lse_out, void* stream) {
+    LayerParams lp;
+    PagedParams pp;
+    int rc = check_decode_args(desc, kv, q, sel_pages, sel_count, sel_seq_len, sel_stride, out, lse_out, &lp, &pp);
+    if (rc) return rc;
+    if (decode_workspace_bytes(lp, pp.batch, sel_stride) > kScratchBytes) return LSERVE_ERR_WORKSPACE;
+    void* ws = nullptr;
+    rc = scratch_on_current_device(&ws);
+    if (rc) return rc;
+    // The kernels write every partial they later read, so nothing in the scratch has to start at zero.
+    hipError_t e = launch_sparse_decode(desc->dtype, lp, pp, q, sel_pages, sel_count, sel_seq_len, sel_stride, out,
+                                        lse_out, ws, (hipStream_t)stream);
+    return e == hipSuccess ? LSERVE_OK : fail_hip(e);
+}
+
 size_t lserve_workspace_bytes(int which_call, const lserve_attn_desc* desc, int32_t batch, int32_t max_pages_per_seq,
                               int32_t sel_stride_or_budget_pages, int32_t total_tokens) {
     LayerParams lp;
@@ -313,6 +359,9 @@ size_t lserve_workspace_bytes(int which_call, const lserve_attn_desc* desc, int3
 }
 
 int lserve_init(void) {
+    void* ws = nullptr;
+    const int rc = scratch_on_current_device(&ws);
+    if (rc) return rc;
     hipError_t e = preload_stats_kernels();
     if (e == hipSuccess) e = preload_select_kernels();
     if (e == hipSuccess) e = preload_prefill_kernels();
