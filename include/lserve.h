@@ -315,7 +315,10 @@ size_t lserve_masked_prefill_workspace_bytes(const lserve_attn_desc *desc, int32
  *   sel_seq_len  device [batch]; all three may be NULL when every KV head is streaming
  *   out          device [batch][H][D]
  *   lse_out      device [batch][H] fp32 or NULL
- *   workspace    device, >= lserve_workspace_bytes(LSERVE_CALL_SPARSE_DECODE, ...)
+ *   workspace    device, >= lserve_workspace_bytes(LSERVE_CALL_SPARSE_DECODE, ...).  It must be zero-filled once
+ *                before the first call that uses it (it starts with one arrival counter per (sequence, KV head)
+ *                list, which every call leaves at zero again); after that it may go from call to call, also
+ *                between different shapes that fit it.  Two calls that may run at the same time need a workspace each.
  * LSERVE_ERR_UNSUPPORTED when batch * (index-table entries per sequence) exceeds 2^31 - 1, an entry count
  * being s + w per streaming head and sel_stride + 1 per selecting head.
  */
@@ -335,7 +338,8 @@ int lserve_sparse_decode(const lserve_attn_desc *desc, const lserve_paged_kv *kv
  *     in lserve_sparse_decode.
  *   - All calls on one GPU share that GPU's scratch: two calls whose kernels may run at the same time on one GPU
  *     (different streams, different threads) race and give undefined results; calls ordered on one stream are fine.
- *     The scratch keeps the last call's partials; each call writes every slot it reads, nothing has to be cleared.
+ *     The scratch keeps the last call's partials; each call writes every slot it reads and leaves the arrival
+ *     counters at its start at zero, which is how the device image initialises them: nothing has to be cleared.
  *   - The address of the scratch is resolved once per device, at lserve_init() or at the first call on that device
  *     (with that device current).  Call lserve_init() before capturing a stream if the first call would otherwise
  *     happen under capture.

@@ -66,23 +66,48 @@ __device__ __forceinline__ float row16_sum(float x) {
     return x;
 }
 
-__device__ __forceinline__ float shfl_xor_f(float x, int mask) { return __shfl_xor(x, mask, kWave); }
+// Reductions across the four rows of a wave (lanes l, l^16, l^32, l^48 hold peers).  gfx950 swaps rows between
+// two registers in the vector ALU: v_permlane16_swap exchanges the odd rows of its first operand with the even
+// rows of its second, v_permlane32_swap the upper half of the first with the lower half of the second.  With the
+// same value in both operands the two results hold, in every lane, the two peers of the pair, so each step is one
+// swap and one combine with no trip through the LDS crossbar.  (The elements of the builtin's result are copied
+// out before any bit cast: a bit cast applied to the subscripted vector reads element 0 both times.)
+typedef unsigned swap_pair_t __attribute__((ext_vector_type(2)));
 
-// Reductions across the four rows of a wave (lanes l, l^16, l^32, l^48 hold peers).
+template <class Op> __device__ __forceinline__ float rows4_combine(float x, Op op) {
+    const unsigned u = __builtin_bit_cast(unsigned, x);
+    const swap_pair_t a = __builtin_amdgcn_permlane16_swap(u, u, false, false);
+    const unsigned a0 = a[0], a1 = a[1];
+    const float y = op(__builtin_bit_cast(float, a0), __builtin_bit_cast(float, a1));  // rows (0,1) and (2,3)
+    const unsigned v = __builtin_bit_cast(unsigned, y);
+    const swap_pair_t b = __builtin_amdgcn_permlane32_swap(v, v, false, false);
+    const unsigned b0 = b[0], b1 = b[1];
+    return op(__builtin_bit_cast(float, b0), __builtin_bit_cast(float, b1));
+}
+// Sums of four values over the four rows at once, for the price of one and a half: the odd rows of one value trade
+// places with the even rows of another before the two are added, then the halves likewise, and on return row r of the
+// result holds the four-row sum of x_r (added as (row 0 + row 1) + (row 2 + row 3), like rows4_sum).
+__device__ __forceinline__ float rows4_sum_scatter(float x0, float x1, float x2, float x3) {
+    auto swap_add = [](float a, float b, bool halves) {
+        const unsigned ua = __builtin_bit_cast(unsigned, a), ub = __builtin_bit_cast(unsigned, b);
+        const swap_pair_t p = halves ? __builtin_amdgcn_permlane32_swap(ua, ub, false, false)
+                                     : __builtin_amdgcn_permlane16_swap(ua, ub, false, false);
+        const unsigned p0 = p[0], p1 = p[1];
+        return __builtin_bit_cast(float, p0) + __builtin_bit_cast(float, p1);
+    };
+    const float t01 = swap_add(x0, x1, false);  // rows 0, 2: pair sums of x0; rows 1, 3: of x1
+    const float t23 = swap_add(x2, x3, false);
+    return swap_add(t01, t23, true);
+}
+
 __device__ __forceinline__ float rows4_sum(float x) {
-    x += shfl_xor_f(x, 16);
-    x += shfl_xor_f(x, 32);
-    return x;
+    return rows4_combine(x, [](float a, float b) { return a + b; });
 }
 __device__ __forceinline__ float rows4_max(float x) {
-    x = fmaxf(x, shfl_xor_f(x, 16));
-    x = fmaxf(x, shfl_xor_f(x, 32));
-    return x;
+    return rows4_combine(x, [](float a, float b) { return fmaxf(a, b); });
 }
 __device__ __forceinline__ float rows4_min(float x) {
-    x = fminf(x, shfl_xor_f(x, 16));
-    x = fminf(x, shfl_xor_f(x, 32));
-    return x;
+    return rows4_combine(x, [](float a, float b) { return fminf(a, b); });
 }
 
 __device__ __forceinline__ float wave_max(float x) {

@@ -334,7 +334,8 @@ int lserve_sparse_decode_noalloc(const lserve_attn_desc* desc, const lserve_page
     void* ws = nullptr;
     rc = scratch_on_current_device(&ws);
     if (rc) return rc;
-    // The kernels write every partial they later read, so nothing in the scratch has to start at zero.
+    // The arrival counters at the start of the scratch are zero when the device image is loaded and every launch
+    // leaves them at zero; the kernels write every partial they later read.
     hipError_t e = launch_sparse_decode(desc->dtype, lp, pp, q, sel_pages, sel_count, sel_seq_len, sel_stride, out,
                                         lse_out, ws, (hipStream_t)stream);
     return e == hipSuccess ? LSERVE_OK : fail_hip(e);

@@ -14,8 +14,8 @@
 // flight while it works on the current one; its four wavefronts each take a quarter of a page's
 // tokens.  A range may cross list boundaries; every (workgroup, list) piece yields either the final
 // result (the list lies inside the range) or a partial (max, sum, unnormalised output) at slot
-// workgroup + list index, which a small merge kernel combines in slot order.  Reduction orders are
-// fixed, so results are deterministic.
+// workgroup + list index; the workgroup that delivers the last piece of a list folds them in slot order.
+// Reduction orders are fixed, so results are deterministic.
 //
 // Pages may also hold quantised rows (Sec. 3.2: 8- or 4-bit codes with one fp16 scale and zero point per
 // token, stored after the page's rows).  The kernel is the same with the slab loads and the per-page
@@ -32,6 +32,7 @@ constexpr int kDecodeThreads = 256;
 constexpr int kDecodeWaves = kDecodeThreads / kWave;
 constexpr int kMaxBlocksPerCU = 4;       // upper bound used to size the workspace
 constexpr int kBlocksPerCU = 2;          // measured best on MI355X: more resident workgroups only queue up in the fabric
+constexpr int kSlackFromEntries = 8;     // ranges at least this long model the cost of a list boundary (see make_plan)
 constexpr float kLn2 = 0.6931471805599453f;
 
 // ---- index tables --------------------------------------------------------------------------------
@@ -394,10 +395,11 @@ __device__ __forceinline__ void process_quarter(WaveState<N>& st, const uint4* q
 // Shared memory of a decode workgroup.
 template <int N, int NP> struct DecodeShared {
     float o[kDecodeWaves][N][kHeadDim];   // cross-wave merge
-    float m[kDecodeWaves][N], l[kDecodeWaves][N];
+    float m[kDecodeWaves][N], l[kDecodeWaves][N], z[kDecodeWaves][N];
     uint4 q[N * 16];                      // queries of the current group
     float q_sum[kMaxGroup];               // quantised pages only: sum over the channels of each query
     float p[kDecodeWaves][(NP / 4) * p_row(N)];
+    unsigned arrived;                     // pieces of a cut list that were in before this workgroup's
 };
 
 // Loads the n queries of KV head hk into shared memory.  Called by the whole workgroup.
@@ -443,6 +445,20 @@ __device__ __forceinline__ void stage_query(DecodeShared<N, NP>& sm, const uint4
     __syncthreads();
 }
 
+// Partial results travel between workgroups that may sit on different XCDs, each with an L2 of its own.  They are
+// written and read with agent-scope accesses (write-through stores, loads that are not served from a stale line),
+// which costs those few hundred kilobytes nothing, instead of fences that write back and invalidate whole caches.
+// Two floats per access (8-byte aligned).
+__device__ __forceinline__ void store_shared_across_chip(float* p, float a, float b) {
+    const float2 v = make_float2(a, b);
+    __hip_atomic_store(reinterpret_cast<unsigned long long*>(p), __builtin_bit_cast(unsigned long long, v),
+                       __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ float2 load_shared_across_chip(const float* p) {
+    return __builtin_bit_cast(float2, __hip_atomic_load(reinterpret_cast<const unsigned long long*>(p), __ATOMIC_RELAXED,
+                                                        __HIP_MEMORY_SCOPE_AGENT));
+}
+
 // Folds the four token rows of every wave, then the four waves of the workgroup, and writes either
 // the final rows (out / lse) or a partial (part_o / part_ml).  Must be called by all 256 threads.
 template <class T, int N, int NP, int BITS>
@@ -451,60 +467,63 @@ __device__ __forceinline__ void flush_block(WaveState<N>& st, DecodeShared<N, NP
                                             float* part_ml, size_t part_slot) {
     const int lane = threadIdx.x % kWave, wave = threadIdx.x / kWave;
     const int r = lane / 16, c = lane % 16;
+    // Sums over the four token rows of the wave, four values at a time: row r ends up with the total of the r-th.
+    constexpr int kQuads = (N + 3) / 4;
+    float lrow[4 * kQuads], zrow[4 * kQuads];
 #pragma unroll
-    for (int hh = 0; hh < N; ++hh) {
-        // every lane of a token added the token's weight: 64 lanes hold LPT copies of the sum
-        float lsum = st.l[hh];
-        lsum += dpp_f<kDppXor1>(lsum);
-        lsum += dpp_f<kDppXor2>(lsum);
-        lsum += dpp_f<kDppHalfMirror>(lsum);
-        lsum += dpp_f<kDppMirror>(lsum);
-        lsum = rows4_sum(lsum) * (1.0f / KeyMap<NP>::LPT);
-        // quantised values: the zero-point term, summed like the weights, belongs to every channel
+    for (int hh = 0; hh < 4 * kQuads; ++hh) {
+        // every lane of a token added the token's weight (and, for quantised values, its share of the zero-point
+        // term, which belongs to every channel): the 64 lanes hold LPT copies of each sum
+        lrow[hh] = hh < N ? row16_sum(st.l[hh]) : 0.f;
+        zrow[hh] = hh < N && BITS != 16 ? row16_sum(st.z[hh]) : 0.f;
+    }
+#pragma unroll
+    for (int g = 0; g < kQuads; ++g) {
+        const float lsum = rows4_sum_scatter(lrow[4 * g], lrow[4 * g + 1], lrow[4 * g + 2], lrow[4 * g + 3]);
         float zsum = 0.f;
-        if (BITS != 16) {
-            zsum = st.z[hh];
-            zsum += dpp_f<kDppXor1>(zsum);
-            zsum += dpp_f<kDppXor2>(zsum);
-            zsum += dpp_f<kDppHalfMirror>(zsum);
-            zsum += dpp_f<kDppMirror>(zsum);
-            zsum = rows4_sum(zsum) * (1.0f / KeyMap<NP>::LPT);
-        }
-#pragma unroll
-        for (int i = 0; i < 8; ++i) st.o[hh][i] = rows4_sum(st.o[hh][i]) + zsum;
-        if (r == 0) {
-#pragma unroll
-            for (int i = 0; i < 8; ++i) sm.o[wave][hh][8 * c + i] = st.o[hh][i];
-        }
-        if (lane == 0) {
-            sm.m[wave][hh] = st.m[hh];
-            sm.l[wave][hh] = lsum;
+        if (BITS != 16) zsum = rows4_sum_scatter(zrow[4 * g], zrow[4 * g + 1], zrow[4 * g + 2], zrow[4 * g + 3]);
+        if (c == 0 && 4 * g + r < N) {
+            sm.l[wave][4 * g + r] = lsum * (1.0f / KeyMap<NP>::LPT);
+            sm.z[wave][4 * g + r] = zsum * (1.0f / KeyMap<NP>::LPT);
         }
     }
+#pragma unroll
+    for (int hh = 0; hh < N; ++hh) {
+#pragma unroll
+        for (int g = 0; g < 2; ++g)  // lane (r, c) receives channel 8 c + 4 g + r
+            sm.o[wave][hh][8 * c + 4 * g + r] =
+                rows4_sum_scatter(st.o[hh][4 * g], st.o[hh][4 * g + 1], st.o[hh][4 * g + 2], st.o[hh][4 * g + 3]);
+        if (lane == 0) sm.m[wave][hh] = st.m[hh];
+    }
     __syncthreads();
-    for (int idx = threadIdx.x; idx < N * kHeadDim; idx += kDecodeThreads) {
-        const int hh = idx / kHeadDim, ch = idx % kHeadDim;
+    // one thread per (query head, four channels): N * 32 <= 256 work items
+    if (threadIdx.x < N * (kHeadDim / 4)) {
+        const int hh = threadIdx.x / (kHeadDim / 4), ch = threadIdx.x % (kHeadDim / 4) * 4;
         float M = sm.m[0][hh];
 #pragma unroll
         for (int w = 1; w < kDecodeWaves; ++w) M = fmaxf(M, sm.m[w][hh]);
-        float lt = 0.f, acc = 0.f;
+        float lt = 0.f, acc[4] = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
         for (int w = 0; w < kDecodeWaves; ++w) {
             const float f = sm.m[w][hh] == -INFINITY ? 0.f : __builtin_amdgcn_exp2f(sm.m[w][hh] - M);
             lt += sm.l[w][hh] * f;
-            acc += sm.o[w][hh][ch] * f;
+            const float4 o4 = *reinterpret_cast<const float4*>(&sm.o[w][hh][ch]);
+            const float z = BITS != 16 ? sm.z[w][hh] : 0.f;
+            acc[0] += (o4.x + z) * f;
+            acc[1] += (o4.y + z) * f;
+            acc[2] += (o4.z + z) * f;
+            acc[3] += (o4.w + z) * f;
         }
         const int h = hk * N + hh;
         if (final_result) {
-            out[((size_t)b * H + h) * kHeadDim + ch] = (uint16_t)(Elem<T>::pack(acc / lt, 0.f) & 0xffffu);
+            const uint2 packed = make_uint2(Elem<T>::pack(acc[0] / lt, acc[1] / lt), Elem<T>::pack(acc[2] / lt, acc[3] / lt));
+            *reinterpret_cast<uint2*>(out + ((size_t)b * H + h) * kHeadDim + ch) = packed;
             if (lse_out && ch == 0) lse_out[b * H + h] = (M + __builtin_amdgcn_logf(lt)) * kLn2;
         } else {
             const size_t pi = part_slot * N + hh;
-            part_o[pi * kHeadDim + ch] = acc;
-            if (ch == 0) {
-                part_ml[pi * 2] = M;
-                part_ml[pi * 2 + 1] = lt;
-            }
+            store_shared_across_chip(part_o + pi * kHeadDim + ch, acc[0], acc[1]);
+            store_shared_across_chip(part_o + pi * kHeadDim + ch + 2, acc[2], acc[3]);
+            if (ch == 0) store_shared_across_chip(part_ml + pi * 2, M, lt);
         }
     }
     __syncthreads();
@@ -521,11 +540,23 @@ __device__ __forceinline__ void flush_block(WaveState<N>& st, DecodeShared<N, NP
 // for more than one new page) are handled by the workgroup that owns the list's last nominal entry.
 
 struct DecodePlan {
-    int per_seq;               // nominal entries per sequence
-    int total;                 // batch * per_seq
-    int quot, rem;             // total = G * quot + rem: the first `rem` ranges hold quot + 1 entries
-    int first[65];             // first nominal entry of KV head hk inside a sequence; first[Hkv] = per_seq
+    int per_seq;                 // nominal entries per sequence
+    int total;                   // batch * per_seq
+    int quot, rem;               // total = G * quot + rem: the first `rem` ranges hold quot + 1 entries
+    int stream_len, select_len;  // nominal entries of a streaming head's list and of a selecting head's
 };
+
+// First nominal entry of KV head hk inside a sequence (hk = Hkv gives per_seq).  The lists of a sequence follow
+// each other in head order, so the start is a count of the streaming heads below hk: plain arithmetic on two
+// launch constants, with nothing to fetch before the first table look-up can be issued.
+__device__ __forceinline__ int first_entry(const DecodePlan& plan, unsigned long long streaming_mask, int hk) {
+    const unsigned long long below = hk >= 64 ? ~0ull : (1ull << hk) - 1ull;
+    const int ns = __popcll(streaming_mask & below);
+    return ns * plan.stream_len + (hk - ns) * plan.select_len;
+}
+__device__ __forceinline__ int nominal_len(const DecodePlan& plan, unsigned long long streaming_mask, int hk) {
+    return ((streaming_mask >> hk) & 1ull) ? plan.stream_len : plan.select_len;
+}
 
 // Range of workgroup j is [range_begin(j), range_begin(j + 1)); no division on the device.
 __device__ __forceinline__ int range_begin(const DecodePlan& plan, int j) { return j * plan.quot + min(j, plan.rem); }
@@ -536,66 +567,87 @@ __device__ __forceinline__ int range_of(const DecodePlan& plan, int x) {
     return x < big ? x / (plan.quot + 1) : plan.rem + (x - big) / plan.quot;
 }
 
-// KV head of nominal entry y of a sequence.  The loop index is uniform, so the table is read with
-// independent scalar loads instead of a chain of dependent ones.
-__device__ __forceinline__ int head_of_entry(const DecodePlan& plan, int Hkv, int y) {
+// KV head of nominal entry y of a sequence: the number of heads whose list starts at or before y, less one.
+__device__ __forceinline__ int head_of_entry(const DecodePlan& plan, unsigned long long streaming_mask, int Hkv, int y) {
     int hk = 0;
-    for (int h = 1; h < Hkv; ++h) hk += y >= plan.first[h];
+    for (int h = 1; h < Hkv; ++h) hk += y >= first_entry(plan, streaming_mask, h);
     return hk;
 }
 
-// Folds the pieces of one list, in slot order, kBatch at a time so that their loads are in flight
-// together (8, or 32 when the lists of a launch are cut into more pieces than that).  Every range between j0 and j1 wrote a piece (ranges there are never empty: an empty
-// range implies quot = 0, and then no list spans two ranges); a range that held only nominal
-// entries past the list's real length wrote a neutral piece (max = -inf), whose output is skipped.
+// Folds the pieces of one list, in slot order, kBatch at a time so that their loads are in flight together, for
+// four channels `ch .. ch + 3` of query head `hh` of the group.  Every range between j0 and j1 holds a real entry
+// of the list and wrote a piece (ranges there are never empty: an empty range implies quot = 0, and then no list
+// spans two ranges).
 template <class T, int N, int kBatch>
 __device__ __forceinline__ void fold_pieces(int list, int j0, int j1, int hh, int ch, int H, int b, int hk,
                                             uint16_t* out, float* lse_out, const float* part_o,
                                             const float* part_ml) {
-    float M = -INFINITY, lt = 0.f, acc = 0.f;
+    float M = -INFINITY, lt = 0.f, acc[4] = {0.f, 0.f, 0.f, 0.f};
     for (int jb = j0; jb <= j1; jb += kBatch) {
-        float pm[kBatch], pl[kBatch], po[kBatch];
+        float2 ml[kBatch], lo[kBatch], hi[kBatch];
 #pragma unroll
         for (int u = 0; u < kBatch; ++u) {
-            const int j = jb + u;
-            const bool real = j <= j1;
-            const size_t pi = ((size_t)(real ? j : j0) + list) * N + hh;
-            pm[u] = real ? part_ml[pi * 2] : -INFINITY;
-            pl[u] = real ? part_ml[pi * 2 + 1] : 0.f;
-            po[u] = real ? part_o[pi * kHeadDim + ch] : 0.f;
+            const size_t pi = ((size_t)min(jb + u, j1) + list) * N + hh;  // past the end: the last piece again, unused
+            ml[u] = load_shared_across_chip(part_ml + pi * 2);
+            lo[u] = load_shared_across_chip(part_o + pi * kHeadDim + ch);
+            hi[u] = load_shared_across_chip(part_o + pi * kHeadDim + ch + 2);
         }
-        float bm = pm[0];
+        float bm = -INFINITY;
 #pragma unroll
-        for (int u = 1; u < kBatch; ++u) bm = fmaxf(bm, pm[u]);
-        if (bm == -INFINITY) continue;
+        for (int u = 0; u < kBatch; ++u) bm = fmaxf(bm, jb + u <= j1 ? ml[u].x : -INFINITY);
+        if (bm == -INFINITY) continue;  // only if every logit of these pieces was -inf
         const float m_new = fmaxf(M, bm);
         const float keep = __builtin_amdgcn_exp2f(M - m_new);  // 0 for the first batch (M = -inf)
         lt *= keep;
-        acc *= keep;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) acc[i] *= keep;
 #pragma unroll
         for (int u = 0; u < kBatch; ++u) {
-            const float f = __builtin_amdgcn_exp2f(pm[u] - m_new);
-            lt += pl[u] * f;
-            acc += pm[u] == -INFINITY ? 0.f : po[u] * f;  // a neutral piece has no output to read
+            const float f = jb + u <= j1 ? __builtin_amdgcn_exp2f(ml[u].x - m_new) : 0.f;
+            lt += ml[u].y * f;
+            acc[0] += lo[u].x * f;
+            acc[1] += lo[u].y * f;
+            acc[2] += hi[u].x * f;
+            acc[3] += hi[u].y * f;
         }
         M = m_new;
     }
     const int h = hk * N + hh;
-    out[((size_t)b * H + h) * kHeadDim + ch] = (uint16_t)(Elem<T>::pack(acc / lt, 0.f) & 0xffffu);
+    const uint2 packed = make_uint2(Elem<T>::pack(acc[0] / lt, acc[1] / lt), Elem<T>::pack(acc[2] / lt, acc[3] / lt));
+    *reinterpret_cast<uint2*>(out + ((size_t)b * H + h) * kHeadDim + ch) = packed;
     if (lse_out && ch == 0) lse_out[b * H + h] = (M + __builtin_amdgcn_logf(lt)) * kLn2;
 }
 
-// Ends a (workgroup, list) piece: a list that lies inside the workgroup's range is written out
-// directly, otherwise the piece goes to the workspace for decode_merge_kernel.  (Folding inside this
-// kernel with a device-scope fence and an arrival counter was measured at 3x the whole kernel time
-// on MI355X: the fence writes back and invalidates the XCD's L2.)  Called by all threads.
+// Ends a (workgroup, list) piece.  `len` is the real length of the list, so its real entries occupy the nominal
+// entries [n0, n_end) and exactly the workgroups whose ranges meet that stretch hold a piece of it.  A list that
+// lies inside this workgroup's range is written out directly.  Otherwise the piece goes to the workspace, the
+// workgroup counts itself in on the list's arrival counter, and the one that finds every other piece already in
+// folds them all, in slot order (so the result does not depend on which workgroup folds), writes the rows and
+// puts the counter back to zero for the next launch.  Nobody waits for anybody.  Stores, counter and loads are
+// agent-scope accesses with a wait for the stores in between; no cache-wide fence (a device-scope fence here was
+// measured at three times the whole kernel: it writes back and invalidates the L2).  Called by all threads.
 template <class T, int N, int NP, int BITS>
 __device__ __forceinline__ void end_piece(WaveState<N>& st, DecodeShared<N, NP>& sm, const DecodePlan& plan, int blk,
-                                          int lo, int hi, int list, int H, int Hkv, uint16_t* out, float* lse_out,
-                                          float* part_o, float* part_ml) {
+                                          int lo, int hi, int list, int len, int H, int Hkv,
+                                          unsigned long long streaming_mask, uint16_t* out,
+                                          float* lse_out, float* part_o, float* part_ml, unsigned* arrivals) {
     const int b = list / Hkv, hk = list % Hkv;
-    const int n0 = b * plan.per_seq + plan.first[hk], n1 = b * plan.per_seq + plan.first[hk + 1];
-    flush_block<T, N, NP, BITS>(st, sm, n0 >= lo && n1 <= hi, H, b, hk, out, lse_out, part_o, part_ml, (size_t)blk + list);
+    const int n0 = b * plan.per_seq + first_entry(plan, streaming_mask, hk);
+    const int n_end = n0 + min(len, nominal_len(plan, streaming_mask, hk));
+    const bool whole = n0 >= lo && n_end <= hi;
+    flush_block<T, N, NP, BITS>(st, sm, whole, H, b, hk, out, lse_out, part_o, part_ml, (size_t)blk + list);
+    if (whole) return;
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // this thread's part of the piece has reached memory
+    __syncthreads();
+    if (threadIdx.x == 0)
+        sm.arrived = __hip_atomic_fetch_add(arrivals + list, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    __syncthreads();
+    const int j0 = range_of(plan, n0), j1 = range_of(plan, n_end - 1);
+    if ((int)sm.arrived != j1 - j0) return;  // somebody else will fold
+    if (threadIdx.x < N * (kHeadDim / 4))
+        fold_pieces<T, N, 8>(list, j0, j1, threadIdx.x / (kHeadDim / 4), threadIdx.x % (kHeadDim / 4) * 4, H, b, hk, out,
+                             lse_out, part_o, part_ml);
+    if (threadIdx.x == 0) __hip_atomic_store(arrivals + list, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 
 // Visits entry IDX of the current batch, whose slabs are in CUR: when the (wave-uniform) list changes the
@@ -609,8 +661,10 @@ __device__ __forceinline__ void end_piece(WaveState<N>& st, DecodeShared<N, NP>&
         const int list = __builtin_amdgcn_readlane(my_list, (IDX));                                                  \
         if (list != cur_list) {                                                                                      \
             if (cur_list >= 0)                                                                                       \
-                end_piece<T, N, NP, BITS>(st, sm, plan, blk, lo, hi, cur_list, lp.H, lp.Hkv, out, lse_out, part_o, part_ml);\
+                end_piece<T, N, NP, BITS>(st, sm, plan, blk, lo, hi, cur_list, cur_len, lp.H, lp.Hkv,                \
+                                          lp.streaming_mask, out, lse_out, part_o, part_ml, arrivals);               \
             cur_list = list;                                                                                         \
+            cur_len = __builtin_amdgcn_readlane(my_len, (IDX));                                                      \
             cur_b = list / lp.Hkv;                                                                                   \
             cur_hk = list % lp.Hkv;                                                                                  \
             stage_query<T, N, NP, BITS>(sm, q, cur_b, lp.H, cur_hk, list, q_ahead);                                  \
@@ -621,7 +675,7 @@ __device__ __forceinline__ void end_piece(WaveState<N>& st, DecodeShared<N, NP>&
         process_quarter<T, N, NP, BITS>(st, sm.q, sm.q_sum, sm.p[wave], CUR, L - pos * NP, tok0, lane, lp.sm_scale_log2); \
         const int extra = __builtin_amdgcn_readlane(my_extra, (IDX));                                                \
         if (extra > 0) {                                                                                             \
-            const int nominal = plan.first[cur_hk + 1] - plan.first[cur_hk];                                         \
+            const int nominal = nominal_len(plan, lp.streaming_mask, cur_hk);                                        \
             const int tail = __builtin_amdgcn_readlane(my_tail, (IDX));                                              \
             for (int e = 0; e < extra; ++e) {                                                                        \
                 const int epos = tail + nominal + e;                                                                 \
@@ -639,8 +693,23 @@ template <class T, int N, int NP, int BITS>
 __global__ __launch_bounds__(kDecodeThreads) void sparse_decode_kernel(
     LayerParams lp, PagedParams kv, DecodePlan plan, const uint4* __restrict__ q, const int* __restrict__ sel_pages,
     const int* __restrict__ sel_count, const int* __restrict__ sel_seq_len, int sel_stride,
-    uint16_t* __restrict__ out, float* __restrict__ lse_out, float* __restrict__ part_o, float* __restrict__ part_ml) {
+    uint16_t* __restrict__ out, float* __restrict__ lse_out, float* __restrict__ part_o, float* __restrict__ part_ml,
+    unsigned* __restrict__ arrivals) {
     __shared__ DecodeShared<N, NP> sm;
+
+    // The launch constants fill four 64-byte lines of the kernel argument block, and the code below wants them in
+    // half a dozen dependent rounds; fetched as needed, each round missed the scalar cache and the first table
+    // look-up left 2.2 us after the start of the kernel.  One word of every line is requested here, together.
+#if defined(__HIP_DEVICE_COMPILE__)
+    {
+        typedef const int __attribute__((address_space(4))) * kernarg_words;
+        const kernarg_words args = (kernarg_words)__builtin_amdgcn_kernarg_segment_ptr();
+        static_assert(sizeof(LayerParams) + sizeof(PagedParams) + sizeof(DecodePlan) + 9 * sizeof(void*) > 48 * sizeof(int),
+                      "the argument block must reach the last line touched");
+        const int a0 = args[0], a1 = args[16], a2 = args[32], a3 = args[48];
+        asm volatile("" ::"s"(a0), "s"(a1), "s"(a2), "s"(a3));
+    }
+#endif
 
     const int blk = blockIdx.x;
     const int lo = range_begin(plan, blk), hi = range_begin(plan, blk + 1);
@@ -668,66 +737,60 @@ __global__ __launch_bounds__(kDecodeThreads) void sparse_decode_kernel(
     QueryAhead q_ahead;
     q_ahead.list = -4;  // matches no list
     q_ahead.x[0] = q_ahead.x[1] = make_uint4(0, 0, 0, 0);
-    if constexpr (kQueriesAhead) {
-        const int b0 = lo / plan.per_seq;
-        q_ahead.list = b0 * lp.Hkv + head_of_entry(plan, lp.Hkv, lo % plan.per_seq);
-        const int last = kv.batch * lp.Hkv - 1;
-#pragma unroll
-        for (int u = 0; u < 2; ++u) {
-            const int list = min(q_ahead.list + u, last);
-            if (threadIdx.x < N * 16)
-                q_ahead.x[u] = q[((size_t)(list / lp.Hkv) * lp.H + (list % lp.Hkv) * N) * (kHeadDim / 8) + threadIdx.x];
-        }
-    }
 
     WaveState<N> st;
-    int cur_list = -1, cur_b = 0, cur_hk = 0;
+    int cur_list = -1, cur_b = 0, cur_hk = 0, cur_len = 0;
+    // with every head streaming there is no selection: the loads below then read a valid word of the lengths
+    const int* sel_table = sel_pages ? sel_pages : kv.seq_lens;
+    const int* sel_counts = sel_pages ? sel_count : kv.seq_lens;
+    const int* sel_lens = sel_pages ? sel_seq_len : kv.seq_lens;
+    const int has_sel = sel_pages != nullptr;  // a factor, not a condition: the loads must not sit behind a branch
 
     for (int base = lo; base < hi; base += kWave) {
-        // one lane per nominal entry: everything that does not depend on another load is requested
-        // at once (lengths, selection entry), then the page table, then the slabs
+        // One lane per nominal entry.  Every load that depends on nothing loaded goes out first and together (the
+        // length; for a selecting head its selection entry, count and selection-time length), then the page
+        // table, then the slabs: three round trips before the first byte of K / V, and no more.  Lanes past the
+        // end of the range repeat its last entry, so that every lane forms valid addresses without a branch.
         const int cnt = min(kWave, hi - base);
-        int my_list = 0, my_pos = 0, my_phys = 0, my_L = 1, my_extra = 0, my_tail = 0;
-        bool my_valid = false;
-        if (lane < cnt) {
-            const int x = base + lane;
-            const int b = x / plan.per_seq, y = x % plan.per_seq;
-            const int hk = head_of_entry(plan, lp.Hkv, y);
-            const int i = y - plan.first[hk], nominal = plan.first[hk + 1] - plan.first[hk];
-            my_list = b * lp.Hkv + hk;
-            my_L = kv.seq_lens[b];
-            const int P = ceil_div(my_L, NP);
-            int head, tail_start, sel_entry = 0;
-            const bool streaming = (lp.streaming_mask >> hk) & 1ull;
-            if (streaming) {
-                head = min(lp.sink_pages, P);
-                tail_start = max(head, P - lp.local_pages);
-                sel_entry = i;
-            } else {
-                sel_entry = sel_pages[(size_t)my_list * sel_stride + min(i, sel_stride - 1)];
-                head = sel_count[my_list];
-                tail_start = ceil_div(sel_seq_len[b], NP);
-            }
-            const int len = head + max(0, P - tail_start);
-            my_valid = i < len;
-            my_pos = i < head ? sel_entry : tail_start + (i - head);
-            my_tail = tail_start - head;  // position of entry i >= head is my_tail + i
-            if (i == nominal - 1 && len > nominal) my_extra = len - nominal;
-            if (my_valid)
-                my_phys = in_stream_pool(lp, kv, hk) ? kv.ring_table[(size_t)b * kv.ring + ring_slot(lp, my_pos)]
-                                                     : kv.page_table[(size_t)b * kv.max_pages + my_pos];
-            // Validity is monotone in i, so if the first nominal entry of a split list inside this range
-            // is past the real length the range holds nothing of the list: leave a neutral piece so that
-            // the merge kernel needs no lengths.
-            const int n0 = x - i, n1 = n0 + nominal;
-            if (!my_valid && x == max(n0, lo) && !(n0 >= lo && n1 <= hi)) {
-                for (int hh = 0; hh < N; ++hh) {
-                    const size_t pi = ((size_t)blk + my_list) * N + hh;
-                    part_ml[pi * 2] = -INFINITY;
-                    part_ml[pi * 2 + 1] = 0.f;
-                }
+        const int x = base + min(lane, cnt - 1);
+        const int b = x / plan.per_seq, y = x - b * plan.per_seq;
+        const int hk = head_of_entry(plan, lp.streaming_mask, lp.Hkv, y);
+        const int i = y - first_entry(plan, lp.streaming_mask, hk), nominal = nominal_len(plan, lp.streaming_mask, hk);
+        const bool streaming = (lp.streaming_mask >> hk) & 1ull;
+        const int my_list = b * lp.Hkv + hk;
+        // no branch between these loads and their first use, or the wait for them could not be counted exactly
+        // and would take in the query loads as well; lanes of streaming heads read valid words they ignore
+        const int my_L = kv.seq_lens[b];
+        const int sel_word = sel_table[has_sel * ((size_t)my_list * sel_stride + min(i, sel_stride - 1))];
+        const int sel_head = sel_counts[has_sel * my_list];
+        const int sel_len = sel_lens[has_sel * b];
+        // The queries of the first two lists of these entries go out behind the table loads (in front of them they
+        // would be waited for first: loads complete in order).  Thread t holds chunk t % (N * 16) of the group.
+        if constexpr (kQueriesAhead) {
+            q_ahead.list = __builtin_amdgcn_readfirstlane(my_list);
+            const int last = kv.batch * lp.Hkv - 1;
+#pragma unroll
+            for (int u = 0; u < 2; ++u) {
+                const int list = min(q_ahead.list + u, last);
+                q_ahead.x[u] = q[((size_t)(list / lp.Hkv) * lp.H + (list % lp.Hkv) * N) * (kHeadDim / 8) +
+                                 threadIdx.x % (N * 16)];
             }
         }
+        __builtin_amdgcn_sched_barrier(0);  // all of the above is requested before any of it is used
+        const int P = ceil_div(my_L, NP);
+        const int stream_head = min(lp.sink_pages, P);
+        const int head = streaming ? stream_head : sel_head;
+        const int tail_start = streaming ? max(stream_head, P - lp.local_pages) : ceil_div(sel_len, NP);
+        const int sel_entry = streaming ? i : sel_word;
+        const int my_len = head + max(0, P - tail_start);
+        const bool my_valid = lane < cnt && i < my_len;
+        const int my_pos = i < head ? sel_entry : tail_start + (i - head);
+        const int my_tail = tail_start - head;  // position of entry i >= head is my_tail + i
+        const int my_extra = (i == nominal - 1 && my_len > nominal) ? my_len - nominal : 0;
+        int my_phys = 0;
+        if (my_valid)
+            my_phys = in_stream_pool(lp, kv, hk) ? kv.ring_table[(size_t)b * kv.ring + ring_slot(lp, my_pos)]
+                                                 : kv.page_table[(size_t)b * kv.max_pages + my_pos];
         unsigned long long todo = __ballot(my_valid);
         if (todo == 0) continue;
         if constexpr (BITS == 16) {
@@ -797,24 +860,11 @@ __global__ __launch_bounds__(kDecodeThreads) void sparse_decode_kernel(
         }
     }
     if (cur_list < 0) return;  // no real entry in this range
-    end_piece<T, N, NP, BITS>(st, sm, plan, blk, lo, hi, cur_list, lp.H, lp.Hkv, out, lse_out, part_o, part_ml);
+    end_piece<T, N, NP, BITS>(st, sm, plan, blk, lo, hi, cur_list, cur_len, lp.H, lp.Hkv, lp.streaming_mask, out, lse_out,
+                              part_o, part_ml, arrivals);
 }
 
 #undef LSERVE_DECODE_VISIT
-
-// Combines the pieces of every list that was cut by a range boundary, in slot order.
-template <class T, int N, int kBatch>
-__global__ __launch_bounds__(N* kHeadDim) void decode_merge_kernel(
-    LayerParams lp, DecodePlan plan, uint16_t* __restrict__ out, float* __restrict__ lse_out,
-    const float* __restrict__ part_o, const float* __restrict__ part_ml) {
-    const int hk = blockIdx.x, b = blockIdx.y, list = b * lp.Hkv + hk;
-    const int n0 = b * plan.per_seq + plan.first[hk], n1 = b * plan.per_seq + plan.first[hk + 1];
-    // workgroups whose ranges hold the first and the last nominal entry of the list
-    const int j0 = range_of(plan, n0), j1 = range_of(plan, n1 - 1);
-    if (j0 == j1) return;  // the list lay inside one range: the decode kernel wrote the final rows
-    fold_pieces<T, N, kBatch>(list, j0, j1, threadIdx.x / kHeadDim, threadIdx.x % kHeadDim, lp.H, b, hk, out, lse_out,
-                              part_o, part_ml);
-}
 
 // ---- host side -----------------------------------------------------------------------------------
 
@@ -828,20 +878,31 @@ int num_compute_units() {
     return cus;
 }
 
-DecodePlan make_plan(const LayerParams& lp, int batch, int sel_stride, int G) {
+// `slack`: nominal entries added to a streaming head's list beyond its s + w pages.  They are never real, so they
+// cost the workgroup that holds them nothing, which makes up for what a list boundary inside a range costs it
+// (the piece of the list that ends there is folded and delivered, the next list's queries are staged: about
+// 0.7 of a page's time, measured).  A selecting head's list has such an entry already, since its "+ 1" page is
+// real only after the sequence has grown into a new page.
+DecodePlan make_plan(const LayerParams& lp, int batch, int sel_stride, int G, int slack) {
     DecodePlan plan;
-    int acc = 0;
-    for (int hk = 0; hk < lp.Hkv; ++hk) {
-        plan.first[hk] = acc;
-        const bool streaming = (lp.streaming_mask >> hk) & 1ull;
-        acc += streaming ? lp.sink_pages + lp.local_pages : sel_stride + 1;
-    }
-    for (int hk = lp.Hkv; hk <= 64; ++hk) plan.first[hk] = acc;
-    plan.per_seq = acc;
-    plan.total = batch * acc;
+    plan.stream_len = lp.sink_pages + lp.local_pages + slack;
+    plan.select_len = sel_stride + 1;
+    int n_stream = 0;
+    for (int hk = 0; hk < lp.Hkv; ++hk) n_stream += (int)((lp.streaming_mask >> hk) & 1ull);
+    plan.per_seq = n_stream * plan.stream_len + (lp.Hkv - n_stream) * plan.select_len;
+    plan.total = batch * plan.per_seq;
     plan.quot = plan.total / G;
     plan.rem = plan.total % G;
     return plan;
+}
+
+struct DecodeScratch {
+    float *part_o, *part_ml;  // pieces: unnormalised outputs, (max, sum) pairs
+    unsigned* arrivals;       // per list: pieces that have arrived
+};
+
+size_t arrival_bytes(const LayerParams& lp, int batch) {
+    return ((size_t)batch * lp.Hkv * sizeof(unsigned) + 255) & ~(size_t)255;
 }
 
 size_t partial_slots(const LayerParams& lp, int batch) {
@@ -851,7 +912,7 @@ size_t partial_slots(const LayerParams& lp, int batch) {
 template <class T, int N, int NP, int BITS>
 hipError_t launch_decode_kernels(const LayerParams& lp, const PagedParams& kv, const void* q, const int* sel_pages,
                                  const int* sel_count, const int* sel_seq_len, int sel_stride, void* out,
-                                 float* lse_out, float* part_o, float* part_ml, hipStream_t stream) {
+                                 float* lse_out, const DecodeScratch& ws, hipStream_t stream) {
     const uint4* q4 = reinterpret_cast<const uint4*>(q);
     uint16_t* o16 = reinterpret_cast<uint16_t*>(out);
     // Resident workgroups per compute unit of this instantiation: a property of the binary and the device, asked
@@ -866,44 +927,34 @@ hipError_t launch_decode_kernels(const LayerParams& lp, const PagedParams& kv, c
         return nb < 1 ? 1 : (nb > kBlocksPerCU ? kBlocksPerCU : nb);
     }();
     // two workgroups per compute unit, unless that leaves fewer than four entries each: a small launch is all
-    // start-up, fold and merge, and half as many workgroups with twice the pages do less of each (measured)
+    // start-up and fold, and half as many workgroups with twice the pages do less of each (measured)
     int G = num_compute_units() * per_cu;
-    DecodePlan plan = make_plan(lp, kv.batch, sel_stride, G);
+    DecodePlan plan = make_plan(lp, kv.batch, sel_stride, G, 0);
     if (per_cu > 1 && plan.quot < 4) {
         G = num_compute_units();
-        plan = make_plan(lp, kv.batch, sel_stride, G);
+        plan = make_plan(lp, kv.batch, sel_stride, G, 0);
+    } else if (plan.quot >= kSlackFromEntries) {
+        plan = make_plan(lp, kv.batch, sel_stride, G, 1);
     }
     hipLaunchKernelGGL((sparse_decode_kernel<T, N, NP, BITS>), dim3(G), dim3(kDecodeThreads), 0, stream, lp, kv, plan, q4,
-                       sel_pages, sel_count, sel_seq_len, sel_stride, o16, lse_out, part_o, part_ml);
-    hipError_t e = hipGetLastError();
-    if (e != hipSuccess) return e;
-    // pieces of the longest list: with few sequences a list is cut into dozens of short ranges
-    int longest = 0;
-    for (int hk = 0; hk < lp.Hkv; ++hk) longest = std::max(longest, plan.first[hk + 1] - plan.first[hk]);
-    const int pieces = plan.quot > 0 ? longest / plan.quot + 2 : 1;
-    if (pieces > 16)
-        hipLaunchKernelGGL((decode_merge_kernel<T, N, 32>), dim3(lp.Hkv, kv.batch), dim3(N * kHeadDim), 0, stream, lp,
-                           plan, o16, lse_out, part_o, part_ml);
-    else
-        hipLaunchKernelGGL((decode_merge_kernel<T, N, 8>), dim3(lp.Hkv, kv.batch), dim3(N * kHeadDim), 0, stream, lp,
-                           plan, o16, lse_out, part_o, part_ml);
+                       sel_pages, sel_count, sel_seq_len, sel_stride, o16, lse_out, ws.part_o, ws.part_ml, ws.arrivals);
     return hipGetLastError();
 }
 
 template <class T, int N>
 hipError_t launch_decode_np(const LayerParams& lp, const PagedParams& kv, const void* q, const int* sel_pages,
                             const int* sel_count, const int* sel_seq_len, int sel_stride, void* out, float* lse_out,
-                            float* part_o, float* part_ml, hipStream_t stream) {
+                            const DecodeScratch& ws, hipStream_t stream) {
 #define LSERVE_DECODE_NP(NPV)                                                                                       \
     case NPV:                                                                                                       \
         return launch_decode_kernels<T, N, NPV, 16>(lp, kv, q, sel_pages, sel_count, sel_seq_len, sel_stride, out,   \
-                                                    lse_out, part_o, part_ml, stream);
+                                                    lse_out, ws, stream);
     if (kv.kv_bits == 8)  // quantised pages are always 64 tokens (checked by the caller)
         return launch_decode_kernels<T, N, 64, 8>(lp, kv, q, sel_pages, sel_count, sel_seq_len, sel_stride, out, lse_out,
-                                                  part_o, part_ml, stream);
+                                                  ws, stream);
     if (kv.kv_bits == 4)
         return launch_decode_kernels<T, N, 64, 4>(lp, kv, q, sel_pages, sel_count, sel_seq_len, sel_stride, out, lse_out,
-                                                  part_o, part_ml, stream);
+                                                  ws, stream);
     switch (lp.NP) {
         LSERVE_DECODE_NP(16)
         LSERVE_DECODE_NP(32)
@@ -919,12 +970,15 @@ template <class T>
 hipError_t launch_decode(const LayerParams& lp, const PagedParams& kv, const void* q, const int* sel_pages,
                          const int* sel_count, const int* sel_seq_len, int sel_stride, void* out, float* lse_out,
                          void* workspace, hipStream_t stream) {
-    float* part_o = reinterpret_cast<float*>(workspace);
-    float* part_ml = part_o + partial_slots(lp, kv.batch) * lp.group * kHeadDim;
+    // arrival counters (one per list, zero between launches), then the pieces
+    DecodeScratch ws;
+    ws.arrivals = reinterpret_cast<unsigned*>(workspace);
+    ws.part_o = reinterpret_cast<float*>(reinterpret_cast<char*>(workspace) + arrival_bytes(lp, kv.batch));
+    ws.part_ml = ws.part_o + partial_slots(lp, kv.batch) * lp.group * kHeadDim;
 #define LSERVE_DECODE_N(NV)                                                                                          \
     case NV:                                                                                                         \
         return launch_decode_np<T, NV>(lp, kv, q, sel_pages, sel_count, sel_seq_len, sel_stride, out, lse_out,       \
-                                       part_o, part_ml, stream);
+                                       ws, stream);
     switch (lp.group) {
         LSERVE_DECODE_N(1)
         LSERVE_DECODE_N(2)
@@ -945,13 +999,14 @@ hipError_t launch_decode(const LayerParams& lp, const PagedParams& kv, const voi
 long long decode_nominal_entries(const LayerParams& lp, int sel_stride) {
     long long acc = 0;
     for (int hk = 0; hk < lp.Hkv; ++hk)
-        acc += ((lp.streaming_mask >> hk) & 1ull) ? (long long)lp.sink_pages + lp.local_pages : (long long)sel_stride + 1;
+        acc += ((lp.streaming_mask >> hk) & 1ull) ? (long long)lp.sink_pages + lp.local_pages + 1  // with the slack entry
+                                                  : (long long)sel_stride + 1;
     return acc;
 }
 
 size_t decode_workspace_bytes(const LayerParams& lp, int batch, int sel_stride) {
     (void)sel_stride;
-    return partial_slots(lp, batch) * lp.group * (kHeadDim + 2) * sizeof(float);
+    return arrival_bytes(lp, batch) + partial_slots(lp, batch) * lp.group * (kHeadDim + 2) * sizeof(float);
 }
 
 hipError_t preload_decode_kernels() {

@@ -62,7 +62,7 @@ class DecodeSession:
         ws_sel = B.lserve_workspace_bytes(B.LSERVE_CALL_SELECT_PAGES, self.desc, batch, max_pages, K, 0)
         ws_dec = B.lserve_workspace_bytes(B.LSERVE_CALL_SPARSE_DECODE, self.desc, batch, max_pages, K, 0)
         self.ws_select = torch.empty((max(ws_sel, 16),), dtype=torch.uint8, device=dev)
-        self.ws_decode = torch.empty((max(ws_dec, 16),), dtype=torch.uint8, device=dev)
+        self.ws_decode = torch.zeros((max(ws_dec, 16),), dtype=torch.uint8, device=dev)  # zero once: arrival counters
         self.out = torch.empty((batch, num_q_heads, head_dim), dtype=dtype, device=dev)
         self.lse = torch.empty((batch, num_q_heads), dtype=torch.float32, device=dev) if want_lse else None
         self.steps_since_selection: Optional[int] = None
