@@ -9,16 +9,21 @@ KV heads 0-3 streaming (128 sink + 512 local tokens), heads 4-7 selecting 64-tok
 A "step" is one decode step of the whole path for the whole batch: when the step opens a reuse chunk,
 the key statistics of the logical pages that received tokens since the last selector run and the page
 selection; on every step the sparse paged decode.
-All inputs are synthetic, seeded, and resident in HBM before the timed region.  The 16-step episode
-is captured once in a HIP graph and replayed; `value` is batch * steps / wall time.
+All inputs are synthetic, seeded, and resident in HBM before the timed region.  Episodes of 16 steps are
+captured in HIP graphs (one more graph holds the remaining steps when --steps is no multiple of 16) and
+replayed; the timed region of exactly --steps steps is repeated --repeats times and `value` is
+batch * steps / the median time.
 
 Extra objects in the JSON line:
-  roofline      sparse decode launch (decode + merge kernel): algorithmic KV bytes per launch / its mean
-                duration inside the timed loop (HIP events around replays of the episode graph with and
-                without the decode calls) against 8 TB/s
-  cpu_baseline  the CPU oracle on the host cores for one reuse chunk of the same workload
-  selector, stats, prefill   per-call timings of the other entry points (prefill on the 64K bf16
-                configuration, against the bf16 MFMA peak)
+  roofline      one lserve_sparse_decode call: algorithmic KV bytes per launch / its mean duration inside the
+                timed loop (HIP events around replays of the episode graph with and without the decode calls)
+                against 8 TB/s; the calls right after a selector run and those that reuse a selection apart;
+                next to it what a library reduction reaches on the same box (measured_read_ceiling_GBs)
+  cpu_baseline  the CPU oracle on the host cores for a bounded sample of the same workload
+  selector, whole_path            the selector run and the whole step against the same 8 TB/s
+  cfg4_256k, cfg4_32k, cfg5       the other decode configurations, compact
+  kv8, kv4, kv_bits_batch64       decode over quantised pages (headline shape; the same layer at batch 64)
+  prefill, append                 cfg3 prefill against the bf16 MFMA peak; KV write-back
 """
 from __future__ import annotations
 
@@ -46,7 +51,11 @@ def parse_args():
     ap.add_argument("--context", type=int, default=0, help="override the context length (cfg2 / cfg4)")
     ap.add_argument("--page-size", type=int, default=0, choices=[0, 16, 32, 64, 128],
                     help="override N_P (N_L = min(16, N_P)); the page-size sweep of the decode path")
+    ap.add_argument("--repeats", type=int, default=5, help="timings of the --steps region; the median is reported")
     ap.add_argument("--no-graph", action="store_true", help="launch eagerly instead of replaying a HIP graph")
+    ap.add_argument("--no-other-configs", action="store_true", help="skip the compact cfg4 / cfg5 objects")
+    ap.add_argument("--other-steps", type=int, default=160, help="timed steps of each secondary decode workload")
+    ap.add_argument("--no-ceiling", action="store_true", help="skip the library copy / reduction ceilings")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-prefill", action="store_true")
     ap.add_argument("--prefill-tokens", type=int, default=65536)
@@ -88,6 +97,213 @@ def read_traffic(workload: str):
     return float(m.group(1)) if m else None
 
 
+def _median(xs):
+    xs = sorted(xs)
+    n = len(xs)
+    return xs[n // 2] if n % 2 else 0.5 * (xs[n // 2 - 1] + xs[n // 2])
+
+
+def _event_ms(torch, fn, reps):
+    """Mean duration of fn() over `reps` back-to-back calls, HIP events on the stream the work is launched on."""
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    fn()
+    torch.cuda.synchronize()
+    e0.record()
+    for _ in range(reps):
+        fn()
+    e1.record()
+    torch.cuda.synchronize()
+    return e0.elapsed_time(e1) / reps
+
+
+class DecodeLoop:
+    """A decode workload resident in HBM with its episode captured in HIP graphs.
+
+    Graphs: the whole episode; the first `r` steps of an episode for any remainder r a run needs; the episode
+    without its decode calls; the episode with only the decode calls that directly follow a selector run.
+    Differences between their replay times give the duration of the decode calls inside the very loop that is
+    timed, split into calls right after a selector run (which has just swept the statistics through the
+    last-level cache) and calls that reuse the selection (which re-read pages the previous call read).
+    """
+
+    def __init__(self, torch, L, dev, w, use_graph=True):
+        from paper_2502_14866_amd.session import DecodeSession
+        from workloads import make_decode_inputs
+
+        self.torch, self.L, self.w, self.use_graph = torch, L, w, use_graph
+        t0 = time.time()
+        self.inp = inp = make_decode_inputs(w, device=dev)
+        torch.cuda.synchronize()
+        self.generate_s = time.time() - t0
+        self.E, self.C, self.B = w.decode_steps, w.reuse_interval, w.batch
+        self.sess = DecodeSession(inp.k_pool, inp.v_pool, inp.page_table, w.num_q_heads, w.streaming_flags(),
+                                  w.sink_tokens, w.local_tokens, w.budget_tokens,
+                                  logical_page_size=w.logical_page_size, reuse_interval=self.C)
+        # lengths for every episode position, rows padded to 16 bytes; row t = length before step t
+        pad = (self.B + 3) // 4 * 4
+        self.len_table = torch.zeros((self.E + 1, pad), dtype=torch.int32, device=dev)
+        for t in range(self.E + 1):
+            self.len_table[t, :self.B] = inp.prompt_lens + t
+        self.sess.set_seq_lens(self.len_table[0, :self.B])
+        self.sess.build_stats_full()
+        torch.cuda.synchronize()
+        self._graphs = {}
+        self.episode()  # eager warm-up of every kernel before any capture
+        torch.cuda.synchronize()
+
+    def episode(self, steps=None, decode="all"):
+        """decode: "all", "none", or "first" (only the calls right after a selector run)."""
+        sess, inp, lt, B = self.sess, self.inp, self.len_table, self.B
+        sess.restart()
+        for t in range(self.E if steps is None else steps):
+            run = decode == "all" or (decode == "first" and t % self.C == 0)
+            sess.step(inp.q[t], lt[t + 1, :B], lt[t, :B], run_decode=run)
+
+    def runner(self, steps=None, decode="all"):
+        """A callable that runs the (partial) episode: a graph replay, or the eager launches with --no-graph."""
+        if not self.use_graph:
+            return lambda: self.episode(steps, decode)
+        key = (steps, decode)
+        if key not in self._graphs:
+            torch = self.torch
+            self.episode(steps, decode)
+            torch.cuda.synchronize()
+            g = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(g):
+                self.episode(steps, decode)
+            torch.cuda.synchronize()
+            self._graphs[key] = g
+        return self._graphs[key].replay
+
+    def run_steps(self, n):
+        full, rest = divmod(n, self.E)
+        whole = self.runner()
+        for _ in range(full):
+            whole()
+        if rest:
+            self.runner(rest)()
+
+    def timed_steps(self, steps, warmup, repeats):
+        """`repeats` timings of exactly `steps` steps, each bracketed by a device synchronisation."""
+        torch = self.torch
+        self.runner()
+        if steps % self.E:
+            self.runner(steps % self.E)
+        if warmup % self.E:
+            self.runner(warmup % self.E)
+        self.run_steps(warmup)
+        torch.cuda.synchronize()
+        samples = []
+        for _ in range(repeats):
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            self.run_steps(steps)
+            torch.cuda.synchronize()
+            samples.append(time.perf_counter() - t0)
+        return samples
+
+    def call_times(self, reps):
+        """(episode ms, episode without decode ms, decode call ms: mean / first after selection / reusing)."""
+        torch, E, C = self.torch, self.E, self.C
+        full = _event_ms(torch, self.runner(None, "all"), reps)
+        none = _event_ms(torch, self.runner(None, "none"), reps)
+        first = _event_ms(torch, self.runner(None, "first"), reps)
+        n_first = (E + C - 1) // C
+        return {
+            "episode_ms": full,
+            "episode_without_decode_ms": none,
+            "decode_call_ms": (full - none) / E,
+            "decode_call_first_after_selection_ms": (first - none) / n_first,
+            "decode_call_reusing_selection_ms": (full - first) / max(1, E - n_first),
+            "selector_run_ms": none / n_first,
+        }
+
+    def algorithmic_bytes(self):
+        """Mean bytes and pages per decode launch of an episode, and the statistics bytes of a selector run."""
+        w, sess, inp, lt, B = self.w, self.sess, self.inp, self.len_table, self.B
+        nbytes, npages = [], []
+        sess.restart()
+        for t in range(self.E):
+            sess.step(inp.q[t], lt[t + 1, :B], lt[t, :B])
+            nb, npg = decode_bytes_per_launch(w, lt[t + 1, :B].cpu(), sess.sel_count.cpu(), sess.sel_seq_len.cpu())
+            nbytes.append(nb)
+            npages.append(npg)
+        n_sel = sum(1 for f in w.streaming_flags() if not f)
+        stats = 0
+        for b in range(B):
+            P = -(-int(inp.prompt_lens[b]) // w.page_size)
+            stats += P * n_sel * (w.page_size // w.logical_page_size) * 2 * w.head_dim * 2
+        return sum(nbytes) / len(nbytes), sum(npages) / len(npages), stats
+
+
+def describe(w, inp):
+    return (f"{w.name}: decode only, batch {w.batch}, {w.num_q_heads}/{w.num_kv_heads} heads x {w.head_dim}, "
+            f"context {int(inp.prompt_lens.min())}" + (f"..{int(inp.prompt_lens.max())}" if inp.prompt_lens.min() != inp.prompt_lens.max() else "")
+            + f", {len(w.streaming_kv_heads)} streaming KV heads ({w.sink_tokens} sink + {w.local_tokens} local), "
+            f"budget {w.budget_tokens}, N_P {w.page_size}, N_L {w.logical_page_size}, reuse interval {w.reuse_interval}, "
+            f"{w.decode_steps}-step episodes")
+
+
+def measure_loop(loop, steps, warmup, repeats):
+    """Throughput of the whole path and the roofline figures of its kernels for one decode workload."""
+    w, B, E, C = loop.w, loop.B, loop.E, loop.C
+    samples = loop.timed_steps(steps, warmup, repeats)
+    elapsed = _median(samples)
+    calls = loop.call_times(max(4, min(40, steps // E)))
+    alg_bytes, pages, stats_bytes = loop.algorithmic_bytes()
+    dec_ms = calls["decode_call_ms"]
+    sel_ms = calls["selector_run_ms"]
+    step_bytes = alg_bytes + stats_bytes * ((E + C - 1) // C) / E
+    gbs = lambda nbytes, ms: nbytes / (ms * 1e-3) / 1e9 if ms and ms > 0 else None  # noqa: E731
+    return {
+        "tokens_per_s": B * steps / elapsed,
+        "ms_per_step": elapsed / steps * 1e3,
+        "ms_per_step_samples": [s / steps * 1e3 for s in samples],
+        "calls": calls,
+        "decode": {"algorithmic_bytes_per_launch": alg_bytes, "pages_per_launch": pages,
+                   "achieved_GBs": gbs(alg_bytes, dec_ms), "frac_of_hbm_peak": gbs(alg_bytes, dec_ms) / HBM_PEAK_GBS},
+        "selector": {"stats_bytes_per_run": stats_bytes, "achieved_GBs": gbs(stats_bytes, sel_ms),
+                     "frac_of_hbm_peak": gbs(stats_bytes, sel_ms) / HBM_PEAK_GBS},
+        "whole_path": {"algorithmic_bytes_per_step": step_bytes,
+                       "achieved_GBs": step_bytes / (elapsed / steps) / 1e9,
+                       "frac_of_hbm_peak": step_bytes / (elapsed / steps) / 1e9 / HBM_PEAK_GBS},
+    }
+
+
+def compact(loop, m):
+    """The figures of a secondary workload in one flat object."""
+    c = m["calls"]
+    return {
+        "workload": describe(loop.w, loop.inp),
+        "tokens_per_s": m["tokens_per_s"], "us_per_step": m["ms_per_step"] * 1e3,
+        "decode_call_us": c["decode_call_ms"] * 1e3,
+        "decode_call_first_after_selection_us": c["decode_call_first_after_selection_ms"] * 1e3,
+        "decode_call_reusing_selection_us": c["decode_call_reusing_selection_ms"] * 1e3,
+        "selector_run_us": c["selector_run_ms"] * 1e3,
+        "decode_bytes_per_launch": m["decode"]["algorithmic_bytes_per_launch"],
+        "decode_GBs": m["decode"]["achieved_GBs"], "decode_frac_of_hbm_peak": m["decode"]["frac_of_hbm_peak"],
+        "selector_bytes_per_run": m["selector"]["stats_bytes_per_run"],
+        "selector_GBs": m["selector"]["achieved_GBs"], "selector_frac_of_hbm_peak": m["selector"]["frac_of_hbm_peak"],
+        "whole_step_frac_of_hbm_peak": m["whole_path"]["frac_of_hbm_peak"],
+    }
+
+
+def measured_read_ceiling(torch, dev):
+    """What plain library kernels reach on this machine: a reduction (read only) and a copy (read + write) over the
+    working-set size of one decode launch and over 4 GB, in GB/s of bytes moved."""
+    out = {}
+    for label, nbytes in (("155MB", 155 << 20), ("4GB", 4 << 30)):
+        x = torch.empty((nbytes // 4,), dtype=torch.float32, device=dev).normal_()
+        y = torch.empty_like(x)
+        red = _event_ms(torch, lambda: torch.sum(x), 10)
+        cp = _event_ms(torch, lambda: y.copy_(x), 10)
+        out[f"reduction_{label}_GBs"] = nbytes / (red * 1e-3) / 1e9
+        out[f"copy_{label}_GBs"] = 2 * nbytes / (cp * 1e-3) / 1e9
+        del x, y
+    torch.cuda.empty_cache()
+    return out
+
+
 def main():
     args = parse_args()
     if args.gpus != 1:
@@ -98,8 +314,7 @@ def main():
     import torch
 
     import paper_2502_14866_amd as L
-    from paper_2502_14866_amd.session import DecodeSession
-    from workloads import get_config, make_decode_inputs, make_prefill_inputs
+    from workloads import get_config
 
     if not os.path.exists(L.library_path()):
         from paper_2502_14866_amd.build import build_library
@@ -108,6 +323,7 @@ def main():
     L.load_library()
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
+    L.lserve_init()
 
     over = {}
     if args.context:
@@ -116,186 +332,107 @@ def main():
         over["page_size"] = args.page_size
         over["logical_page_size"] = min(16, args.page_size)
     w = get_config(args.workload, **over)
-    t0 = time.time()
-    inp = make_decode_inputs(w, device=dev)
-    torch.cuda.synchronize()
-    gen_s = time.time() - t0
-    E = w.decode_steps  # episode length
-    C = w.reuse_interval
-    B = w.batch
-
-    sess = DecodeSession(inp.k_pool, inp.v_pool, inp.page_table, w.num_q_heads, w.streaming_flags(),
-                         w.sink_tokens, w.local_tokens, w.budget_tokens, logical_page_size=w.logical_page_size,
-                         reuse_interval=C)
-    # lengths for every episode position, rows padded to 16 bytes; row t = length before step t
-    pad = (B + 3) // 4 * 4
-    len_table = torch.zeros((E + 1, pad), dtype=torch.int32, device=dev)
-    for t in range(E + 1):
-        len_table[t, :B] = inp.prompt_lens + t
-    sess.set_seq_lens(len_table[0, :B])
-    sess.build_stats_full()
-    torch.cuda.synchronize()
-
-    def episode():
-        sess.restart()
-        for t in range(E):
-            sess.step(inp.q[t], len_table[t + 1, :B], len_table[t, :B])
+    loop = DecodeLoop(torch, L, dev, w, use_graph=not args.no_graph)
+    inp, sess, len_table = loop.inp, loop.sess, loop.len_table
 
     if args.profile_only:
         run_profile_only(args, torch, L, sess, inp, len_table, w, dev)
         return
 
-    episode()  # eager warm-up of every kernel (first-use module load must not land in a capture)
-    torch.cuda.synchronize()
-    graph = None
-    if not args.no_graph:
-        graph = torch.cuda.CUDAGraph()
-        with torch.cuda.graph(graph):
-            episode()
-        torch.cuda.synchronize()
-
-    def run_steps(n):
-        full, rest = divmod(n, E)
-        for _ in range(full):
-            graph.replay() if graph is not None else episode()
-        if rest:  # a partial episode is launched eagerly
-            sess.restart()
-            for t in range(rest):
-                sess.step(inp.q[t], len_table[t + 1, :B], len_table[t, :B])
-
-    run_steps(args.warmup)
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    run_steps(args.steps)
-    torch.cuda.synchronize()
-    elapsed = time.perf_counter() - t0
-    tokens_per_s = B * args.steps / elapsed
-
-    # ---- duration of the decode launches inside the timed loop (HIP events on the launch stream) ----
-    # The same episode is captured once more without its lserve_sparse_decode calls; the difference of
-    # the two replays, both bracketed by events on the stream the kernels run on, is the time the 16
-    # decode launches (decode + merge kernel) take in the very loop that `value` times.
-    def episode_without_decode():
-        sess.restart()
-        for t in range(E):
-            sess.step(inp.q[t], len_table[t + 1, :B], len_table[t, :B], run_decode=False)
-
-    def timed(fn, reps):
-        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        fn()
-        torch.cuda.synchronize()
-        e0.record()
-        for _ in range(reps):
-            fn()
-        e1.record()
-        torch.cuda.synchronize()
-        return e0.elapsed_time(e1) / reps
-
-    reps = max(4, min(40, args.steps // E))
-    if graph is not None:
-        graph_nd = torch.cuda.CUDAGraph()
-        episode_without_decode()
-        torch.cuda.synchronize()
-        with torch.cuda.graph(graph_nd):
-            episode_without_decode()
-        torch.cuda.synchronize()
-        full_ms = timed(graph.replay, reps)
-        rest_ms = timed(graph_nd.replay, reps)
-    else:
-        full_ms = timed(episode, reps)
-        rest_ms = timed(episode_without_decode, reps)
-    dec_mean_ms = (full_ms - rest_ms) / E
-    sel_runs = E // C
-    sel_mean_ms = rest_ms / sel_runs  # statistics refresh + scoring + top-K of one selector run
-
-    # algorithmic bytes of every decode launch of an episode (needs the selections: one eager episode)
-    bytes_per_launch, pages_per_launch = [], []
-    sess.restart()
-    for t in range(E):
-        sess.step(inp.q[t], len_table[t + 1, :B], len_table[t, :B])
-        nbytes, npages = decode_bytes_per_launch(w, len_table[t + 1, :B].cpu(), sess.sel_count.cpu(),
-                                                 sess.sel_seq_len.cpu())
-        bytes_per_launch.append(nbytes)
-        pages_per_launch.append(npages)
-    mean = lambda xs: sum(xs) / max(1, len(xs))  # noqa: E731
-    alg_bytes = mean(bytes_per_launch)
-    achieved = alg_bytes / (dec_mean_ms * 1e-3) / 1e9
+    m = measure_loop(loop, args.steps, args.warmup, args.repeats)
+    calls = m["calls"]
     traffic = read_traffic(w.name)
-
-    stats_bytes_run = 0
-    flags = w.streaming_flags()
-    n_sel = sum(1 for f in flags if not f)
-    for b in range(B):
-        P = -(-int(inp.prompt_lens[b]) // w.page_size)
-        stats_bytes_run += P * n_sel * (w.page_size // w.logical_page_size) * 2 * w.head_dim * 2
     result = {
         "metric": "sparse decode tokens/s at 32K context (decode + amortised page selection + stats update)",
-        "value": tokens_per_s,
+        "value": m["tokens_per_s"],
         "unit": "tokens/s",
         "n_gpus": 1,
         "steps": args.steps,
         "warmup": args.warmup,
-        "ms_per_step": elapsed / args.steps * 1e3,
+        "ms_per_step": m["ms_per_step"],
         "higher_is_better": True,
         "scaling": "weak",
         "vs_baseline": None,
         "dtype": "f16",
         "data": "synthetic",
         "config": {
-            "workload": f"{w.name}: decode only, batch {B}, {w.num_q_heads}/{w.num_kv_heads} heads x {w.head_dim}, "
-                        f"context {int(inp.prompt_lens.max())}, {len(w.streaming_kv_heads)} streaming KV heads "
-                        f"({w.sink_tokens} sink + {w.local_tokens} local), budget {w.budget_tokens}, "
-                        f"N_P {w.page_size}, N_L {w.logical_page_size}, reuse interval {C}, {E}-step episodes",
-            "launch": "eager" if graph is None else "hip graph of one episode",
-            "generate_s": round(gen_s, 2),
+            "workload": describe(w, inp),
+            "launch": "eager" if args.no_graph else "hip graphs: whole episodes plus one graph for the remaining steps",
+            "timing": f"median of {args.repeats} timings of {args.steps} steps each (all in ms_per_step_samples)",
+            "generate_s": round(loop.generate_s, 2),
         },
+        "ms_per_step_samples": m["ms_per_step_samples"],
         "roofline": {
             "bound": "hbm",
-            "kernel": "sparse_decode_kernel + decode_merge_kernel (one lserve_sparse_decode call)",
-            "achieved": achieved,
+            "kernel": "sparse_decode_kernel (one lserve_sparse_decode call; the pieces of cut lists are folded inside it)",
+            "achieved": m["decode"]["achieved_GBs"],
             "peak": HBM_PEAK_GBS,
             "unit": "GB/s",
-            "frac": achieved / HBM_PEAK_GBS,
+            "frac": m["decode"]["frac_of_hbm_peak"],
             "traffic": traffic,
-            "algorithmic_bytes_per_launch": alg_bytes,
-            "pages_per_launch": mean(pages_per_launch),
-            "launch_ms": dec_mean_ms,
-            "episode_ms": full_ms,
-            "episode_without_decode_ms": rest_ms,
+            "traffic_source": "profiles/sparse_decode_cfg2_traffic.txt (rocprofv3 counters of a separate run)" if traffic else None,
+            "algorithmic_bytes_per_launch": m["decode"]["algorithmic_bytes_per_launch"],
+            "pages_per_launch": m["decode"]["pages_per_launch"],
+            "launch_ms": calls["decode_call_ms"],
+            "launch_ms_first_after_selection": calls["decode_call_first_after_selection_ms"],
+            "launch_ms_reusing_selection": calls["decode_call_reusing_selection_ms"],
+            "episode_ms": calls["episode_ms"],
+            "episode_without_decode_ms": calls["episode_without_decode_ms"],
         },
         "selector": {
-            "ms_per_run": sel_mean_ms,
+            "ms_per_run": calls["selector_run_ms"],
             "kernels": "page_score_kernel (rebuilds the stale tail statistics itself) + topk_pages_kernel",
-            "stats_bytes_per_run": stats_bytes_run,
-            "achieved_GBs": stats_bytes_run / (sel_mean_ms * 1e-3) / 1e9 if sel_mean_ms else None,
-            "frac_of_hbm_peak": stats_bytes_run / (sel_mean_ms * 1e-3) / 1e9 / HBM_PEAK_GBS if sel_mean_ms else None,
+            "stats_bytes_per_run": m["selector"]["stats_bytes_per_run"],
+            "achieved_GBs": m["selector"]["achieved_GBs"],
+            "frac_of_hbm_peak": m["selector"]["frac_of_hbm_peak"],
         },
-        "whole_path": {
-            "algorithmic_bytes_per_step": (mean(bytes_per_launch) * E + stats_bytes_run * (E // C)) / E,
-            "achieved_GBs": (mean(bytes_per_launch) * E + stats_bytes_run * (E // C)) / E / (elapsed / args.steps) / 1e9,
-            "frac_of_hbm_peak": (mean(bytes_per_launch) * E + stats_bytes_run * (E // C)) / E / (elapsed / args.steps) / 1e9
-            / HBM_PEAK_GBS,
-        },
+        "whole_path": m["whole_path"],
     }
+    if not args.no_ceiling:
+        try:
+            ceiling = measured_read_ceiling(torch, dev)
+            result["roofline"]["measured_read_ceiling_GBs"] = ceiling["reduction_155MB_GBs"]
+            result["roofline"]["frac_of_measured_read_ceiling"] = m["decode"]["achieved_GBs"] / ceiling["reduction_155MB_GBs"]
+            result["measured_ceilings"] = ceiling
+        except Exception as e:  # the decode line must still be printed
+            result["measured_ceilings"] = {"error": repr(e)}
 
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(torch, w, inp)
-    if not args.no_prefill:
-        try:
-            result["prefill"] = bench_prefill(torch, L, dev, args.prefill_tokens)
-        except Exception as e:  # the decode line must still be printed
-            result["prefill"] = {"error": repr(e)}
-    if not args.no_append:
-        try:
-            result["append"] = bench_append(torch, L, dev, args.prefill_tokens, w)
-        except Exception as e:
-            result["append"] = {"error": repr(e)}
     if not args.no_kv8 and w.page_size == 64:
         try:
             result["kv8"] = bench_quantised(torch, L, dev, w, inp, sess, len_table, 8)
             result["kv4"] = bench_quantised(torch, L, dev, w, inp, sess, len_table, 4)
         except Exception as e:
             result["kv8"] = {"error": repr(e)}
+    # the other decode configurations, each in its own compact object (the main workload's memory is released first)
+    del loop, inp, sess, len_table
+    torch.cuda.empty_cache()
+    if not args.no_other_configs and args.workload == "cfg2" and not over:
+        for key, name, kw in (("cfg4_256k", "cfg4", {}), ("cfg4_32k", "cfg4", {"context": 32768}), ("cfg5", "cfg5", {})):
+            try:
+                other = DecodeLoop(torch, L, dev, get_config(name, **kw), use_graph=not args.no_graph)
+                result[key] = compact(other, measure_loop(other, args.other_steps, 32, 3))
+                del other
+            except Exception as e:
+                result[key] = {"error": repr(e)}
+            torch.cuda.empty_cache()
+        if not args.no_kv8:
+            try:
+                result["kv_bits_batch64"] = bench_quantised_large(torch, L, dev)
+            except Exception as e:
+                result["kv_bits_batch64"] = {"error": repr(e)}
+            torch.cuda.empty_cache()
+    if not args.no_prefill:
+        try:
+            result["prefill"] = bench_prefill(torch, L, dev, args.prefill_tokens)
+        except Exception as e:
+            result["prefill"] = {"error": repr(e)}
+    if not args.no_append:
+        try:
+            result["append"] = bench_append(torch, L, dev, args.prefill_tokens, w)
+        except Exception as e:
+            result["append"] = {"error": repr(e)}
     print(json.dumps(result))
 
 
@@ -574,6 +711,46 @@ def bench_quantised(torch, L, dev, w, inp, sess, len_table, bits):
                                   "achieved_GBs": wb_bytes / (wb_ms * 1e-3) / 1e9},
         "note": "not part of `value`",
     }
+
+
+def bench_quantised_large(torch, L, dev, batch=64):
+    """The decode launch over 16-, 8- and 4-bit pages where the fixed part of a launch is amortised: the headline
+    shape at four times the batch (one selection, eager launches, HIP events)."""
+    from paper_2502_14866_amd.session import DecodeSession
+    from workloads import get_config, make_decode_inputs
+
+    w = get_config("cfg2", batch=batch)
+    inp = make_decode_inputs(w, device=dev)
+    B = w.batch
+    sess = DecodeSession(inp.k_pool, inp.v_pool, inp.page_table, w.num_q_heads, w.streaming_flags(), w.sink_tokens,
+                         w.local_tokens, w.budget_tokens, logical_page_size=w.logical_page_size,
+                         reuse_interval=w.reuse_interval)
+    lens = torch.zeros(((B + 3) // 4 * 4,), dtype=torch.int32, device=dev)
+    lens[:B] = inp.prompt_lens
+    sess.set_seq_lens(lens[:B])
+    sess.build_stats_full()
+    q = inp.q[0]
+    sess.select(q)
+    out = torch.empty_like(sess.out)
+    res = {"workload": f"cfg2's layer at batch {B}: one decode launch per cache width on the same selection"}
+    _, pages = decode_bytes_per_launch(w, lens[:B].cpu(), sess.sel_count.cpu(), sess.sel_seq_len.cpu())
+    ms16 = None
+    for bits in (16, 8, 4):
+        if bits == 16:
+            kv, slab = L.PagedKV(inp.k_pool, inp.v_pool, sess.stats, inp.page_table, lens[:B]), 2 * w.page_size * w.head_dim
+        else:
+            kv, slab, _, _, _ = quantised_cache(torch, L, dev, w, inp, sess, bits)
+        ms = _event_ms(torch, lambda: L.lserve_sparse_decode(sess.desc, kv, q, sess.sel_pages, sess.sel_count,
+                                                             sess.sel_seq_len, out, None, sess.ws_decode), 100)
+        nbytes = pages * 2 * slab + 2 * B * w.num_q_heads * w.head_dim * 2 + pages * 8
+        ms16 = ms if bits == 16 else ms16
+        res[f"kv{bits}"] = {"decode_launch_ms": ms, "algorithmic_bytes_per_launch": nbytes,
+                            "achieved_GBs": nbytes / (ms * 1e-3) / 1e9,
+                            "frac_of_hbm_peak": nbytes / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
+                            "speedup_over_16bit": ms16 / ms}
+        del kv
+        torch.cuda.empty_cache()
+    return res
 
 
 def run_profile_only(args, torch, L, sess, inp, len_table, w, dev):

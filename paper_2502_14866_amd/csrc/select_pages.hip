@@ -5,9 +5,10 @@
 // Scoring is a bandwidth-bound scan of the statistics (2 KiB per page and head for N_P = 64,
 // N_L = 16): 16 lanes read the max row and the min row of one logical page with 16-byte loads.
 // Because kmax >= kmin, max(q*kmax, q*kmin) = max(q,0)*kmax + min(q,0)*kmin, so each channel costs
-// two packed dot-product lanes and no compare.  Top-K is a 4-pass radix select on an order-
-// preserving integer image of the fp32 score, followed by an index-ordered compaction, so the
-// output is ascending and ties resolve to the lower page index.
+// two packed dot-product lanes and no compare.  Top-K ranks an order-preserving integer image of the
+// fp32 score: lists of up to 8192 candidates from registers, on ballots alone; longer ones from memory
+// with a 4-pass radix select.  Both emit in index order, so the output is ascending and ties resolve
+// to the lower page index.
 #include "kernels.h"
 
 namespace lserve {
@@ -303,6 +304,126 @@ __global__ __launch_bounds__(kTopkThreads) void topk_pages_kernel(LayerParams lp
     }
 }
 
+// The same selection on ballots alone, for lists of up to 64 * KPL * WAVES candidate pages: WAVES wavefronts share
+// a list, each keeping the keys of 64 * KPL consecutive pages in registers (lane l holds pages l, l + 64, ... of
+// its wavefront's stretch).  The key of the (K - 1)-th best candidate is found bit by bit from the top (the largest
+// t with at least K - 1 keys >= t): a step is one compare and one ballot per register and, with more than one
+// wavefront, one barrier to add up their counts.  Nothing is histogrammed, so keys that agree in their leading
+// bytes (page scores do: same sign, neighbouring exponents) cost nothing extra, where shared-memory atomics on a
+// few hot buckets serialise.  Candidates above the threshold are taken, those equal to it in index order until the
+// budget is full; a ballot per row of 64 pages places every taken page, so the output is ascending.
+template <int KPL, int WAVES>
+__global__ __launch_bounds__(kWave* WAVES) void topk_pages_ballot_kernel(LayerParams lp, PagedParams kv, int K,
+                                                                         const float* __restrict__ scores,
+                                                                         float* __restrict__ user_scores,
+                                                                         int* __restrict__ sel_pages,
+                                                                         int* __restrict__ sel_count,
+                                                                         int* __restrict__ sel_seq_len) {
+    __shared__ int counts[2][WAVES];     // per-wavefront counts of a search step, double buffered
+    __shared__ int above_eq[2][WAVES];   // per-wavefront candidates above / equal to the threshold
+    const int lane = threadIdx.x % kWave, wave = threadIdx.x / kWave, tid = threadIdx.x;
+    const int list = blockIdx.x;
+    const int b = list / lp.Hkv, hk = list % lp.Hkv;
+    const int L = kv.seq_lens[b];
+    const int P = ceil_div(L, lp.NP);
+    int* out = sel_pages + (size_t)list * K;
+    if (hk == 0 && tid == 0) sel_seq_len[b] = L;
+
+    if ((lp.streaming_mask >> hk) & 1ull) {  // streaming heads take no selection
+        for (int i = tid; i < K; i += kWave * WAVES) out[i] = -1;
+        if (user_scores)
+            for (int i = tid; i < kv.max_pages; i += kWave * WAVES) user_scores[(size_t)list * kv.max_pages + i] = 0.f;
+        if (tid == 0) sel_count[list] = 0;
+        return;
+    }
+    if (P <= K) {  // the budget covers the whole context
+        for (int i = tid; i < K; i += kWave * WAVES) out[i] = i < P ? i : -1;
+        if (tid == 0) sel_count[list] = P;
+        return;
+    }
+
+    const float* sc = scores + (size_t)list * kv.max_pages;
+    const int M = P - 1;  // candidates: every page but the newest, which is always kept
+    const int first = wave * (KPL * kWave) + lane;  // this lane's pages: first, first + 64, ...
+    // All loads first and without conditions (a guarded load is a branch, and the loads would then be waited for
+    // one by one); rows past the end read the last candidate again and are blanked afterwards.
+    float raw[KPL];
+#pragma unroll
+    for (int j = 0; j < KPL; ++j) raw[j] = sc[min(first + kWave * j, M - 1)];
+    unsigned key[KPL];  // 0 stands for "no page": below the key of every number
+#pragma unroll
+    for (int j = 0; j < KPL; ++j) key[j] = first + kWave * j < M ? orderable(raw[j]) : 0u;
+
+    // sum over the wavefronts of the list of a count every lane of a wavefront agrees on
+    auto all_waves = [&](int mine, int (*slots)[WAVES], int phase) {
+        if (WAVES == 1) return mine;
+        if (lane == 0) slots[phase & 1][wave] = mine;
+        __syncthreads();
+        int total = 0;
+#pragma unroll
+        for (int w = 0; w < WAVES; ++w) total += slots[phase & 1][w];
+        return total;
+    };
+
+    const int need = K - 1;
+    unsigned threshold = 0xffffffffu;
+    int need_eq = 0;
+    if (need > 0) {
+        unsigned prefix = 0;
+        for (int bit = 31; bit >= 0; --bit) {
+            const unsigned t = prefix | (1u << bit);
+            int at_least = 0;
+#pragma unroll
+            for (int j = 0; j < KPL; ++j) at_least += __popcll(__ballot(key[j] >= t));
+            if (all_waves(at_least, counts, bit) >= need) prefix = t;
+        }
+        threshold = prefix;
+    }
+    int above = 0, equal = 0;
+#pragma unroll
+    for (int j = 0; j < KPL; ++j) {
+        above += __popcll(__ballot(key[j] > threshold));
+        equal += __popcll(__ballot(first + kWave * j < M && key[j] == threshold));
+    }
+    // candidates of the wavefronts before this one: those above the threshold, and those equal to it
+    int above_before = 0, equal_before = 0, above_all = above;
+    if (WAVES > 1) {
+        if (lane == 0) {
+            above_eq[0][wave] = above;
+            above_eq[1][wave] = equal;
+        }
+        __syncthreads();
+        above_all = 0;
+#pragma unroll
+        for (int w = 0; w < WAVES; ++w) {
+            above_all += above_eq[0][w];
+            if (w < wave) {
+                above_before += above_eq[0][w];
+                equal_before += above_eq[1][w];
+            }
+        }
+    }
+    if (need > 0) need_eq = need - above_all;  // candidates equal to the threshold still to take, lowest indices first
+    const unsigned long long lower_lanes = (1ull << lane) - 1ull;
+    int taken = above_before + min(equal_before, need_eq), eq_seen = equal_before;
+#pragma unroll
+    for (int j = 0; j < KPL; ++j) {
+        const int i = first + kWave * j;
+        const bool is_eq = i < M && key[j] == threshold;
+        const unsigned long long eq_row = __ballot(is_eq);
+        const bool take = i < M && (key[j] > threshold || (is_eq && eq_seen + __popcll(eq_row & lower_lanes) < need_eq));
+        const unsigned long long take_row = __ballot(take);
+        const int pos = taken + __popcll(take_row & lower_lanes);
+        if (take && pos < K - 1) out[pos] = i;  // the bound only matters for non-finite scores
+        taken += __popcll(take_row);
+        eq_seen += __popcll(eq_row);
+    }
+    if (tid == 0) {
+        out[K - 1] = P - 1;
+        sel_count[list] = K;
+    }
+}
+
 template <class T>
 hipError_t launch_score(const LayerParams& lp, const PagedParams& kv, const void* q, const int* stats_valid_len,
                         float* scores, const HeadList& selecting, hipStream_t stream) {
@@ -350,9 +471,24 @@ hipError_t launch_select_pages(int dtype, const LayerParams& lp, const PagedPara
                                   : launch_score<BF16>(lp, kv, q, stats_valid_len, scores, selecting, stream);
         if (e != hipSuccess) return e;
     }
-    dim3 grid(lp.Hkv, kv.batch);
-    hipLaunchKernelGGL(topk_pages_kernel, grid, dim3(kTopkThreads), 0, stream, lp, kv, budget_pages, scores,
-                       scores_is_user_buffer ? scores : nullptr, sel_pages, sel_count, sel_seq_len);
+    float* user_scores = scores_is_user_buffer ? scores : nullptr;
+    const int candidates = kv.max_pages - 1;  // no list has more
+#define LSERVE_TOPK_BALLOT(KPL, WAVES)                                                                                  \
+    hipLaunchKernelGGL((topk_pages_ballot_kernel<KPL, WAVES>), dim3(kv.batch * lp.Hkv), dim3(kWave * WAVES), 0, stream, \
+                       lp, kv, budget_pages, scores, user_scores, sel_pages, sel_count, sel_seq_len)
+    if (candidates <= kWave * 4) {
+        LSERVE_TOPK_BALLOT(4, 1);
+    } else if (candidates <= kWave * 8) {
+        LSERVE_TOPK_BALLOT(8, 1);
+    } else if (candidates <= kWave * 8 * 4) {
+        LSERVE_TOPK_BALLOT(8, 4);
+    } else if (candidates <= kWave * 16 * 8) {
+        LSERVE_TOPK_BALLOT(16, 8);
+    } else {  // beyond 8192 candidate pages the keys stay in memory
+        hipLaunchKernelGGL(topk_pages_kernel, dim3(lp.Hkv, kv.batch), dim3(kTopkThreads), 0, stream, lp, kv, budget_pages,
+                           scores, user_scores, sel_pages, sel_count, sel_seq_len);
+    }
+#undef LSERVE_TOPK_BALLOT
     return hipGetLastError();
 }
 
