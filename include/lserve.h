@@ -226,7 +226,8 @@ int lserve_select_pages(const lserve_attn_desc *desc, const lserve_paged_kv *kv,
  *   max_seqlen   host: upper bound of the sequence lengths (sizes the launch)
  *   out          device [total_tokens][H][D]
  *   lse_out      device [H][total_tokens] fp32 or NULL: natural-log sum of exp of the scaled scores
- *   workspace    device, >= lserve_workspace_bytes(LSERVE_CALL_SPARSE_PREFILL, ...) (may be 0 bytes)
+ *   workspace    unused: lserve_workspace_bytes(LSERVE_CALL_SPARSE_PREFILL, ...) is 0 (Q, K and V are read where
+ *                they are); NULL is accepted
  * Requires desc->page_size == 64 (the mask tile).
  */
 int lserve_sparse_prefill(const lserve_attn_desc *desc, const void *q, const void *k, const void *v,
@@ -247,7 +248,8 @@ int lserve_sparse_prefill(const lserve_attn_desc *desc, const void *q, const voi
  *   q            device [total_new][H][D], cu_q device [batch + 1] (batch = kv->batch), n_b >= 0
  *   max_new_per_seq  host bound of n_b (> 0); max_seqlen host bound of L_b
  *   out          device [total_new][H][D]; lse_out device [H][total_new] fp32 or NULL
- *   workspace    device, >= lserve_paged_prefill_workspace_bytes(desc, batch, max_pages_per_seq)
+ *   workspace    unused: lserve_paged_prefill_workspace_bytes() is 0 (keys and values are read from the pages as
+ *                they are); NULL is accepted
  */
 int lserve_sparse_prefill_paged(const lserve_attn_desc *desc, const lserve_paged_kv *kv, const void *q,
                                 const int32_t *cu_q, int32_t total_new, int32_t max_new_per_seq,

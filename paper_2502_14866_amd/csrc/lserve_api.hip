@@ -226,7 +226,7 @@ int prefill_impl(const lserve_attn_desc* desc, const lserve_block_mask* mask, co
         ma.nnz = mask->nnz;
         need = masked_prefill_workspace_bytes(lp, total_tokens, batch, max_seqlen, mask->num_masks, mask->nnz);
     }
-    if (!workspace || workspace_bytes < need) return LSERVE_ERR_WORKSPACE;
+    if (need > 0 && (!workspace || workspace_bytes < need)) return LSERVE_ERR_WORKSPACE;
     hipError_t e = launch_sparse_prefill(desc->dtype, lp, q, k, v, cu_seqlens, batch, total_tokens, max_seqlen, out,
                                          lse_out, workspace, mask ? &ma : nullptr, (hipStream_t)stream);
     return e == hipSuccess ? LSERVE_OK : fail_hip(e);
@@ -266,7 +266,8 @@ int lserve_sparse_prefill_paged(const lserve_attn_desc* desc, const lserve_paged
         return LSERVE_ERR_INVALID_ARG;
     if (!aligned16(q) || !aligned16(cu_q) || !aligned16(out) || !aligned16(lse_out) || !aligned16(workspace))
         return LSERVE_ERR_INVALID_ARG;
-    if (!workspace || workspace_bytes < paged_prefill_workspace_bytes(lp, pp.batch, pp.max_pages)) return LSERVE_ERR_WORKSPACE;
+    const size_t need = paged_prefill_workspace_bytes(lp, pp.batch, pp.max_pages);
+    if (need > 0 && (!workspace || workspace_bytes < need)) return LSERVE_ERR_WORKSPACE;
     hipError_t e = launch_sparse_prefill_paged(desc->dtype, lp, pp, q, cu_q, total_new, max_new_per_seq, max_seqlen, out,
                                                lse_out, workspace, (hipStream_t)stream);
     return e == hipSuccess ? LSERVE_OK : fail_hip(e);

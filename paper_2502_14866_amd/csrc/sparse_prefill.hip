@@ -7,15 +7,16 @@
 // Mapping to CDNA4: a workgroup of eight wavefronts owns 256 consecutive query rows of one head;
 // wavefronts 2t and 2t + 1 own the two 32-row halves of mask tile 4 * block + t.  Two wavefronts
 // share each SIMD, so the matrix pipe of one overlaps the softmax arithmetic of the other.  K and
-// V^T tiles are brought into LDS once per workgroup by direct-to-LDS loads, double buffered, and
+// V tiles are brought into LDS once per workgroup by direct-to-LDS loads, double buffered, and
 // consumed by all eight wavefronts.  Scores are computed transposed,
 //   S^T (keys x queries) = K (keys x d) * Q^T (d x queries)          v_mfma_f32_32x32x16
 // so that a lane owns one query column: the softmax reductions over keys stay inside the lane
 // (plus one exchange between the two lane halves), and the exponentiated tile is already in the
 // register layout of the B operand of the second product
 //   O^T (d x queries) += V^T (d x keys) * P^T (keys x queries).
-// V^T tiles come from a small pre-pass that transposes V once per call into 64-key tiles whose key
-// order matches the accumulator layout, so every LDS operand read is one 16-byte access.
+// V stays as it is in memory, one row per key: the V^T operand is read from the row-major tile with the
+// transposing LDS read of gfx950 (ds_read_b64_tr_b16), which hands a lane four keys of one channel, so
+// there is no transposition pass and no transposed copy of V.
 #include <algorithm>
 
 #include "kernels.h"
@@ -36,17 +37,19 @@ constexpr int kRowsPerBlock = kTilesPerBlock * kTile;
 constexpr int kDmaLoads = 16 / kPrefillWaves;      // 1 KiB loads per wave, tile and operand
 constexpr int kAhead = 4;                          // operand reads in flight ahead of the score products
 constexpr int kKRowBytes = 256;                    // K tile row: 128 x 16 bit = 16 chunks of 16 B
-constexpr int kVRowBytes = 128;                    // V^T tile row: 64 keys x 16 bit = 8 chunks of 16 B
+constexpr int kVRowBytes = 256;                    // V tile row (one key): the same
 constexpr int kKTileBytes = kTile * kKRowBytes;
-constexpr int kVTileBytes = kHeadDim * kVRowBytes;
+constexpr int kVTileBytes = kTile * kVRowBytes;
 
 // Tiles reach LDS through direct-to-LDS loads, which place the 64 lanes of an instruction at 64
 // consecutive 16-byte slots, so rows cannot be padded.  Bank conflicts are avoided by permuting the
-// chunks inside a row instead: chunk c of K row r sits at position c ^ (r % 16), chunk c of V^T row d
-// at position c ^ ((d / 2) % 8).  Sixteen consecutive rows then hit sixteen different 16-byte bank
-// groups for any fixed c, which is what the matrix-operand reads (one row per lane) need.
+// chunks inside a row instead.  Chunk c of K row r sits at position c ^ (r % 16): sixteen consecutive rows
+// then hit sixteen different 16-byte bank groups for any fixed c, which is what the K operand reads (one
+// row per lane) need.  Chunk c of V row r sits at position c ^ 4 (r % 4): a transposing read takes, from
+// each of four consecutive rows, the same 64 bytes (32 channels), and the four stretches then fall into
+// the four 64-byte quarters of the 256 bytes the banks serve per cycle.
 __device__ __forceinline__ int k_chunk_pos(int row, int c) { return c ^ (row % 16); }
-__device__ __forceinline__ int v_chunk_pos(int d, int c) { return c ^ ((d / 2) % 8); }
+__device__ __forceinline__ int v_chunk_pos(int row, int c) { return c ^ (4 * (row % 4)); }
 
 // The load itself is written in assembly: left to the compiler it is treated as an access that may
 // touch both memory and LDS, and while one is in flight every LDS operand read in the loop waits with
@@ -81,75 +84,15 @@ template <> struct Mfma<BF16> {
     }
 };
 
-// First V^T tile slot of sequence b: floor(cu[b] / 64) + b leaves room for every ragged last tile.
-__device__ __forceinline__ int tile_base(int cu_b, int b) { return cu_b / kTile + b; }
-
-// Slot of key (relative to its 64-key tile) inside a V^T tile row.  Register v of a 32 x 32
-// accumulator holds row 8 * (v / 4) + 4 * half + v % 4; the second product consumes registers
-// 8j .. 8j+7 of each half as one operand, so those eight keys must be contiguous.
-__device__ __forceinline__ int vt_slot(int key) {
-    const int kb = key / 32, k32 = key % 32;
-    const int v = (k32 / 8) * 4 + (k32 % 4), half = (k32 / 4) % 2;
-    return kb * 32 + (v / 8) * 16 + half * 8 + (v % 8);
-}
-
-// V [total][Hkv][D]  ->  vt [Hkv][tile slot][D][64 key slots], 16-byte chunks of a row permuted as in
-// LDS; keys past the sequence end become 0.
-template <class T>
-__global__ __launch_bounds__(256) void transpose_v_kernel(const uint16_t* __restrict__ v, uint16_t* __restrict__ vt,
-                                                          const int* __restrict__ cu_seqlens, int Hkv,
-                                                          int tiles_total) {
-    __shared__ uint16_t sm[kTile][kHeadDim + 2];
-    const int b = blockIdx.z, hk = blockIdx.y, jt = blockIdx.x;
-    const int start = cu_seqlens[b], len = cu_seqlens[b + 1] - start;
-    if (jt * kTile >= len) return;
-    for (int idx = threadIdx.x; idx < kTile * kHeadDim; idx += 256) {
-        const int key = idx / kHeadDim, d = idx % kHeadDim;
-        const int t = jt * kTile + key;
-        sm[key][d] = t < len ? v[((size_t)(start + t) * Hkv + hk) * kHeadDim + d] : (uint16_t)0;
-    }
-    __syncthreads();
-    uint16_t* dst = vt + ((size_t)hk * tiles_total + tile_base(start, b) + jt) * kHeadDim * kTile;
-    for (int idx = threadIdx.x; idx < kTile * kHeadDim; idx += 256) {
-        const int d = idx / kTile, key = idx % kTile;
-        const int sl = vt_slot(key);
-        dst[(size_t)d * kTile + v_chunk_pos(d, sl / 8) * 8 + sl % 8] = sm[key][d];  // stored as the LDS tile is laid out
-    }
-}
-
 // Chunked prefill over a paged cache: keys and values of every token, the chunk's own included, are read
 // from the pages; the queries are the last cu_q[b+1] - cu_q[b] tokens of each sequence.
 struct PrefillPaged {
     const uint16_t* k_pool;  // [pages][Hkv][64][D]
+    const uint16_t* v_pool;  // the same shape
     const int* page_table;   // [batch][max_pages]
     const int* seq_lens;     // [batch]
     int max_pages;
 };
-
-// V^T tiles of a paged cache: page jt of sequence b -> vt [Hkv][b * max_pages + jt][D][64 key slots], chunks
-// permuted as in LDS; slots at or past the sequence length become 0 (a page may hold anything there).
-template <class T>
-__global__ __launch_bounds__(256) void transpose_v_paged_kernel(const uint16_t* __restrict__ v_pool,
-                                                                uint16_t* __restrict__ vt, PrefillPaged pg, int Hkv,
-                                                                int tiles_total) {
-    __shared__ uint16_t sm[kTile][kHeadDim + 2];
-    const int b = blockIdx.z, hk = blockIdx.y, jt = blockIdx.x;
-    const int len = pg.seq_lens[b];
-    if (jt * kTile >= len) return;
-    const int phys = pg.page_table[(size_t)b * pg.max_pages + jt];
-    const uint16_t* src = v_pool + ((size_t)phys * Hkv + hk) * kTile * kHeadDim;
-    for (int idx = threadIdx.x; idx < kTile * kHeadDim; idx += 256) {
-        const int key = idx / kHeadDim, d = idx % kHeadDim;
-        sm[key][d] = jt * kTile + key < len ? src[idx] : (uint16_t)0;
-    }
-    __syncthreads();
-    uint16_t* dst = vt + ((size_t)hk * tiles_total + (size_t)b * pg.max_pages + jt) * kHeadDim * kTile;
-    for (int idx = threadIdx.x; idx < kTile * kHeadDim; idx += 256) {
-        const int d = idx / kTile, key = idx % kTile;
-        const int sl = vt_slot(key);
-        dst[(size_t)d * kTile + v_chunk_pos(d, sl / 8) * 8 + sl % 8] = sm[key][d];
-    }
-}
 
 template <class T>
 __device__ __forceinline__ uint4 pack8(const float* p) {
@@ -158,8 +101,29 @@ __device__ __forceinline__ uint4 pack8(const float* p) {
 }
 
 // Combine a value with the one held by the same lane of the other 32-lane half of the wave.
-__device__ __forceinline__ float halves_max(float x) { return fmaxf(x, __shfl_xor(x, 32, kWave)); }
-__device__ __forceinline__ float halves_sum(float x) { return x + __shfl_xor(x, 32, kWave); }
+// (one swap of the upper half of a register with the lower half of its copy, in the vector ALU)
+template <class Op> __device__ __forceinline__ float halves_combine(float x, Op op) {
+    const unsigned u = __builtin_bit_cast(unsigned, x);
+    const swap_pair_t p = __builtin_amdgcn_permlane32_swap(u, u, false, false);
+    const unsigned p0 = p[0], p1 = p[1];
+    return op(__builtin_bit_cast(float, p0), __builtin_bit_cast(float, p1));
+}
+__device__ __forceinline__ float halves_max(float x) {
+    return halves_combine(x, [](float a, float b) { return fmaxf(a, b); });
+}
+__device__ __forceinline__ float halves_sum(float x) {
+    return halves_combine(x, [](float a, float b) { return a + b; });
+}
+
+typedef short short4_t __attribute__((ext_vector_type(4)));
+// Transposing LDS read (ds_read_b64_tr_b16).  The sixteen lanes of a row each name four consecutive 16-bit
+// elements; lane i receives element i % 4 of the lanes i / 4, i / 4 + 4, i / 4 + 8 and i / 4 + 12.  With lane s
+// pointing at channels 4 (s % 4) .. + 3 of key s / 4, lane i ends up with channel i of four consecutive keys.
+__device__ __forceinline__ uint2 lds_read_transposed(const unsigned char* p) {
+    const short4_t v = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+        (__attribute__((address_space(3))) short4_t*)(const __attribute__((address_space(3))) void*)p);
+    return __builtin_bit_cast(uint2, v);
+}
 
 // Work order of the launch.  Workgroup ids go round-robin over the eight XCDs, each with its own L2.
 // Dense heads come first (heaviest query blocks first), streaming heads after.  When the number of
@@ -259,11 +223,11 @@ enum PrefillMode { kPlain = 0, kMasked = 1, kPaged = 2 };
 
 template <class T, int MODE>
 __global__ __launch_bounds__(kPrefillThreads, 512 / kPrefillThreads) void sparse_prefill_kernel(
-    LayerParams lp, const uint16_t* __restrict__ q, const uint16_t* __restrict__ k, const uint16_t* __restrict__ vt,
-    const int* __restrict__ cu_seqlens, int batch, int blocks_per_seq, int tiles_total, uint16_t* __restrict__ out,
+    LayerParams lp, const uint16_t* __restrict__ q, const uint16_t* __restrict__ k, const uint16_t* __restrict__ v,
+    const int* __restrict__ cu_seqlens, int batch, int blocks_per_seq, uint16_t* __restrict__ out,
     float* __restrict__ lse_out, int total_tokens, PrefillSchedule sched, PrefillMask mk, PrefillPaged pg) {
     constexpr bool MASKED = MODE == kMasked, PAGED = MODE == kPaged;
-    // Two stages of (K tile, V^T tile).  Four separate arrays, and a loop unrolled over the two stages,
+    // Two stages of (K tile, V tile).  Four separate arrays, and a loop unrolled over the two stages,
     // so that the compiler can tell the tile being read from the tile being filled and does not wait
     // for the loads in flight before every operand read.
     __shared__ __attribute__((aligned(1024))) unsigned char k_lds0[kKTileBytes];
@@ -363,11 +327,12 @@ __global__ __launch_bounds__(kPrefillThreads, 512 / kPrefillThreads) void sparse
     // contiguous keys: tile jt starts jt * 64 rows after the sequence's first row; paged keys: tile jt is
     // the slab of (page_table[b][jt], hk), rows 256 bytes apart
     const uint16_t* kbase = PAGED ? pg.k_pool + (size_t)hk * kTile * kHeadDim : k + ((size_t)start * lp.Hkv + hk) * kHeadDim;
-    const uint16_t* vtbase = vt + ((size_t)hk * tiles_total + (PAGED ? b * pg.max_pages : tile_base(start, b))) * kHeadDim * kTile;
+    const uint16_t* vbase = PAGED ? pg.v_pool + (size_t)hk * kTile * kHeadDim : v + ((size_t)start * lp.Hkv + hk) * kHeadDim;
     const int* page_row = PAGED ? pg.page_table + (size_t)b * pg.max_pages : nullptr;
-    // lane `lane` of load i of this wave fills slot (2 wave + i) * 64 + lane of the tile.  Addresses are a
-    // wave-uniform 64-bit tile base (scalar arithmetic) plus a 32-bit lane offset that does not depend
-    // on the tile, except in the ragged last tile of a sequence where rows past the end are clamped.
+    // lane `lane` of load i of this wave fills slot (2 wave + i) * 64 + lane of the tile, i.e. position lane % 16
+    // of row 4 (2 wave + i) + lane / 16.  Addresses are a wave-uniform 64-bit tile base (scalar arithmetic) plus a
+    // 32-bit lane offset that does not depend on the tile, except in the last tile of a sequence, where rows
+    // past the end read the last row again (finite values; their softmax weights are 0).
     const unsigned k_row_bytes = PAGED ? kHeadDim * 2u : (unsigned)__builtin_amdgcn_readfirstlane(lp.Hkv * kHeadDim * 2);
     const unsigned long long k_page_bytes = (unsigned long long)lp.Hkv * kTile * kHeadDim * 2;
     const int krow0 = wave * (4 * kDmaLoads) + lane / 16;  // K row of load 0; load i takes row + 4 i
@@ -375,27 +340,30 @@ __global__ __launch_bounds__(kPrefillThreads, 512 / kPrefillThreads) void sparse
 #pragma unroll
     for (int i = 0; i < kDmaLoads; ++i) {
         kofs[i] = (unsigned)(krow0 + 4 * i) * k_row_bytes + k_chunk_pos(krow0 + 4 * i, lane % 16) * 16;  // an involution
-        vofs[i] = ((wave * kDmaLoads + i) * 64 + lane) * 16;
+        vofs[i] = (unsigned)(krow0 + 4 * i) * k_row_bytes + v_chunk_pos(krow0 + 4 * i, lane % 16) * 16;  // likewise
     }
     const unsigned lds_wave = (unsigned)__builtin_amdgcn_readfirstlane(wave * kDmaLoads * 1024);
-    const unsigned long long kbase_u = uniform64((unsigned long long)kbase), vtbase_u = uniform64((unsigned long long)vtbase);
+    const unsigned long long kbase_u = uniform64((unsigned long long)kbase), vbase_u = uniform64((unsigned long long)vbase);
     const int len_u = __builtin_amdgcn_readfirstlane(len);
     auto fetch = [&](unsigned char* kd, unsigned char* vd, int jt, int phys) {
         jt = __builtin_amdgcn_readfirstlane(jt);
         const unsigned long long ktile =
             PAGED ? kbase_u + (unsigned long long)(unsigned)__builtin_amdgcn_readfirstlane(phys) * k_page_bytes
                   : kbase_u + (unsigned long long)jt * (kTile * k_row_bytes);
-        const unsigned long long vtile = vtbase_u + (unsigned long long)jt * (kHeadDim * kTile * 2);
-        const int rows_left = PAGED ? kTile : len_u - jt * kTile;  // a page is readable to its end
+        const unsigned long long vtile = ktile - kbase_u + vbase_u;  // K and V are laid out alike
+        // Rows at or past the sequence length must not be read as they are: a page may hold anything there, and
+        // although their weights are 0 a non-finite value would still poison the second product.
+        const int rows_left = len_u - jt * kTile;
 #pragma unroll
         for (int i = 0; i < kDmaLoads; ++i) {
-            unsigned ko = kofs[i];
+            unsigned ko = kofs[i], vo = vofs[i];
             if (rows_left < kTile) {
                 const int row = krow0 + 4 * i;
                 ko = (unsigned)min(row, rows_left - 1) * k_row_bytes + k_chunk_pos(row, lane % 16) * 16;
+                vo = (unsigned)min(row, rows_left - 1) * k_row_bytes + v_chunk_pos(row, lane % 16) * 16;
             }
             dma_load16(ktile, ko, __builtin_amdgcn_readfirstlane(lds_address(kd) + lds_wave + i * 1024));
-            dma_load16(vtile, vofs[i], __builtin_amdgcn_readfirstlane(lds_address(vd) + lds_wave + i * 1024));
+            dma_load16(vtile, vo, __builtin_amdgcn_readfirstlane(lds_address(vd) + lds_wave + i * 1024));
         }
     };
     // Entry `it` of the walk: key tile in the low bits; with a listed mask also which query tiles keep it.
@@ -411,8 +379,17 @@ __global__ __launch_bounds__(kPrefillThreads, 512 / kPrefillThreads) void sparse
     int koff[8], voff[4];
 #pragma unroll
     for (int kk = 0; kk < 8; ++kk) koff[kk] = n * kKRowBytes + k_chunk_pos(n, kk * 2 + half) * 16;
+    // V^T operand of (channel block db, 16-key step, half u of the lane's 8 keys): the lane's row of sixteen names
+    // keys 16 step + 8 u + 4 half + s / 4 (s = lane % 16) and channels 32 db + 16 (n / 16) + 4 (s % 4) .. + 3, which
+    // after the exchange leaves lane (n, half) with channel 32 db + n of keys 16 step + 8 u + 4 half + 0 .. 3: the
+    // keys its weights P^T[8 half + 4 u .. + 3] belong to.  Per db the lane part of the address is fixed; step and u
+    // add (4 step + 2 u) KiB.
 #pragma unroll
-    for (int step = 0; step < 4; ++step) voff[step] = n * kVRowBytes + v_chunk_pos(n, step * 2 + half) * 16;
+    for (int db = 0; db < 4; ++db) {
+        const int s16 = lane % 16, rr = s16 / 4;
+        const int chunk = 4 * db + 2 * (n / 16) + (s16 % 4) / 2;
+        voff[db] = half * 1024 + rr * kVRowBytes + v_chunk_pos(rr, chunk) * 16 + 8 * (s16 % 2);
+    }
 
     auto tile_step = [&](int it, const unsigned char* ks, const unsigned char* vs, unsigned char* kd, unsigned char* vd) {
         const int e_new = it + 2 < n_visit ? entry_of(it + 2) : 0;  // requested two steps ahead of its use
@@ -509,8 +486,11 @@ __global__ __launch_bounds__(kPrefillThreads, 512 / kPrefillThreads) void sparse
                 const int kb = step / 2, j = step % 2;
                 uint4 va[4];
 #pragma unroll
-                for (int db = 0; db < 4; ++db)
-                    va[db] = *reinterpret_cast<const uint4*>(vs + db * 32 * kVRowBytes + voff[step]);
+                for (int db = 0; db < 4; ++db) {
+                    const uint2 lo = lds_read_transposed(vs + (4 * step) * 1024 + voff[db]);
+                    const uint2 hi = lds_read_transposed(vs + (4 * step + 2) * 1024 + voff[db]);
+                    va[db] = make_uint4(lo.x, lo.y, hi.x, hi.y);
+                }
 #pragma unroll
                 for (int db = 0; db < 4; ++db) acc[db] = Mfma<T>::run(va[db], pb[kb][j], acc[db]);
             }
@@ -550,8 +530,6 @@ __global__ __launch_bounds__(kPrefillThreads, 512 / kPrefillThreads) void sparse
         lse_out[(size_t)h * total_tokens + start + row] = lt > 0.f ? (m_run + __builtin_amdgcn_logf(lt)) * kLn2 : -INFINITY;
 }
 
-int prefill_tile_slots(int total_tokens, int batch) { return total_tokens / kTile + batch; }
-
 PrefillSchedule make_schedule(const LayerParams& lp, int blocks_per_seq, int batch) {
     PrefillSchedule sched;
     sched.qblocks_total = blocks_per_seq * batch;
@@ -572,26 +550,18 @@ PrefillSchedule make_schedule(const LayerParams& lp, int blocks_per_seq, int bat
     return sched;
 }
 
-size_t vt_bytes(const LayerParams& lp, int total_tokens, int batch) {
-    return (size_t)lp.Hkv * prefill_tile_slots(total_tokens, batch) * kHeadDim * kTile * sizeof(uint16_t);
-}
 size_t align16(size_t x) { return (x + 15) & ~(size_t)15; }
 
 template <class T>
 hipError_t launch_prefill(const LayerParams& lp, const void* q, const void* k, const void* v, const int* cu_seqlens,
                           int batch, int total_tokens, int max_seqlen, void* out, float* lse_out, void* workspace,
                           const PrefillMaskArgs* mask, hipStream_t stream) {
-    const int tiles_total = prefill_tile_slots(total_tokens, batch);
-    uint16_t* vt = reinterpret_cast<uint16_t*>(workspace);
     const int max_tiles = (max_seqlen + kTile - 1) / kTile;
-    hipLaunchKernelGGL(transpose_v_kernel<T>, dim3(max_tiles, lp.Hkv, batch), dim3(256), 0, stream,
-                       reinterpret_cast<const uint16_t*>(v), vt, cu_seqlens, lp.Hkv, tiles_total);
-    hipError_t e = hipGetLastError();
-    if (e != hipSuccess) return e;
+    hipError_t e = hipSuccess;
     const int blocks_per_seq = (max_seqlen + kRowsPerBlock - 1) / kRowsPerBlock;
     PrefillMask mk = {};
     if (mask) {
-        unsigned char* ws = reinterpret_cast<unsigned char*>(workspace) + align16(vt_bytes(lp, total_tokens, batch));
+        unsigned char* ws = reinterpret_cast<unsigned char*>(workspace);
         mk.head_mask = mask->head_mask;
         mk.q_tile_start = mask->q_tile_start;
         mk.row_ptr = mask->row_ptr;
@@ -609,12 +579,14 @@ hipError_t launch_prefill(const LayerParams& lp, const void* q, const void* k, c
     const PrefillPaged pg = {};
     if (mask)
         hipLaunchKernelGGL((sparse_prefill_kernel<T, kMasked>), dim3(grid), dim3(kPrefillThreads), 0, stream, lp,
-                           reinterpret_cast<const uint16_t*>(q), reinterpret_cast<const uint16_t*>(k), vt, cu_seqlens, batch,
-                           blocks_per_seq, tiles_total, reinterpret_cast<uint16_t*>(out), lse_out, total_tokens, sched, mk, pg);
+                           reinterpret_cast<const uint16_t*>(q), reinterpret_cast<const uint16_t*>(k),
+                           reinterpret_cast<const uint16_t*>(v), cu_seqlens, batch, blocks_per_seq,
+                           reinterpret_cast<uint16_t*>(out), lse_out, total_tokens, sched, mk, pg);
     else
         hipLaunchKernelGGL((sparse_prefill_kernel<T, kPlain>), dim3(grid), dim3(kPrefillThreads), 0, stream, lp,
-                           reinterpret_cast<const uint16_t*>(q), reinterpret_cast<const uint16_t*>(k), vt, cu_seqlens, batch,
-                           blocks_per_seq, tiles_total, reinterpret_cast<uint16_t*>(out), lse_out, total_tokens, sched, mk, pg);
+                           reinterpret_cast<const uint16_t*>(q), reinterpret_cast<const uint16_t*>(k),
+                           reinterpret_cast<const uint16_t*>(v), cu_seqlens, batch, blocks_per_seq,
+                           reinterpret_cast<uint16_t*>(out), lse_out, total_tokens, sched, mk, pg);
     return hipGetLastError();
 }
 
@@ -624,23 +596,19 @@ hipError_t launch_prefill_paged(const LayerParams& lp, const PagedParams& kv, co
                                 void* workspace, hipStream_t stream) {
     PrefillPaged pg;
     pg.k_pool = reinterpret_cast<const uint16_t*>(kv.k_pool);
+    pg.v_pool = reinterpret_cast<const uint16_t*>(kv.v_pool);
     pg.page_table = kv.page_table;
     pg.seq_lens = kv.seq_lens;
     pg.max_pages = kv.max_pages;
-    const int tiles_total = kv.batch * kv.max_pages;
-    uint16_t* vt = reinterpret_cast<uint16_t*>(workspace);
-    const int max_tiles = std::min(kv.max_pages, (max_seqlen + kTile - 1) / kTile);
-    hipLaunchKernelGGL(transpose_v_paged_kernel<T>, dim3(max_tiles, lp.Hkv, kv.batch), dim3(256), 0, stream,
-                       reinterpret_cast<const uint16_t*>(kv.v_pool), vt, pg, lp.Hkv, tiles_total);
-    hipError_t e = hipGetLastError();
-    if (e != hipSuccess) return e;
+    (void)workspace;
+    (void)max_seqlen;
     // the chunk's rows start anywhere inside a 256-row block: one block more than the chunk length needs
     const int blocks_per_seq = (max_new_per_seq + kRowsPerBlock - 1) / kRowsPerBlock + 1;
     const PrefillSchedule sched = make_schedule(lp, blocks_per_seq, kv.batch);
     const int grid = kXcds * (sched.cls[0].items_per_xcd + sched.cls[1].items_per_xcd);
     const PrefillMask mk = {};
     hipLaunchKernelGGL((sparse_prefill_kernel<T, kPaged>), dim3(grid), dim3(kPrefillThreads), 0, stream, lp,
-                       reinterpret_cast<const uint16_t*>(q), nullptr, vt, cu_q, kv.batch, blocks_per_seq, tiles_total,
+                       reinterpret_cast<const uint16_t*>(q), nullptr, nullptr, cu_q, kv.batch, blocks_per_seq,
                        reinterpret_cast<uint16_t*>(out), lse_out, total_new, sched, mk, pg);
     return hipGetLastError();
 }
@@ -653,7 +621,10 @@ hipError_t preload_prefill_kernels() {
 }
 
 size_t paged_prefill_workspace_bytes(const LayerParams& lp, int batch, int max_pages) {
-    return (size_t)lp.Hkv * batch * max_pages * kHeadDim * kTile * sizeof(uint16_t);
+    (void)lp;
+    (void)batch;
+    (void)max_pages;
+    return 0;  // keys and values are read from the pages as they are
 }
 
 hipError_t launch_sparse_prefill_paged(int dtype, const LayerParams& lp, const PagedParams& kv, const void* q,
@@ -666,15 +637,20 @@ hipError_t launch_sparse_prefill_paged(int dtype, const LayerParams& lp, const P
 }
 
 size_t prefill_workspace_bytes(const LayerParams& lp, int total_tokens, int batch) {
-    return vt_bytes(lp, total_tokens, batch);
+    (void)lp;
+    (void)total_tokens;
+    (void)batch;
+    return 0;  // Q, K and V are read where they are
 }
 
-// V^T tiles, then the merged tile lists (at most one entry per mask entry), then one count per
-// (mask, sequence, workgroup of query rows).
+// The merged tile lists (at most one entry per mask entry), then one count per (mask, sequence, workgroup of
+// query rows).
 size_t masked_prefill_workspace_bytes(const LayerParams& lp, int total_tokens, int batch, int max_seqlen, int num_masks,
                                       int nnz) {
     const int blocks_per_seq = (max_seqlen + kRowsPerBlock - 1) / kRowsPerBlock;
-    return align16(vt_bytes(lp, total_tokens, batch)) + align16((size_t)nnz * sizeof(int)) +
+    (void)lp;
+    (void)total_tokens;
+    return align16((size_t)nnz * sizeof(int)) +
            align16((size_t)num_masks * batch * blocks_per_seq * sizeof(int));
 }
 
