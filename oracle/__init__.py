@@ -19,6 +19,7 @@ from .reference import (  # noqa: F401
     sparse_prefill_rows,
     block_mask_prefill_rows,
     paged_prefill_rows,
+    chunk_prefill_rows,
     count_nonempty_tiles,
     block_sparse_speedup,
 )

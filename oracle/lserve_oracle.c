@@ -18,7 +18,9 @@
  *                                      K highest pages under the token budget)
  *   - decode over an index table     : Sec. 3.6 (selected pages for dense heads, sink + local
  *                                      pages for streaming heads), Sec. 3.2 ("shorter page table")
- *   - chunked prefill over paged KV  : Sec. 2.1 (prefill with S tokens of history), mask of Sec. 3.1
+ *   - chunked prefill over paged KV  : Sec. 2.1 (prefill with S tokens of history), mask of Sec. 3.1; also in the
+ *                                      order of the prefill flow of Sec. 3.2 (history from the cache, the chunk's
+ *                                      own K / V not yet written back)
  *   - general block mask in prefill  : Sec. 3.1 / Sec. 3.4 (kept key tiles listed per query tile and head)
  *   - KV write-back                  : Sec. 3.2 / Sec. 2.1 (new tokens stored at their slots of the
  *                                      paged cache; statistics afterwards = the definition above
@@ -476,6 +478,70 @@ void oracle_paged_prefill_rows(const uint16_t *q, const uint16_t *k_pool, const 
             int page = page_table[(size_t)b * max_pages + u / NP];
             for (int c = 0; c < D; ++c)
                 o[c] += pr * oracle_widen(v_pool[pool_index(page, hk, u % NP, c, Hkv, NP, D)], dtype);
+        }
+        if (lse) lse[r] = mx + log(denom);
+        free(score);
+    }
+}
+
+/* ---- chunked prefill in the order of the prefill flow (Sec. 3.2: attention first, write-back after; Sec. 2.1:
+ *      N new tokens with S tokens of history) ---------------------------------------------------------------- */
+/*
+ * Sequence b has hist_lens[b] = S_b tokens in its cache and n_b = cu_new[b+1] - cu_new[b] new tokens whose Q, K, V
+ * arrive contiguously; query j of the chunk sits at position t = S_b + j.  It attends the positions u <= t allowed
+ * by the tile-granular mask of oracle_sparse_prefill_rows (tiles counted from position 0): a history token u < S_b
+ * with the key / value the cache stands for, given as doubles in k_hist / v_hist [batch][hist_stride][Hkv][D]
+ * (gathered, and for a quantised cache dequantised, by the caller; a position the cache no longer holds may be NaN
+ * there: a streaming head must never touch it), a chunk token u >= S_b with k_new / v_new [total_new][Hkv][D].
+ * Row r asks for chunk token rows_token[r] (index into q) and query head rows_head[r].
+ */
+void oracle_chunk_prefill_rows(const uint16_t *q, const uint16_t *k_new, const uint16_t *v_new,
+                               const double *k_hist, const double *v_hist, const int32_t *hist_lens,
+                               const int32_t *cu_new, int batch, int hist_stride, int H, int Hkv, int D,
+                               int T, int dtype, int sink_tokens, int local_tokens,
+                               const uint8_t *kv_head_is_streaming, double sm_scale,
+                               const int32_t *rows_token, const int32_t *rows_head, int n_rows, double *out,
+                               double *lse)
+{
+    int n = H / Hkv;
+    int s = ceil_div(sink_tokens, T);
+    int w = ceil_div(local_tokens, T);
+#pragma omp parallel for schedule(dynamic, 4)
+    for (int r = 0; r < n_rows; ++r) {
+        int tok = rows_token[r], h = rows_head[r], hk = h / n;
+        int b = 0;
+        while (b + 1 < batch && cu_new[b + 1] <= tok) ++b;
+        int S = hist_lens[b];
+        int t = S + (tok - cu_new[b]);
+        int streaming = kv_head_is_streaming[hk];
+        double *score = (double *)malloc(sizeof(double) * (size_t)(t + 1));
+        const uint16_t *qh = &q[((size_t)tok * H + h) * D];
+        double mx = -INFINITY;
+        for (int u = 0; u <= t; ++u) {
+            int allowed = !streaming || (u / T < s) || (u / T > t / T - w);
+            if (!allowed) { score[u] = -INFINITY; continue; }
+            double dot = 0.0;
+            for (int c = 0; c < D; ++c) {
+                double kc = u < S ? k_hist[(((size_t)b * hist_stride + u) * Hkv + hk) * D + c]
+                                  : oracle_widen(k_new[((size_t)(cu_new[b] + u - S) * Hkv + hk) * D + c], dtype);
+                dot += oracle_widen(qh[c], dtype) * kc;
+            }
+            score[u] = dot * sm_scale;
+            if (score[u] > mx) mx = score[u];
+        }
+        double denom = 0.0;
+        for (int u = 0; u <= t; ++u)
+            if (score[u] != -INFINITY) denom += exp(score[u] - mx);
+        double *o = &out[(size_t)r * D];
+        for (int c = 0; c < D; ++c) o[c] = 0.0;
+        for (int u = 0; u <= t; ++u) {
+            if (score[u] == -INFINITY) continue;
+            double pr = exp(score[u] - mx) / denom;
+            for (int c = 0; c < D; ++c) {
+                double vc = u < S ? v_hist[(((size_t)b * hist_stride + u) * Hkv + hk) * D + c]
+                                  : oracle_widen(v_new[((size_t)(cu_new[b] + u - S) * Hkv + hk) * D + c], dtype);
+                o[c] += pr * vc;
+            }
         }
         if (lse) lse[r] = mx + log(denom);
         free(score);

@@ -282,6 +282,32 @@ def paged_prefill_rows(q: torch.Tensor, k_pool: torch.Tensor, v_pool: torch.Tens
     return out, lse
 
 
+def chunk_prefill_rows(q: torch.Tensor, k_new: torch.Tensor, v_new: torch.Tensor, k_hist: np.ndarray,
+                       v_hist: np.ndarray, hist_lens, cu_new, streaming_flags: Sequence[int], tile: int,
+                       sink_tokens: int, local_tokens: int, rows_token, rows_head, sm_scale: Optional[float] = None):
+    """Chunked prefill rows with the history given as values: k_hist / v_hist are float64 [batch, hist_stride, Hkv, D]
+    (what the cache stands for at positions below hist_lens; NaN where it holds nothing), the chunk's own K / V are
+    the 16-bit tensors.  Returns (out [R, D] f64, lse [R])."""
+    total, H, D = q.shape
+    Hkv = k_new.shape[1]
+    hl, cu = _i32(hist_lens), _i32(cu_new)
+    rt, rh = _i32(rows_token), _i32(rows_head)
+    flags = _u8(streaming_flags)
+    kh = np.ascontiguousarray(k_hist, dtype=np.float64)
+    vh = np.ascontiguousarray(v_hist, dtype=np.float64)
+    assert kh.shape == vh.shape and kh.shape[0] == hl.shape[0] and kh.shape[2:] == (Hkv, D)
+    out = np.zeros((rt.shape[0], D), dtype=np.float64)
+    lse = np.zeros((rt.shape[0],), dtype=np.float64)
+    scale = float(sm_scale) if sm_scale else 1.0 / float(np.sqrt(D))
+    qb, kb, vb = _bits(q), _bits(k_new), _bits(v_new)
+    _load().oracle_chunk_prefill_rows(_p(qb), _p(kb), _p(vb), _p(kh), _p(vh), _p(hl), _p(cu), ctypes.c_int(hl.shape[0]),
+                                      ctypes.c_int(kh.shape[1]), ctypes.c_int(H), ctypes.c_int(Hkv), ctypes.c_int(D),
+                                      ctypes.c_int(tile), ctypes.c_int(_dtype_code(q)), ctypes.c_int(sink_tokens),
+                                      ctypes.c_int(local_tokens), _p(flags), ctypes.c_double(scale), _p(rt), _p(rh),
+                                      ctypes.c_int(rt.shape[0]), _p(out), _p(lse))
+    return out, lse
+
+
 def block_mask_prefill_rows(q: torch.Tensor, k: torch.Tensor, v: torch.Tensor, cu_seqlens,
                             streaming_flags: Sequence[int], tile: int, sink_tokens: int, local_tokens: int,
                             head_mask, q_tile_start, row_ptr, cols, rows_per_mask: int, rows_token, rows_head,

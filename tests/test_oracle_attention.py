@@ -379,3 +379,74 @@ def test_paged_chunk_rows_equal_the_contiguous_prefill_rows_and_the_decode_of_th
         out = out.reshape(sum(chunk), w.num_q_heads, -1)
         np.testing.assert_allclose(out, full[idx], rtol=1e-12, atol=1e-14)
         np.testing.assert_allclose(lse.reshape(sum(chunk), -1), full_lse.reshape(total, -1)[idx], rtol=1e-12, atol=1e-12)
+
+
+# ---- chunked prefill in the order of the prefill flow: history from the cache, the chunk's K / V alongside ----------
+
+def test_chunk_rows_with_history_values_equal_the_contiguous_prefill_rows():
+    """Cut a contiguous prefill into history + chunk at several places (none, off a tile boundary, on one, one
+    token): with the history handed over as exactly the 16-bit values, the rows of the chunk must reproduce the
+    rows of the contiguous prefill (another function with other addressing)."""
+    w = _prefill_workload(batch=2, sink_tokens=64, local_tokens=128)
+    lengths = (300, 131)
+    pin = make_prefill_inputs(w, lengths=lengths)
+    total = sum(lengths)
+    tok, head = _all_rows(total, w.num_q_heads)
+    full, full_lse = oracle.sparse_prefill_rows(pin.q, pin.k, pin.v, pin.cu_seqlens, w.streaming_flags(), 64,
+                                                w.sink_tokens, w.local_tokens, tok, head)
+    full = full.reshape(total, w.num_q_heads, -1)
+    full_lse = full_lse.reshape(total, w.num_q_heads)
+    for chunk in ((300, 131), (100, 67), (1, 1), (64, 3), (236, 0)):
+        hist = [L - n for L, n in zip(lengths, chunk)]
+        stride = max(max(hist), 1)
+        k_hist = np.full((2, stride, w.num_kv_heads, w.head_dim), np.nan)
+        v_hist = np.full_like(k_hist, np.nan)
+        qs, ks, vs, idx = [], [], [], []
+        for b, (L, n) in enumerate(zip(lengths, chunk)):
+            a = int(pin.cu_seqlens[b])
+            k_hist[b, :hist[b]] = pin.k[a:a + hist[b]].to(torch.float64).numpy()
+            v_hist[b, :hist[b]] = pin.v[a:a + hist[b]].to(torch.float64).numpy()
+            qs.append(pin.q[a + hist[b]:a + L]); ks.append(pin.k[a + hist[b]:a + L]); vs.append(pin.v[a + hist[b]:a + L])
+            idx.extend(range(a + hist[b], a + L))
+        qc, kc, vc = torch.cat(qs), torch.cat(ks), torch.cat(vs)
+        cu_new = np.concatenate([[0], np.cumsum(chunk)]).astype(np.int32)
+        t2, h2 = _all_rows(sum(chunk), w.num_q_heads)
+        out, lse = oracle.chunk_prefill_rows(qc, kc, vc, k_hist, v_hist, np.asarray(hist, np.int32), cu_new,
+                                             w.streaming_flags(), 64, w.sink_tokens, w.local_tokens, t2, h2)
+        np.testing.assert_allclose(out.reshape(sum(chunk), w.num_q_heads, -1), full[idx], rtol=1e-12, atol=1e-14)
+        np.testing.assert_allclose(lse.reshape(sum(chunk), -1), full_lse[idx], rtol=1e-12, atol=1e-12)
+
+
+def test_chunk_rows_against_sdpa_under_the_expanded_mask_and_never_touch_dropped_history():
+    """Direct pin: torch attention under the boolean mask written out token by token, over keys = history values
+    followed by the chunk.  History positions no streaming query of the chunk may see hold NaN for the streaming
+    head (a bounded cache has dropped them); history values that are no 16-bit numbers (a dequantised cache) are
+    taken as they are."""
+    w = _prefill_workload(batch=1, sink_tokens=64, local_tokens=128)   # heads: KV head 0 streaming, 1 dense
+    T, S, n = 64, 333, 150
+    pin = make_prefill_inputs(w, lengths=(n,))
+    g = np.random.default_rng(5)
+    k_hist = g.standard_normal((1, S, w.num_kv_heads, w.head_dim)) * 1.37   # arbitrary doubles
+    v_hist = g.standard_normal((1, S, w.num_kv_heads, w.head_dim))
+    s_t, w_t = 1, 2
+    first_tile = S // T
+    for u in range(S):   # what the first chunk row cannot see, no later row can: sink tiles and the local band only
+        if not (u // T < s_t or u // T > first_tile - w_t):
+            k_hist[0, u, 0] = np.nan
+            v_hist[0, u, 0] = np.nan
+    tok, head = _all_rows(n, w.num_q_heads)
+    out, lse = oracle.chunk_prefill_rows(pin.q, pin.k, pin.v, k_hist, v_hist, [S], [0, n], w.streaming_flags(), T,
+                                         w.sink_tokens, w.local_tokens, tok, head)
+    assert np.isfinite(out).all() and np.isfinite(lse).all()
+    out = out.reshape(n, w.num_q_heads, -1)
+    q = pin.q.to(torch.float64).numpy()
+    group = w.num_q_heads // w.num_kv_heads
+    for j in (0, 1, 30, 31, 95, n - 1):
+        t = S + j
+        for h in range(w.num_q_heads):
+            hk = h // group
+            keys = np.concatenate([k_hist[0, :, hk], pin.k[:, hk].to(torch.float64).numpy()])
+            vals = np.concatenate([v_hist[0, :, hk], pin.v[:, hk].to(torch.float64).numpy()])
+            allowed = np.array([(u <= t) and (hk != 0 or u // T < s_t or u // T > t // T - w_t) for u in range(S + n)])
+            ref = _sdpa(q[j, h], np.nan_to_num(keys), np.nan_to_num(vals), mask=allowed)
+            np.testing.assert_allclose(out[j, h], ref, rtol=1e-10, atol=1e-12)
