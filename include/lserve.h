@@ -10,8 +10,9 @@
  *   lserve_sparse_decode     paged decode attention over an index table (Sec. 3.6)
  * and, around them, lserve_append_kv: write-back of new K/V into the pages with the statistics
  * updated in the same pass (Sec. 3.2, Sec. 3.5.2), lserve_sparse_prefill_masked: prefill under a
- * caller-supplied block mask (Sec. 3.1, Sec. 3.4), and lserve_sparse_prefill_paged: chunked prefill
- * whose keys and values come from the paged cache (Sec. 2.1).
+ * caller-supplied block mask (Sec. 3.1, Sec. 3.4), lserve_sparse_prefill_paged: chunked prefill whose keys
+ * and values all come from the paged cache (Sec. 2.1), and lserve_sparse_prefill_chunk: chunked prefill over
+ * the history in the cache with the chunk's own K / V alongside, before their write-back (Sec. 3.2).
  *
  * Conventions common to every call
  *   - "device" pointers are HIP device memory owned by the caller; "host" pointers are ordinary
@@ -258,6 +259,30 @@ int lserve_sparse_prefill_paged(const lserve_attn_desc *desc, const lserve_paged
 
 size_t lserve_paged_prefill_workspace_bytes(const lserve_attn_desc *desc, int32_t batch,
                                             int32_t max_pages_per_seq);
+
+/*
+ * Chunked prefill in the order of the prefill flow (Sec. 3.2: attention over the new tokens first, then their K / V
+ * are written back into the two caches; Sec. 2.1: N new tokens with S tokens of KV history; mask of Sec. 3.1).
+ * Sequence b has S_b = kv->seq_lens[b] tokens of history in the cache (S_b >= 0 here) and n_b = cu_new[b+1] - cu_new[b]
+ * new tokens whose Q, K and V arrive contiguously.  Query j sits at position t = S_b + j and attends the positions
+ * u <= t that the analytic mask of `desc` allows, tiles counted from position 0: keys u < S_b are read from the cache,
+ * keys u >= S_b from k_new / v_new.  Nothing is written to the cache: call lserve_append_kv with the same k_new, v_new,
+ * cu_new (and start_pos = the lengths) afterwards.  With S_b = 0 everywhere this equals lserve_sparse_prefill.
+ *
+ *   kv           the history, 16-bit rows, N_P = 64: one pool holding every KV head, or the two-way cache (dense
+ *                heads in the main pool, streaming heads in their ring: the ring of a sequence of S_b tokens holds the
+ *                sink pages and the last w pages, which is every history key a streaming query of the chunk may
+ *                attend; the keys between come from the chunk itself).  stats are not used.  Quantised pages:
+ *                LSERVE_ERR_UNSUPPORTED.
+ *   q            device [total_new][H][D]; k_new, v_new device [total_new][Hkv][D]
+ *   cu_new       device [batch + 1] (batch = kv->batch), cu_new[0] = 0, n_b >= 0
+ *   max_new_per_seq  host bound of n_b (> 0)
+ *   out          device [total_new][H][D]; lse_out device [H][total_new] fp32 or NULL
+ * No workspace.
+ */
+int lserve_sparse_prefill_chunk(const lserve_attn_desc *desc, const lserve_paged_kv *kv, const void *q,
+                                const void *k_new, const void *v_new, const int32_t *cu_new, int32_t total_new,
+                                int32_t max_new_per_seq, void *out, float *lse_out, void *stream);
 
 /*
  * Block-sparse prefill under a general block mask (Sec. 3.1: every tile of the attention map is skipped or

@@ -21,6 +21,7 @@ from .binding import (  # noqa: F401
     lserve_sparse_prefill_masked,
     lserve_paged_prefill_workspace_bytes,
     lserve_sparse_prefill_paged,
+    lserve_sparse_prefill_chunk,
     lserve_build_page_stats,
     lserve_init,
     lserve_last_hip_error,

@@ -26,6 +26,7 @@ EXPORTED_SYMBOLS = (
     "lserve_append_kv",
     "lserve_sparse_prefill_masked",
     "lserve_sparse_prefill_paged",
+    "lserve_sparse_prefill_chunk",
     "lserve_paged_prefill_workspace_bytes",
     "lserve_masked_prefill_workspace_bytes",
     "BlockMask",
@@ -100,6 +101,8 @@ def load_library():
         lib.lserve_masked_prefill_workspace_bytes.restype = ctypes.c_size_t
         lib.lserve_sparse_prefill_paged.argtypes = [dp, kp, vp, vp, i32, i32, i32, vp, vp, vp, sz, vp]
         lib.lserve_sparse_prefill_paged.restype = ctypes.c_int
+        lib.lserve_sparse_prefill_chunk.argtypes = [dp, kp, vp, vp, vp, vp, i32, i32, vp, vp, vp]
+        lib.lserve_sparse_prefill_chunk.restype = ctypes.c_int
         lib.lserve_paged_prefill_workspace_bytes.argtypes = [dp, i32, i32]
         lib.lserve_paged_prefill_workspace_bytes.restype = ctypes.c_size_t
         lib.lserve_workspace_bytes.argtypes = [ctypes.c_int, dp, i32, i32, i32, i32]
@@ -296,6 +299,14 @@ def lserve_sparse_prefill_paged(desc: AttnDesc, kv: PagedKV, q: torch.Tensor, cu
                                                       max_new_per_seq, max_seqlen, _ptr(out), _ptr(lse_out),
                                                       _ptr(workspace), ws_bytes, _stream(stream)),
            "lserve_sparse_prefill_paged")
+
+
+def lserve_sparse_prefill_chunk(desc: AttnDesc, kv: PagedKV, q: torch.Tensor, k_new: torch.Tensor, v_new: torch.Tensor,
+                                cu_new: torch.Tensor, max_new_per_seq: int, out: torch.Tensor,
+                                lse_out: Optional[torch.Tensor] = None, stream=None) -> None:
+    _check(load_library().lserve_sparse_prefill_chunk(desc.c(), kv.c(), _ptr(q), _ptr(k_new), _ptr(v_new), _ptr(cu_new),
+                                                      q.shape[0], max_new_per_seq, _ptr(out), _ptr(lse_out),
+                                                      _stream(stream)), "lserve_sparse_prefill_chunk")
 
 
 def lserve_sparse_decode(desc: AttnDesc, kv: PagedKV, q: torch.Tensor, sel_pages: Optional[torch.Tensor],

@@ -24,9 +24,12 @@ hipError_t launch_select_pages(int dtype, const LayerParams& lp, const PagedPara
                                hipStream_t stream);
 
 size_t paged_prefill_workspace_bytes(const LayerParams& lp, int batch, int max_pages);
+// k_new / v_new: the chunk's own K / V when they have not been written back yet (the cache is then the chunk's
+// history), or null when the cache already holds the chunk.
 hipError_t launch_sparse_prefill_paged(int dtype, const LayerParams& lp, const PagedParams& kv, const void* q,
-                                       const int* cu_q, int total_new, int max_new_per_seq, int max_seqlen, void* out,
-                                       float* lse_out, void* workspace, hipStream_t stream);
+                                       const void* k_new, const void* v_new, const int* cu_q, int total_new,
+                                       int max_new_per_seq, int max_seqlen, void* out, float* lse_out, void* workspace,
+                                       hipStream_t stream);
 
 size_t decode_workspace_bytes(const LayerParams& lp, int batch, int sel_stride);
 

@@ -268,8 +268,29 @@ int lserve_sparse_prefill_paged(const lserve_attn_desc* desc, const lserve_paged
         return LSERVE_ERR_INVALID_ARG;
     const size_t need = paged_prefill_workspace_bytes(lp, pp.batch, pp.max_pages);
     if (need > 0 && (!workspace || workspace_bytes < need)) return LSERVE_ERR_WORKSPACE;
-    hipError_t e = launch_sparse_prefill_paged(desc->dtype, lp, pp, q, cu_q, total_new, max_new_per_seq, max_seqlen, out,
-                                               lse_out, workspace, (hipStream_t)stream);
+    hipError_t e = launch_sparse_prefill_paged(desc->dtype, lp, pp, q, nullptr, nullptr, cu_q, total_new, max_new_per_seq,
+                                               max_seqlen, out, lse_out, workspace, (hipStream_t)stream);
+    return e == hipSuccess ? LSERVE_OK : fail_hip(e);
+}
+
+int lserve_sparse_prefill_chunk(const lserve_attn_desc* desc, const lserve_paged_kv* kv, const void* q, const void* k_new,
+                                const void* v_new, const int32_t* cu_new, int32_t total_new, int32_t max_new_per_seq,
+                                void* out, float* lse_out, void* stream) {
+    LayerParams lp;
+    PagedParams pp;
+    int rc = make_layer(desc, &lp);
+    if (rc) return rc;
+    rc = make_paged(kv, lp, true, true, false, true, &pp);
+    if (rc) return rc;
+    if (lp.NP != 64) return LSERVE_ERR_UNSUPPORTED;
+    if (pp.kv_bits != 16) return LSERVE_ERR_UNSUPPORTED;
+    if (!q || !k_new || !v_new || !cu_new || !out) return LSERVE_ERR_INVALID_ARG;
+    if (total_new <= 0 || max_new_per_seq <= 0 || max_new_per_seq > total_new) return LSERVE_ERR_INVALID_ARG;
+    if (!aligned16(q) || !aligned16(k_new) || !aligned16(v_new) || !aligned16(cu_new) || !aligned16(out) ||
+        !aligned16(lse_out))
+        return LSERVE_ERR_INVALID_ARG;
+    hipError_t e = launch_sparse_prefill_paged(desc->dtype, lp, pp, q, k_new, v_new, cu_new, total_new, max_new_per_seq, 0,
+                                               out, lse_out, nullptr, (hipStream_t)stream);
     return e == hipSuccess ? LSERVE_OK : fail_hip(e);
 }
 

@@ -84,14 +84,14 @@ template <> struct Mfma<BF16> {
     }
 };
 
-// Chunked prefill over a paged cache: keys and values of every token, the chunk's own included, are read
-// from the pages; the queries are the last cu_q[b+1] - cu_q[b] tokens of each sequence.
+// Chunked prefill over a paged cache (Sec. 2.1, Sec. 3.2).  The cache holds seq_lens[b] tokens of sequence b, in
+// any of the forms of PagedParams with 16-bit rows (one pool; dense heads in the main pool and streaming heads in
+// their ring of sink + local pages).  With k_new / v_new the queries are n_b new tokens whose K / V arrive
+// alongside and have not been written back yet: the cache is their history.  Without, the cache already holds
+// the chunk and the queries are its last n_b tokens.
 struct PrefillPaged {
-    const uint16_t* k_pool;  // [pages][Hkv][64][D]
-    const uint16_t* v_pool;  // the same shape
-    const int* page_table;   // [batch][max_pages]
-    const int* seq_lens;     // [batch]
-    int max_pages;
+    PagedParams kv;
+    const uint16_t *k_new, *v_new;  // [total_new][Hkv][D] or null
 };
 
 template <class T>
@@ -251,7 +251,9 @@ __global__ __launch_bounds__(kPrefillThreads, 512 / kPrefillThreads) void sparse
     // start: row of the sequence's first query in q / out; len: keys of the sequence; first: position of
     // that first query (0 unless the keys come from a paged cache that already holds earlier tokens)
     const int start = cu_seqlens[b];
-    const int len = PAGED ? pg.seq_lens[b] : cu_seqlens[b + 1] - start;
+    // cached: keys that come from the pages (all of them, or the history of a chunk whose K / V arrive alongside)
+    const int cached = PAGED ? pg.kv.seq_lens[b] : 0;
+    const int len = PAGED ? (pg.k_new ? cached + (cu_seqlens[b + 1] - start) : cached) : cu_seqlens[b + 1] - start;
     const int first = PAGED ? len - (cu_seqlens[b + 1] - start) : 0;
     const int qblk = first / kRowsPerBlock + blocks_per_seq - 1 - rank / batch;
     if (qblk * kRowsPerBlock >= len) return;
@@ -324,17 +326,31 @@ __global__ __launch_bounds__(kPrefillThreads, 512 / kPrefillThreads) void sparse
     for (int i = 0; i < 16; ++i) neg_m[i] = 0.f;
 
     // ---- staging: every wave issues two direct-to-LDS loads of 1 KiB per tile and operand
-    // contiguous keys: tile jt starts jt * 64 rows after the sequence's first row; paged keys: tile jt is
-    // the slab of (page_table[b][jt], hk), rows 256 bytes apart
-    const uint16_t* kbase = PAGED ? pg.k_pool + (size_t)hk * kTile * kHeadDim : k + ((size_t)start * lp.Hkv + hk) * kHeadDim;
-    const uint16_t* vbase = PAGED ? pg.v_pool + (size_t)hk * kTile * kHeadDim : v + ((size_t)start * lp.Hkv + hk) * kHeadDim;
-    const int* page_row = PAGED ? pg.page_table + (size_t)b * pg.max_pages : nullptr;
+    // contiguous keys: tile jt starts jt * 64 rows after the sequence's first row; paged keys: tile jt is the
+    // slab of (its page, hk) in the pool the head lives in, rows 256 bytes apart; keys of a chunk that has not
+    // been written back: row u - cached of the chunk's own K / V
+    const bool ring = PAGED && in_stream_pool(lp, pg.kv, hk);  // a streaming head kept in its bounded pool
+    const int heads_in_pool = PAGED ? (ring ? pg.kv.stream_heads : pg.kv.pool_heads) : lp.Hkv;
+    const size_t slab_in_page = PAGED ? (size_t)pool_rank(lp, pg.kv, hk, ring) * kTile * kHeadDim : 0;
+    const uint16_t* kbase = PAGED ? reinterpret_cast<const uint16_t*>(ring ? pg.kv.k_stream : pg.kv.k_pool) + slab_in_page
+                                  : k + ((size_t)start * lp.Hkv + hk) * kHeadDim;
+    const uint16_t* vbase = PAGED ? reinterpret_cast<const uint16_t*>(ring ? pg.kv.v_stream : pg.kv.v_pool) + slab_in_page
+                                  : v + ((size_t)start * lp.Hkv + hk) * kHeadDim;
+    const int* page_row = !PAGED ? nullptr
+                          : ring ? pg.kv.ring_table + (size_t)b * pg.kv.ring
+                                 : pg.kv.page_table + (size_t)b * pg.kv.max_pages;
+    // page of key tile jt, for tiles that hold cached keys (0 otherwise: never used)
+    auto page_of = [&](int jt) {
+        if (!PAGED || jt * kTile >= cached) return 0;
+        return page_row[ring ? ring_slot(lp, jt) : jt];
+    };
     // lane `lane` of load i of this wave fills slot (2 wave + i) * 64 + lane of the tile, i.e. position lane % 16
     // of row 4 (2 wave + i) + lane / 16.  Addresses are a wave-uniform 64-bit tile base (scalar arithmetic) plus a
     // 32-bit lane offset that does not depend on the tile, except in the last tile of a sequence, where rows
     // past the end read the last row again (finite values; their softmax weights are 0).
-    const unsigned k_row_bytes = PAGED ? kHeadDim * 2u : (unsigned)__builtin_amdgcn_readfirstlane(lp.Hkv * kHeadDim * 2);
-    const unsigned long long k_page_bytes = (unsigned long long)lp.Hkv * kTile * kHeadDim * 2;
+    const unsigned seq_row_bytes = (unsigned)__builtin_amdgcn_readfirstlane(lp.Hkv * kHeadDim * 2);  // [token][Hkv][D]
+    const unsigned k_row_bytes = PAGED ? kHeadDim * 2u : seq_row_bytes;
+    const unsigned long long k_page_bytes = (unsigned long long)heads_in_pool * kTile * kHeadDim * 2;
     const int krow0 = wave * (4 * kDmaLoads) + lane / 16;  // K row of load 0; load i takes row + 4 i
     unsigned kofs[kDmaLoads], vofs[kDmaLoads];
 #pragma unroll
@@ -344,7 +360,12 @@ __global__ __launch_bounds__(kPrefillThreads, 512 / kPrefillThreads) void sparse
     }
     const unsigned lds_wave = (unsigned)__builtin_amdgcn_readfirstlane(wave * kDmaLoads * 1024);
     const unsigned long long kbase_u = uniform64((unsigned long long)kbase), vbase_u = uniform64((unsigned long long)vbase);
-    const int len_u = __builtin_amdgcn_readfirstlane(len);
+    // the chunk's own rows, addressed from its first token (the row of position `cached`)
+    const unsigned long long knew_u =
+        uniform64((unsigned long long)(PAGED && pg.k_new ? pg.k_new + ((size_t)start * lp.Hkv + hk) * kHeadDim : nullptr));
+    const unsigned long long vnew_u =
+        uniform64((unsigned long long)(PAGED && pg.v_new ? pg.v_new + ((size_t)start * lp.Hkv + hk) * kHeadDim : nullptr));
+    const int len_u = __builtin_amdgcn_readfirstlane(len), cached_u = __builtin_amdgcn_readfirstlane(cached);
     auto fetch = [&](unsigned char* kd, unsigned char* vd, int jt, int phys) {
         jt = __builtin_amdgcn_readfirstlane(jt);
         const unsigned long long ktile =
@@ -354,16 +375,38 @@ __global__ __launch_bounds__(kPrefillThreads, 512 / kPrefillThreads) void sparse
         // Rows at or past the sequence length must not be read as they are: a page may hold anything there, and
         // although their weights are 0 a non-finite value would still poison the second product.
         const int rows_left = len_u - jt * kTile;
+        // rows of the tile below `from_pages` come from the page, the others from the chunk's own K / V
+        const int from_pages = PAGED ? cached_u - jt * kTile : kTile;
+        if (!PAGED || from_pages >= min(rows_left, kTile)) {
 #pragma unroll
-        for (int i = 0; i < kDmaLoads; ++i) {
-            unsigned ko = kofs[i], vo = vofs[i];
-            if (rows_left < kTile) {
-                const int row = krow0 + 4 * i;
-                ko = (unsigned)min(row, rows_left - 1) * k_row_bytes + k_chunk_pos(row, lane % 16) * 16;
-                vo = (unsigned)min(row, rows_left - 1) * k_row_bytes + v_chunk_pos(row, lane % 16) * 16;
+            for (int i = 0; i < kDmaLoads; ++i) {
+                unsigned ko = kofs[i], vo = vofs[i];
+                if (rows_left < kTile) {
+                    const int row = krow0 + 4 * i;
+                    ko = (unsigned)min(row, rows_left - 1) * k_row_bytes + k_chunk_pos(row, lane % 16) * 16;
+                    vo = (unsigned)min(row, rows_left - 1) * k_row_bytes + v_chunk_pos(row, lane % 16) * 16;
+                }
+                dma_load16(ktile, ko, __builtin_amdgcn_readfirstlane(lds_address(kd) + lds_wave + i * 1024));
+                dma_load16(vtile, vo, __builtin_amdgcn_readfirstlane(lds_address(vd) + lds_wave + i * 1024));
             }
-            dma_load16(ktile, ko, __builtin_amdgcn_readfirstlane(lds_address(kd) + lds_wave + i * 1024));
-            dma_load16(vtile, vo, __builtin_amdgcn_readfirstlane(lds_address(vd) + lds_wave + i * 1024));
+        } else {
+            // the tile holds rows of the chunk: row r of the tile is the chunk's token jt * 64 + r - cached
+            const unsigned long long shift = (unsigned long long)((long long)jt * kTile - cached_u) * seq_row_bytes;
+            const unsigned long long ktile_new = knew_u + shift, vtile_new = vnew_u + shift;
+#pragma unroll
+            for (int i = 0; i < kDmaLoads; ++i) {
+                const int row = krow0 + 4 * i, r = min(row, rows_left - 1);
+                const unsigned kc = k_chunk_pos(row, lane % 16) * 16, vc = v_chunk_pos(row, lane % 16) * 16;
+                const unsigned lds_k = __builtin_amdgcn_readfirstlane(lds_address(kd) + lds_wave + i * 1024);
+                const unsigned lds_v = __builtin_amdgcn_readfirstlane(lds_address(vd) + lds_wave + i * 1024);
+                if (r < from_pages) {  // only in the one tile that straddles the end of the cache
+                    dma_load16(ktile, (unsigned)r * k_row_bytes + kc, lds_k);
+                    dma_load16(vtile, (unsigned)r * k_row_bytes + vc, lds_v);
+                } else {
+                    dma_load16(ktile_new, (unsigned)r * seq_row_bytes + kc, lds_k);
+                    dma_load16(vtile_new, (unsigned)r * seq_row_bytes + vc, lds_v);
+                }
+            }
         }
     };
     // Entry `it` of the walk: key tile in the low bits; with a listed mask also which query tiles keep it.
@@ -373,7 +416,7 @@ __global__ __launch_bounds__(kPrefillThreads, 512 / kPrefillThreads) void sparse
     };
     int e_cur = n_visit > 0 ? entry_of(0) : 0, e_nxt = n_visit > 1 ? entry_of(1) : 0;
     // physical pages of the tiles to come, looked up two steps ahead of the loads that need them
-    int ph_cur = PAGED && n_visit > 0 ? page_row[e_cur] : 0, ph_nxt = PAGED && n_visit > 1 ? page_row[e_nxt] : 0;
+    int ph_cur = n_visit > 0 ? page_of(e_cur) : 0, ph_nxt = n_visit > 1 ? page_of(e_nxt) : 0;
 
     // loop-invariant operand offsets of this lane inside a tile
     int koff[8], voff[4];
@@ -393,7 +436,7 @@ __global__ __launch_bounds__(kPrefillThreads, 512 / kPrefillThreads) void sparse
 
     auto tile_step = [&](int it, const unsigned char* ks, const unsigned char* vs, unsigned char* kd, unsigned char* vd) {
         const int e_new = it + 2 < n_visit ? entry_of(it + 2) : 0;  // requested two steps ahead of its use
-        const int ph_new = PAGED && it + 2 < n_visit ? page_row[e_new] : 0;
+        const int ph_new = it + 2 < n_visit ? page_of(e_new) : 0;
         const int jt = e_cur & ((1 << kKeepShift) - 1);
         if (it + 1 < n_visit) fetch(kd, vd, e_nxt & ((1 << kKeepShift) - 1), ph_nxt);
         ph_nxt = ph_new;
@@ -576,7 +619,7 @@ hipError_t launch_prefill(const LayerParams& lp, const void* q, const void* k, c
     }
     const PrefillSchedule sched = make_schedule(lp, blocks_per_seq, batch);
     const int grid = kXcds * (sched.cls[0].items_per_xcd + sched.cls[1].items_per_xcd);
-    const PrefillPaged pg = {};
+    const PrefillPaged pg = {};  // not read by these instantiations
     if (mask)
         hipLaunchKernelGGL((sparse_prefill_kernel<T, kMasked>), dim3(grid), dim3(kPrefillThreads), 0, stream, lp,
                            reinterpret_cast<const uint16_t*>(q), reinterpret_cast<const uint16_t*>(k),
@@ -591,15 +634,13 @@ hipError_t launch_prefill(const LayerParams& lp, const void* q, const void* k, c
 }
 
 template <class T>
-hipError_t launch_prefill_paged(const LayerParams& lp, const PagedParams& kv, const void* q, const int* cu_q,
-                                int total_new, int max_new_per_seq, int max_seqlen, void* out, float* lse_out,
-                                void* workspace, hipStream_t stream) {
+hipError_t launch_prefill_paged(const LayerParams& lp, const PagedParams& kv, const void* q, const void* k_new,
+                                const void* v_new, const int* cu_q, int total_new, int max_new_per_seq, int max_seqlen,
+                                void* out, float* lse_out, void* workspace, hipStream_t stream) {
     PrefillPaged pg;
-    pg.k_pool = reinterpret_cast<const uint16_t*>(kv.k_pool);
-    pg.v_pool = reinterpret_cast<const uint16_t*>(kv.v_pool);
-    pg.page_table = kv.page_table;
-    pg.seq_lens = kv.seq_lens;
-    pg.max_pages = kv.max_pages;
+    pg.kv = kv;
+    pg.k_new = reinterpret_cast<const uint16_t*>(k_new);
+    pg.v_new = reinterpret_cast<const uint16_t*>(v_new);
     (void)workspace;
     (void)max_seqlen;
     // the chunk's rows start anywhere inside a 256-row block: one block more than the chunk length needs
@@ -628,12 +669,13 @@ size_t paged_prefill_workspace_bytes(const LayerParams& lp, int batch, int max_p
 }
 
 hipError_t launch_sparse_prefill_paged(int dtype, const LayerParams& lp, const PagedParams& kv, const void* q,
-                                       const int* cu_q, int total_new, int max_new_per_seq, int max_seqlen, void* out,
-                                       float* lse_out, void* workspace, hipStream_t stream) {
-    return dtype == 0 ? launch_prefill_paged<F16>(lp, kv, q, cu_q, total_new, max_new_per_seq, max_seqlen, out, lse_out,
-                                                  workspace, stream)
-                      : launch_prefill_paged<BF16>(lp, kv, q, cu_q, total_new, max_new_per_seq, max_seqlen, out, lse_out,
-                                                   workspace, stream);
+                                       const void* k_new, const void* v_new, const int* cu_q, int total_new,
+                                       int max_new_per_seq, int max_seqlen, void* out, float* lse_out, void* workspace,
+                                       hipStream_t stream) {
+    return dtype == 0 ? launch_prefill_paged<F16>(lp, kv, q, k_new, v_new, cu_q, total_new, max_new_per_seq, max_seqlen,
+                                                  out, lse_out, workspace, stream)
+                      : launch_prefill_paged<BF16>(lp, kv, q, k_new, v_new, cu_q, total_new, max_new_per_seq, max_seqlen,
+                                                   out, lse_out, workspace, stream);
 }
 
 size_t prefill_workspace_bytes(const LayerParams& lp, int total_tokens, int batch) {

@@ -144,6 +144,14 @@ def test_invalid_arguments_are_rejected_on_the_host(L):
     assert _rc(lambda: L.lserve_sparse_prefill_paged(desc(), dense_only, q, cu4, 2, 64, out, None, ws, stream)) == -1
     assert _rc(lambda: L.lserve_sparse_prefill_paged(desc(page_size=32), kv, q, cu4, 2, 64, out, None, ws, stream)) == -2
     assert L.lserve_paged_prefill_workspace_bytes(desc(), 2, 4) == 0  # keys and values read from the pages
+    # chunk prefill (history in the cache, the chunk's K / V alongside): missing chunk tensors, bounds, page size;
+    # a two-way cache is fine here, but its ring needs its table
+    assert _rc(lambda: L.lserve_sparse_prefill_chunk(desc(), kv, q, None, kn, cu4, 2, out, None, stream)) == -1
+    assert _rc(lambda: L.lserve_sparse_prefill_chunk(desc(), kv, q, kn, kn, cu4, 0, out, None, stream)) == -1
+    assert _rc(lambda: L.lserve_sparse_prefill_chunk(desc(), kv, q, kn, kn, cu4, 3, out, None, stream)) == -1
+    assert _rc(lambda: L.lserve_sparse_prefill_chunk(desc(page_size=32), kv, q, kn, kn, cu4, 2, out, None, stream)) == -2
+    assert _rc(lambda: L.lserve_sparse_prefill_chunk(desc(), no_table, q, kn, kn, cu4, 2, out, None, stream)) == -1
+    assert _rc(lambda: L.lserve_sparse_prefill_chunk(desc(), dense_only, q, kn, kn, cu4, 2, out, None, stream)) == -1
     # quantised pages: only 8 or 4 bits and 64-token pages; no statistics from the pages, no paged prefill
     def q8(bits=8):
         return L.PagedKV(kv.k_pool, kv.v_pool, kv.stats, kv.page_table, kv.seq_lens, kv_bits=bits)
