@@ -119,8 +119,9 @@ typedef struct lserve_attn_desc {
  * in IEEE fp32 with round to nearest even (fp16 conversions saturate at 65504).  lserve_append_kv writes
  * such pages (statistics are taken from the 16-bit keys it is handed) and lserve_sparse_decode reads them;
  * lserve_select_pages works from the statistics alone, so only its rebuild of stale statistics
- * (stats_valid_len) is unavailable; lserve_build_page_stats and lserve_sparse_prefill_paged return
- * LSERVE_ERR_UNSUPPORTED.  The stats array keeps the 16-bit layout.
+ * (stats_valid_len) is unavailable; lserve_sparse_prefill_chunk reads them as the history of a chunk;
+ * lserve_build_page_stats and lserve_sparse_prefill_paged return LSERVE_ERR_UNSUPPORTED.  The stats array keeps the
+ * 16-bit layout.
  */
 typedef struct lserve_paged_kv {
     void *k_pool;              /* device, [num_pages][pool_heads][N_P][D]; quantised: [num_pages][pool_heads][64 * D * kv_bits / 8 + 256] bytes */
@@ -269,11 +270,12 @@ size_t lserve_paged_prefill_workspace_bytes(const lserve_attn_desc *desc, int32_
  * keys u >= S_b from k_new / v_new.  Nothing is written to the cache: call lserve_append_kv with the same k_new, v_new,
  * cu_new (and start_pos = the lengths) afterwards.  With S_b = 0 everywhere this equals lserve_sparse_prefill.
  *
- *   kv           the history, 16-bit rows, N_P = 64: one pool holding every KV head, or the two-way cache (dense
- *                heads in the main pool, streaming heads in their ring: the ring of a sequence of S_b tokens holds the
- *                sink pages and the last w pages, which is every history key a streaming query of the chunk may
- *                attend; the keys between come from the chunk itself).  stats are not used.  Quantised pages:
- *                LSERVE_ERR_UNSUPPORTED.
+ *   kv           the history, N_P = 64: one pool holding every KV head, or the two-way cache (dense heads in the
+ *                main pool, streaming heads in their ring: the ring of a sequence of S_b tokens holds the sink pages
+ *                and the last w pages, which is every history key a streaming query of the chunk may attend; the keys
+ *                between come from the chunk itself).  Pages of 16-bit rows or quantised pages (kv_bits 8 or 4): a
+ *                history key / value is then the number its code stands for, code * scale + zero, computed in fp32
+ *                and rounded to the layer's 16-bit type on its way to the matrix cores.  stats are not used.
  *   q            device [total_new][H][D]; k_new, v_new device [total_new][Hkv][D]
  *   cu_new       device [batch + 1] (batch = kv->batch), cu_new[0] = 0, n_b >= 0
  *   max_new_per_seq  host bound of n_b (> 0)

@@ -283,7 +283,6 @@ int lserve_sparse_prefill_chunk(const lserve_attn_desc* desc, const lserve_paged
     rc = make_paged(kv, lp, true, true, false, true, &pp);
     if (rc) return rc;
     if (lp.NP != 64) return LSERVE_ERR_UNSUPPORTED;
-    if (pp.kv_bits != 16) return LSERVE_ERR_UNSUPPORTED;
     if (!q || !k_new || !v_new || !cu_new || !out) return LSERVE_ERR_INVALID_ARG;
     if (total_new <= 0 || max_new_per_seq <= 0 || max_new_per_seq > total_new) return LSERVE_ERR_INVALID_ARG;
     if (!aligned16(q) || !aligned16(k_new) || !aligned16(v_new) || !aligned16(cu_new) || !aligned16(out) ||

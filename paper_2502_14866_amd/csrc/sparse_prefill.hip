@@ -221,12 +221,16 @@ template <> struct Ones<BF16> { static constexpr uint32_t pair = 0x3f803f80u; };
 
 enum PrefillMode { kPlain = 0, kMasked = 1, kPaged = 2 };
 
-template <class T, int MODE>
+// BITS: width of the rows in the pages (16, or 8 / 4 for quantised pages, kPaged only).  Quantised tiles cannot take
+// the direct-to-LDS path: their codes travel through registers, are turned into the layer's 16-bit type as
+// code * scale + zero (fp32, then rounded) and are stored to the same LDS places the direct loads would fill.
+template <class T, int MODE, int BITS = 16>
 __global__ __launch_bounds__(kPrefillThreads, 512 / kPrefillThreads) void sparse_prefill_kernel(
     LayerParams lp, const uint16_t* __restrict__ q, const uint16_t* __restrict__ k, const uint16_t* __restrict__ v,
     const int* __restrict__ cu_seqlens, int batch, int blocks_per_seq, uint16_t* __restrict__ out,
     float* __restrict__ lse_out, int total_tokens, PrefillSchedule sched, PrefillMask mk, PrefillPaged pg) {
-    constexpr bool MASKED = MODE == kMasked, PAGED = MODE == kPaged;
+    constexpr bool MASKED = MODE == kMasked, PAGED = MODE == kPaged, QUANT = BITS != 16;
+    static_assert(!QUANT || PAGED, "quantised rows live in pages");
     // Two stages of (K tile, V tile).  Four separate arrays, and a loop unrolled over the two stages,
     // so that the compiler can tell the tile being read from the tile being filled and does not wait
     // for the loads in flight before every operand read.
@@ -331,7 +335,8 @@ __global__ __launch_bounds__(kPrefillThreads, 512 / kPrefillThreads) void sparse
     // been written back: row u - cached of the chunk's own K / V
     const bool ring = PAGED && in_stream_pool(lp, pg.kv, hk);  // a streaming head kept in its bounded pool
     const int heads_in_pool = PAGED ? (ring ? pg.kv.stream_heads : pg.kv.pool_heads) : lp.Hkv;
-    const size_t slab_in_page = PAGED ? (size_t)pool_rank(lp, pg.kv, hk, ring) * kTile * kHeadDim : 0;
+    constexpr size_t kSlabBytes = slab_chunks(kTile, BITS) * 16;  // one (page, head) of a pool
+    const size_t slab_in_page = PAGED ? (size_t)pool_rank(lp, pg.kv, hk, ring) * (kSlabBytes / 2) : 0;  // in 16-bit units
     const uint16_t* kbase = PAGED ? reinterpret_cast<const uint16_t*>(ring ? pg.kv.k_stream : pg.kv.k_pool) + slab_in_page
                                   : k + ((size_t)start * lp.Hkv + hk) * kHeadDim;
     const uint16_t* vbase = PAGED ? reinterpret_cast<const uint16_t*>(ring ? pg.kv.v_stream : pg.kv.v_pool) + slab_in_page
@@ -350,7 +355,7 @@ __global__ __launch_bounds__(kPrefillThreads, 512 / kPrefillThreads) void sparse
     // past the end read the last row again (finite values; their softmax weights are 0).
     const unsigned seq_row_bytes = (unsigned)__builtin_amdgcn_readfirstlane(lp.Hkv * kHeadDim * 2);  // [token][Hkv][D]
     const unsigned k_row_bytes = PAGED ? kHeadDim * 2u : seq_row_bytes;
-    const unsigned long long k_page_bytes = (unsigned long long)heads_in_pool * kTile * kHeadDim * 2;
+    const unsigned long long k_page_bytes = (unsigned long long)heads_in_pool * kSlabBytes;
     const int krow0 = wave * (4 * kDmaLoads) + lane / 16;  // K row of load 0; load i takes row + 4 i
     unsigned kofs[kDmaLoads], vofs[kDmaLoads];
 #pragma unroll
@@ -366,8 +371,49 @@ __global__ __launch_bounds__(kPrefillThreads, 512 / kPrefillThreads) void sparse
     const unsigned long long vnew_u =
         uniform64((unsigned long long)(PAGED && pg.v_new ? pg.v_new + ((size_t)start * lp.Hkv + hk) * kHeadDim : nullptr));
     const int len_u = __builtin_amdgcn_readfirstlane(len), cached_u = __builtin_amdgcn_readfirstlane(cached);
+    // quantised rows on their way through registers: per load the codes of this lane's 16-byte place (8 channels) of
+    // K and of V, the (scale, zero) pairs of the row, and whether the lane's row comes from the pages at all
+    constexpr int kRowCodeBytes = kHeadDim * BITS / 8, kPlaceCodeBytes = BITS;  // per row; per 8 channels
+    uint2 staged_k[kDmaLoads], staged_v[kDmaLoads];
+    uint32_t staged_ksz[kDmaLoads], staged_vsz[kDmaLoads];
+    int staged_from = 0, staged_left = 1;  // of the tile in flight: rows that come from the pages; rows it has
     auto fetch = [&](unsigned char* kd, unsigned char* vd, int jt, int phys) {
         jt = __builtin_amdgcn_readfirstlane(jt);
+        if constexpr (QUANT) {
+            const int rows_left = len_u - jt * kTile;
+            const int from_pages = cached_u - jt * kTile;  // rows of the tile below this come from the pages
+            staged_from = from_pages;
+            staged_left = rows_left;
+            const unsigned char* kslab = reinterpret_cast<const unsigned char*>(kbase) +
+                                         (size_t)(unsigned)__builtin_amdgcn_readfirstlane(phys) * k_page_bytes;
+            const unsigned char* vslab = kslab - reinterpret_cast<const unsigned char*>(kbase) +
+                                         reinterpret_cast<const unsigned char*>(vbase);
+            const unsigned long long shift = (unsigned long long)((long long)jt * kTile - cached_u) * seq_row_bytes;
+#pragma unroll
+            for (int i = 0; i < kDmaLoads; ++i) {
+                const int row = krow0 + 4 * i, r = min(row, rows_left - 1);
+                const int kplace = k_chunk_pos(row, lane % 16), vplace = v_chunk_pos(row, lane % 16);
+                if (r < from_pages) {
+                    const unsigned char* kr = kslab + (size_t)r * kRowCodeBytes + kplace * kPlaceCodeBytes;
+                    const unsigned char* vr = vslab + (size_t)r * kRowCodeBytes + vplace * kPlaceCodeBytes;
+                    if constexpr (BITS == 8) {
+                        staged_k[i] = *reinterpret_cast<const uint2*>(kr);
+                        staged_v[i] = *reinterpret_cast<const uint2*>(vr);
+                    } else {
+                        staged_k[i] = make_uint2(*reinterpret_cast<const uint32_t*>(kr), 0u);
+                        staged_v[i] = make_uint2(*reinterpret_cast<const uint32_t*>(vr), 0u);
+                    }
+                    staged_ksz[i] = reinterpret_cast<const uint32_t*>(kslab + kTile * kRowCodeBytes)[r];
+                    staged_vsz[i] = reinterpret_cast<const uint32_t*>(vslab + kTile * kRowCodeBytes)[r];
+                } else {  // a row of the chunk: 16-bit, straight to LDS
+                    dma_load16(knew_u + shift, (unsigned)r * seq_row_bytes + kplace * 16,
+                               __builtin_amdgcn_readfirstlane(lds_address(kd) + lds_wave + i * 1024));
+                    dma_load16(vnew_u + shift, (unsigned)r * seq_row_bytes + vplace * 16,
+                               __builtin_amdgcn_readfirstlane(lds_address(vd) + lds_wave + i * 1024));
+                }
+            }
+            return;
+        }
         const unsigned long long ktile =
             PAGED ? kbase_u + (unsigned long long)(unsigned)__builtin_amdgcn_readfirstlane(phys) * k_page_bytes
                   : kbase_u + (unsigned long long)jt * (kTile * k_row_bytes);
@@ -433,6 +479,37 @@ __global__ __launch_bounds__(kPrefillThreads, 512 / kPrefillThreads) void sparse
         const int chunk = 4 * db + 2 * (n / 16) + (s16 % 4) / 2;
         voff[db] = half * 1024 + rr * kVRowBytes + v_chunk_pos(rr, chunk) * 16 + 8 * (s16 % 2);
     }
+
+    // Quantised rows fetched for the tile in flight: eight codes -> code * scale + zero -> eight 16-bit values at the
+    // lane's place of the row in LDS (the place a direct load of the same row would have filled).
+    auto dequantise8 = [&](uint2 codes, uint32_t scale_zero) {
+        const half2_t sz = __builtin_bit_cast(half2_t, scale_zero);
+        const float scale = (float)sz[0], zero = (float)sz[1];
+        uint32_t lo = codes.x, hi = codes.y;  // channels 0..3 and 4..7, one byte each
+        if constexpr (BITS == 4) {
+            hi = (codes.x >> 4) & 0x0f0f0f0fu;
+            lo = codes.x & 0x0f0f0f0fu;
+        }
+        float x[8];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            x[j] = __builtin_fmaf((float)((lo >> (8 * j)) & 0xffu), scale, zero);
+            x[4 + j] = __builtin_fmaf((float)((hi >> (8 * j)) & 0xffu), scale, zero);
+        }
+        return pack8<T>(x);
+    };
+    auto store_staged = [&](unsigned char* kd, unsigned char* vd) {
+        if constexpr (QUANT) {
+            if (staged_from <= 0) return;
+#pragma unroll
+            for (int i = 0; i < kDmaLoads; ++i) {
+                if (min(krow0 + 4 * i, staged_left - 1) < staged_from) {  // the lanes that fetch() gave codes
+                    *reinterpret_cast<uint4*>(kd + lds_wave + i * 1024 + lane * 16) = dequantise8(staged_k[i], staged_ksz[i]);
+                    *reinterpret_cast<uint4*>(vd + lds_wave + i * 1024 + lane * 16) = dequantise8(staged_v[i], staged_vsz[i]);
+                }
+            }
+        }
+    };
 
     auto tile_step = [&](int it, const unsigned char* ks, const unsigned char* vs, unsigned char* kd, unsigned char* vd) {
         const int e_new = it + 2 < n_visit ? entry_of(it + 2) : 0;  // requested two steps ahead of its use
@@ -538,11 +615,15 @@ __global__ __launch_bounds__(kPrefillThreads, 512 / kPrefillThreads) void sparse
                 for (int db = 0; db < 4; ++db) acc[db] = Mfma<T>::run(va[db], pb[kb][j], acc[db]);
             }
         }
+        if (it + 1 < n_visit) store_staged(kd, vd);
         dma_wait();
         __syncthreads();  // the next tile has landed and this one is free
     };
 
-    if (n_visit > 0) fetch(k_lds0, v_lds0, e_cur & ((1 << kKeepShift) - 1), ph_cur);
+    if (n_visit > 0) {
+        fetch(k_lds0, v_lds0, e_cur & ((1 << kKeepShift) - 1), ph_cur);
+        store_staged(k_lds0, v_lds0);
+    }
     dma_wait();
     __syncthreads();
     for (int it = 0; it < n_visit; it += 2) {
@@ -648,9 +729,17 @@ hipError_t launch_prefill_paged(const LayerParams& lp, const PagedParams& kv, co
     const PrefillSchedule sched = make_schedule(lp, blocks_per_seq, kv.batch);
     const int grid = kXcds * (sched.cls[0].items_per_xcd + sched.cls[1].items_per_xcd);
     const PrefillMask mk = {};
-    hipLaunchKernelGGL((sparse_prefill_kernel<T, kPaged>), dim3(grid), dim3(kPrefillThreads), 0, stream, lp,
-                       reinterpret_cast<const uint16_t*>(q), nullptr, nullptr, cu_q, kv.batch, blocks_per_seq,
-                       reinterpret_cast<uint16_t*>(out), lse_out, total_new, sched, mk, pg);
+#define LSERVE_PREFILL_PAGED(BITS)                                                                                     \
+    hipLaunchKernelGGL((sparse_prefill_kernel<T, kPaged, BITS>), dim3(grid), dim3(kPrefillThreads), 0, stream, lp,     \
+                       reinterpret_cast<const uint16_t*>(q), nullptr, nullptr, cu_q, kv.batch, blocks_per_seq,         \
+                       reinterpret_cast<uint16_t*>(out), lse_out, total_new, sched, mk, pg)
+    if (kv.kv_bits == 8)
+        LSERVE_PREFILL_PAGED(8);
+    else if (kv.kv_bits == 4)
+        LSERVE_PREFILL_PAGED(4);
+    else
+        LSERVE_PREFILL_PAGED(16);
+#undef LSERVE_PREFILL_PAGED
     return hipGetLastError();
 }
 

@@ -168,3 +168,102 @@ def test_prefill_in_chunks_over_the_two_way_cache_attention_first_then_write_bac
                                                                      f"two-way chunk {dtype} {hist}->{now}", dropped)
         L.lserve_append_kv(desc, kv, kc.to(dev), vc.to(dev), _pad4(cu_new, dev), _pad4(list(hist), dev), max(max(chunks), 1))
         hist = list(now)
+
+
+# ---- the paper's cache: quantised pages, two-way -------------------------------------------------------------
+
+def _cache_values(kv, bits, page_table, ring_table, hist, n_kv_heads, streaming, s_pages, w_pages):
+    """float64 [B, max hist, Hkv, D] x 2 of what the cache holds for every history position (NaN where it holds
+    nothing): bytes of the pools read back, codes / scales / zero points taken apart, code * scale + zero."""
+    from test_gpu_quant import _values
+
+    def vals(pool):
+        return None if pool is None else _values(pool.cpu(), bits)
+    km, vm, kr, vr = vals(kv.k_pool), vals(kv.v_pool), vals(kv.k_pool_stream), vals(kv.v_pool_stream)
+    dense = [h for h in range(n_kv_heads) if h not in streaming]
+    B = len(hist)
+    stride = max(max(hist), 1)
+    kh = np.full((B, stride, n_kv_heads, 128), np.nan)
+    vh = np.full_like(kh, np.nan)
+    for b, S in enumerate(hist):
+        P = -(-S // NP)
+        for u in range(S):
+            p, t = u // NP, u % NP
+            for hk in range(n_kv_heads):
+                if kr is not None and hk in streaming:
+                    if not (p < s_pages or p >= P - w_pages):
+                        continue  # dropped by the ring
+                    slot = p if p < s_pages else s_pages + (p - s_pages) % w_pages
+                    page, rank = int(ring_table[b, slot]), list(streaming).index(hk)
+                    kh[b, u, hk], vh[b, u, hk] = kr[page, rank, t], vr[page, rank, t]
+                else:
+                    page = int(page_table[b, p])
+                    rank = dense.index(hk) if km.shape[1] != n_kv_heads else hk
+                    kh[b, u, hk], vh[b, u, hk] = km[page, rank, t], vm[page, rank, t]
+    return kh, vh
+
+
+# bf16: the dequantised key is rounded to bf16 (2^-9 relative) like the scaled query, which adds a second term of the
+# same size to the logit error: sqrt(2) x the 9e-3 four-sigma bound of the 16-bit cache
+LSE_TOL_QUANT_HISTORY = {"fp16": 2e-3, "bf16": 1.3e-2}
+
+
+@pytest.mark.parametrize("bits", [8, 4])
+@pytest.mark.parametrize("dtype", ["fp16", "bf16"])
+@pytest.mark.parametrize("two_way", [False, True])
+def test_prefill_in_chunks_over_quantised_pages_attention_first_then_quantising_write_back(dtype, bits, two_way):
+    """The cache the paper keeps: low-bit pages, streaming heads in their ring.  Each chunk attends the numbers the
+    bytes of the cache stand for (read back and dequantised on the CPU for the oracle) plus its own 16-bit K / V,
+    then the quantising write-back adds it to the cache."""
+    L = _lib()
+    dev = torch.device("cuda:0")
+    lengths = (900, 333, 64)
+    steps = [(300, 100, 0), (557, 101, 30), (558, 300, 64), (900, 333, 64)]
+    B_ = len(lengths)
+    streaming = (0, 2)
+    w = Workload(name="cpq", batch=B_, num_q_heads=8, num_kv_heads=4, dtype=dtype, streaming_kv_heads=streaming,
+                 sink_tokens=64, local_tokens=192, seed=47)
+    s_pages, w_pages = 1, 3
+    ring = s_pages + w_pages
+    pin = make_prefill_inputs(w, lengths=lengths)
+    max_pages = max(-(-l // NP) for l in lengths) + 1
+    g = torch.Generator().manual_seed(31)
+    page_table = torch.randperm(B_ * max_pages + 2, generator=g)[:B_ * max_pages].to(torch.int32).reshape(B_, max_pages)
+    ring_table = torch.randperm(B_ * ring + 3, generator=g)[:B_ * ring].to(torch.int32).reshape(B_, ring)
+    slab = 64 * 128 * bits // 8 + 256
+    main_heads = 2 if two_way else 4
+    mk = lambda pages, heads: torch.full((pages, heads, slab), 0xff, dtype=torch.uint8, device=dev)  # NaN scales / zeros
+    stats = torch.zeros((B_ * max_pages + 2, main_heads, 4, 2, 128), dtype=pin.k.dtype, device=dev)
+    kv = L.PagedKV(mk(B_ * max_pages + 2, main_heads), mk(B_ * max_pages + 2, main_heads), stats, page_table.to(dev),
+                   _pad4([0] * B_, dev), kv_bits=bits)
+    if two_way:
+        kv.pool_heads = 2
+        kv.k_pool_stream, kv.v_pool_stream = mk(B_ * ring + 3, 2), mk(B_ * ring + 3, 2)
+        kv.ring_table = ring_table.to(dev)
+    desc = L.AttnDesc(w.num_q_heads, w.num_kv_heads, w.streaming_flags(), dtype=w.torch_dtype,
+                      sink_tokens=w.sink_tokens, local_tokens=w.local_tokens)
+    H = w.num_q_heads
+    hist = [0] * B_
+    for now in steps:
+        qc, kc, vc, _ = _split(pin, now, hist)
+        chunks = [a - h for a, h in zip(now, hist)]
+        total_new = qc.shape[0]
+        cu_new = np.concatenate([[0], np.cumsum(chunks)]).astype(np.int32)
+        kh, vh = _cache_values(kv, bits, page_table, ring_table, hist, w.num_kv_heads, streaming if two_way else (),
+                               s_pages, w_pages)
+        out = torch.full((total_new, H, 128), float("nan"), dtype=qc.dtype, device=dev)
+        lse = torch.full((H, total_new), float("nan"), dtype=torch.float32, device=dev)
+        kv.seq_lens = _pad4(list(hist), dev)
+        qd, kd, vd = qc.to(dev), kc.to(dev), vc.to(dev)
+        L.lserve_sparse_prefill_chunk(desc, kv, qd, kd, vd, _pad4(cu_new, dev), max(chunks), out, lse)
+        torch.cuda.synchronize()
+        tok = np.repeat(np.arange(total_new, dtype=np.int32), H)
+        head = np.tile(np.arange(H, dtype=np.int32), total_new)
+        ref, lse_ref = oracle.chunk_prefill_rows(qc, kc, vc, kh, vh, np.asarray(hist, np.int32), cu_new,
+                                                 w.streaming_flags(), NP, w.sink_tokens, w.local_tokens, tok, head)
+        assert np.isfinite(ref).all()
+        what = f"quantised chunk {dtype} {bits} bit two_way={two_way} {hist}->{list(now)}"
+        assert_attention_close(out, ref.reshape(total_new, H, -1), what)
+        assert_lse_close(lse.t().contiguous(), lse_ref.reshape(total_new, H), what + " lse", LSE_TOL_QUANT_HISTORY[dtype])
+        L.lserve_append_kv(desc, kv, kd, vd, _pad4(cu_new, dev), _pad4(list(hist), dev), max(max(chunks), 1))
+        hist = list(now)
