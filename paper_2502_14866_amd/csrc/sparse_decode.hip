@@ -152,14 +152,26 @@ __device__ __forceinline__ void load_v(Slabs<64, 8>& s, const uint4* vslab, int 
 template <int N> struct WaveState {
     float m[N], l[N], o[N][8];
     float z[N];  // quantised values only: sum of weight * zero point, the same for every channel
+    // Quantised pages keep the softmax of a token in the four lanes that read its key, one query head (two for
+    // groups above four) per lane: lane l of a wave owns heads l % 4 and l % 4 + 4.  Running maximum, sum of weights
+    // and zero-point sum of those heads; w_sum: per head, the sum of the 16-bit weights this lane fed to `o`.
+    static constexpr int kHeadsPerLane = (N + 3) / 4;
+    float lane_m[kHeadsPerLane], lane_l[kHeadsPerLane], lane_z[kHeadsPerLane], w_sum[N];
     __device__ __forceinline__ void reset() {
 #pragma unroll
         for (int hh = 0; hh < N; ++hh) {
             m[hh] = -INFINITY;
             l[hh] = 0.f;
             z[hh] = 0.f;
+            w_sum[hh] = 0.f;
 #pragma unroll
             for (int i = 0; i < 8; ++i) o[hh][i] = 0.f;
+        }
+#pragma unroll
+        for (int g = 0; g < kHeadsPerLane; ++g) {
+            lane_m[g] = -INFINITY;
+            lane_l[g] = 0.f;
+            lane_z[g] = 0.f;
         }
     }
 };
@@ -277,6 +289,36 @@ __device__ __forceinline__ void process_quarter_page(WaveState<N>& st, const uin
     __builtin_amdgcn_wave_barrier();
 }
 
+// Value of lane k of the caller's group of four lanes.
+__device__ __forceinline__ float quad_lane(float x, int k) {
+    switch (k) {
+        case 0: return dpp_f<0x00>(x);
+        case 1: return dpp_f<0x55>(x);
+        case 2: return dpp_f<0xAA>(x);
+        default: return dpp_f<0xFF>(x);
+    }
+}
+
+// Sums x0 .. x3 over the four lanes that share a token; lane k of the four receives the total of x_k.
+__device__ __forceinline__ float quad_sum_scatter(float x0, float x1, float x2, float x3, int lane) {
+    const bool odd = lane & 1, upper = lane & 2;
+    float a0 = odd ? x1 : x0, a1 = odd ? x3 : x2;
+    const float b0 = odd ? x0 : x1, b1 = odd ? x2 : x3;
+    a0 += dpp_f<kDppXor1>(b0);
+    a1 += dpp_f<kDppXor1>(b1);
+    const float keep = upper ? a1 : a0, send = upper ? a0 : a1;
+    return keep + dpp_f<kDppXor2>(send);
+}
+
+// Maximum over the sixteen lanes of a wave that have the caller's lane % 4; all of them receive it.
+__device__ __forceinline__ float wave_max_same_quarter(float x) {
+    x = fmaxf(x, dpp_f<0x124>(x));  // row_ror:4
+    x = fmaxf(x, dpp_f<0x128>(x));  // row_ror:8
+    return rows4_max(x);
+}
+
+constexpr float kWeightScale = 64.f;  // keeps weight * scale clear of the fp16 subnormals, and below 65504 for any fp16 row
+
 // The same over a quantised quarter page.  q_lds holds the queries as fp16 whatever the storage type and
 // q_sum[h] the sum of query h's channels.  With k = code * scale + zero the logit of a token is
 //   q . k = scale * (q . code) + zero * sum(q).
@@ -285,16 +327,29 @@ __device__ __forceinline__ void process_quarter_page(WaveState<N>& st, const uin
 // to every dot product is taken off again.  For values the weight is folded into the scale,
 //   sum_t p_t v_t = sum_t (p_t scale_t) code_t + sum_t p_t zero_t,
 // and the second sum, which no channel distinguishes, is kept as one number per query head.
+//
+// The instruction count, not the memory system, bounds this path (a page is half or a quarter of the bytes for the
+// same number of tokens), so it is arranged to issue as little as possible per token:
+//   - after the dot products the four lanes of a token hold four partial sums for each of N heads; a reduce-scatter
+//     leaves lane k with the total of head k, and maximum, exponential, sums and scales are then computed once
+//     per (token, head) instead of four times;
+//   - the weights go to LDS as fp16 (times kWeightScale), two tokens of a value row side by side, so that the
+//     value side reads ready-made pairs and takes two tokens per packed dot instruction, with the codes of the
+//     two tokens interleaved by byte permutes and lifted to 1024 + code like the keys; the 1024 * (sum of the
+//     rounded weights) this adds to every channel is subtracted, and the scale undone, once per piece of a list
+//     (lane_state_to_wave_state).  A weight is rounded to fp16 (2^-11 relative) before it meets the codes; the
+//     denominator keeps the unrounded weights.
+// p_lds is read as 16-bit [token pair][value row r][p_row(N) heads][2 tokens].
 template <class T, int N, int BITS>
 __device__ __forceinline__ void process_quantised_quarter_page(WaveState<N>& st, const uint4* q_lds, const float* q_sum,
                                                      float* p_lds, Slabs<64, BITS>& cur, int valid, int tok0, int lane,
                                                      float scale_log2) {
     static_assert(BITS == 8 || BITS == 4, "quantised pages");
-    constexpr int PR = p_row(N);
-    const int r = lane / 16;
-    float s[N];
+    constexpr int PR = p_row(N), HPL = WaveState<N>::kHeadsPerLane;
+    const int r = lane / 16, qd = lane % 4;
+    float s[4 * HPL];
 #pragma unroll
-    for (int hh = 0; hh < N; ++hh) s[hh] = 0.f;
+    for (int hh = 0; hh < 4 * HPL; ++hh) s[hh] = 0.f;
     // 16 channels at a time: four bytes-per-code words (two of the 8-bit chunk's words, or the low and the high
     // halves of two of the 4-bit chunk's words) become eight fp16 pairs and meet two 8-channel query chunks
 #pragma unroll
@@ -326,61 +381,94 @@ __device__ __forceinline__ void process_quantised_quarter_page(WaveState<N>& st,
     }
     const bool dead = valid < 64 && tok0 + lane / 4 >= valid;
     const half2_t ksz = __builtin_bit_cast(half2_t, cur.ksz), vsz = __builtin_bit_cast(half2_t, cur.vsz);
-    const float k_scale = (float)ksz[0], k_zero = (float)ksz[1];
-    const float v_scale = dead ? 0.f : (float)vsz[0], v_zero = dead ? 0.f : (float)vsz[1];  // slots past the end may hold anything
-    float wgt[N];
+    const float k_scale = (float)ksz[0] * scale_log2, k_zero = (float)ksz[1] * scale_log2;
+    // slots past the end may hold anything
+    const float v_scale = dead ? 0.f : (float)vsz[0] * kWeightScale, v_zero = dead ? 0.f : (float)vsz[1];
+    // this lane's place in the weight buffer: token lane / 4 of the quarter page is member (t / 4) % 2 of pair t / 8 of
+    // value row t % 4
+    const int t = lane / 4;
+    _Float16* w_lds = reinterpret_cast<_Float16*>(p_lds) + (((t / 8) * 4 + t % 4) * PR + qd) * 2 + (t / 4) % 2;
 #pragma unroll
-    for (int hh = 0; hh < N; ++hh) {
-        const float dot = token_sum<4>(s[hh]) - 1024.f * q_sum[hh];
-        const float x = (k_scale * dot + k_zero * q_sum[hh]) * scale_log2;
-        float pm = wave_max_of_quads(dead ? -INFINITY : x);
-        if (pm > st.m[hh]) {  // wave-uniform: rescale only when the running maximum moves
-            const float alpha = __builtin_amdgcn_exp2f(st.m[hh] - pm);
-            st.m[hh] = pm;
-            st.l[hh] *= alpha;
-            st.z[hh] *= alpha;
+    for (int g = 0; g < HPL; ++g) {
+        const bool mine = 4 * g + qd < N;  // lanes without a head of their own carry zeros along
+        const float qs = mine ? q_sum[4 * g + qd] : 0.f;
+        const float dot = quad_sum_scatter(s[4 * g], s[4 * g + 1], s[4 * g + 2], s[4 * g + 3], lane) - 1024.f * qs;
+        const float x = dead ? -INFINITY : __builtin_fmaf(k_scale, dot, k_zero * qs);
+        const float pm = wave_max_same_quarter(x);
+        const bool moved = pm > st.lane_m[g];
+        if (__any(moved)) {  // rare after the first pages: some head's running maximum moves
+            const float alpha = moved ? __builtin_amdgcn_exp2f(st.lane_m[g] - pm) : 1.f;
+            st.lane_m[g] = moved ? pm : st.lane_m[g];
+            st.lane_l[g] *= alpha;
+            st.lane_z[g] *= alpha;
 #pragma unroll
-            for (int i = 0; i < 8; ++i) st.o[hh][i] *= alpha;
+            for (int k = 0; k < 4; ++k) {
+                if (4 * g + k >= N) continue;
+                const float a = quad_lane(alpha, k);
+                st.w_sum[4 * g + k] *= a;
+#pragma unroll
+                for (int i = 0; i < 8; ++i) st.o[4 * g + k][i] *= a;
+            }
         }
-        const float m_safe = st.m[hh] == -INFINITY ? 0.f : st.m[hh];
+        const float m_safe = st.lane_m[g] == -INFINITY ? 0.f : st.lane_m[g];
         const float p = dead ? 0.f : __builtin_amdgcn_exp2f(x - m_safe);
-        st.l[hh] += p;  // counted once per lane of the token: divided by 4 at the end, and so is z
-        st.z[hh] += p * v_zero;
-        wgt[hh] = p * v_scale;
-    }
-    if (lane % 4 == 0) {
-        float* dst = p_lds + (lane / 4) * PR;
-#pragma unroll
-        for (int hh = 0; hh < N; ++hh) dst[hh] = wgt[hh];
+        st.lane_l[g] += p;
+        st.lane_z[g] = __builtin_fmaf(p, v_zero, st.lane_z[g]);
+        w_lds[8 * g] = (_Float16)(p * v_scale);  // head 4 g + qd: four heads = four token pairs = eight halves on
     }
     __builtin_amdgcn_wave_barrier();
 #pragma unroll
-    for (int it = 0; it < 4; ++it) {
-        uint2 vv;  // one byte per code, channels in order
+    for (int pr = 0; pr < 2; ++pr) {
+        uint32_t ta[2], tb[2];  // one byte per code, channels 0 .. 3 and 4 .. 7 of the pair's two tokens
         if constexpr (BITS == 8) {
-            vv = cur.v[it];
+            ta[0] = cur.v[2 * pr].x, ta[1] = cur.v[2 * pr].y;
+            tb[0] = cur.v[2 * pr + 1].x, tb[1] = cur.v[2 * pr + 1].y;
         } else {
-            vv = make_uint2(cur.v[it] & 0x0f0f0f0fu, (cur.v[it] >> 4) & 0x0f0f0f0fu);
+            ta[0] = cur.v[2 * pr] & 0x0f0f0f0fu, ta[1] = (cur.v[2 * pr] >> 4) & 0x0f0f0f0fu;
+            tb[0] = cur.v[2 * pr + 1] & 0x0f0f0f0fu, tb[1] = (cur.v[2 * pr + 1] >> 4) & 0x0f0f0f0fu;
         }
-        if (valid < 64 && tok0 + 4 * it + r >= valid) vv = make_uint2(0, 0);
-        float pv[PR];
+        uint32_t wp[PR];  // (weight of the first token, weight of the second) per head, fp16
 #pragma unroll
         for (int x4 = 0; x4 < PR / 4; ++x4) {
-            const float4 t4 = *reinterpret_cast<const float4*>(p_lds + (4 * it + r) * PR + 4 * x4);
-            pv[4 * x4] = t4.x;
-            pv[4 * x4 + 1] = t4.y;
-            pv[4 * x4 + 2] = t4.z;
-            pv[4 * x4 + 3] = t4.w;
+            const uint4 w4 = *reinterpret_cast<const uint4*>(reinterpret_cast<const uint32_t*>(p_lds) + (pr * 4 + r) * PR + 4 * x4);
+            wp[4 * x4] = w4.x, wp[4 * x4 + 1] = w4.y, wp[4 * x4 + 2] = w4.z, wp[4 * x4 + 3] = w4.w;
         }
-        const float code[8] = {(float)(vv.x & 0xffu), (float)((vv.x >> 8) & 0xffu), (float)((vv.x >> 16) & 0xffu),
-                               (float)(vv.x >> 24),   (float)(vv.y & 0xffu),        (float)((vv.y >> 8) & 0xffu),
-                               (float)((vv.y >> 16) & 0xffu), (float)(vv.y >> 24)};
+        uint32_t ch[8];  // channel i of both tokens as an fp16 pair (1024 + code)
 #pragma unroll
-        for (int hh = 0; hh < N; ++hh)
+        for (int u = 0; u < 2; ++u) {
+            const uint32_t lo = __builtin_amdgcn_perm(tb[u], ta[u], 0x05010400u);  // a0 b0 a1 b1
+            const uint32_t hi = __builtin_amdgcn_perm(tb[u], ta[u], 0x07030602u);  // a2 b2 a3 b3
+            ch[4 * u] = __builtin_amdgcn_perm(0x64646464u, lo, 0x04010400u);
+            ch[4 * u + 1] = __builtin_amdgcn_perm(0x64646464u, lo, 0x04030402u);
+            ch[4 * u + 2] = __builtin_amdgcn_perm(0x64646464u, hi, 0x04010400u);
+            ch[4 * u + 3] = __builtin_amdgcn_perm(0x64646464u, hi, 0x04030402u);
+        }
 #pragma unroll
-            for (int i = 0; i < 8; ++i) st.o[hh][i] = __builtin_fmaf(pv[hh], code[i], st.o[hh][i]);
+        for (int hh = 0; hh < N; ++hh) {
+            st.w_sum[hh] = Elem<F16>::dot2(wp[hh], 0x3c003c00u, st.w_sum[hh]);
+#pragma unroll
+            for (int i = 0; i < 8; ++i) st.o[hh][i] = Elem<F16>::dot2(wp[hh], ch[i], st.o[hh][i]);
+        }
     }
     __builtin_amdgcn_wave_barrier();
+}
+
+// Turns the per-lane softmax state of the quantised path into the form flush_block() folds: per head a wave-uniform
+// maximum, per-lane sums that add up (over the wave) to four times the head's total, and outputs with the code
+// offset and the weight scale taken off.
+template <int N>
+__device__ __forceinline__ void lane_state_to_wave_state(WaveState<N>& st, int lane) {
+    const int qd = lane % 4;
+#pragma unroll
+    for (int hh = 0; hh < N; ++hh) {
+        const int g = hh / 4, k = hh % 4;
+        st.m[hh] = quad_lane(st.lane_m[g], k);
+        st.l[hh] = qd == k ? 4.f * st.lane_l[g] : 0.f;
+        st.z[hh] = qd == k ? 4.f * st.lane_z[g] : 0.f;
+#pragma unroll
+        for (int i = 0; i < 8; ++i)
+            st.o[hh][i] = __builtin_fmaf(-1024.f, st.w_sum[hh], st.o[hh][i]) * (1.f / kWeightScale);
+    }
 }
 
 template <class T, int N, int NP, int BITS>
@@ -635,6 +723,7 @@ __device__ __forceinline__ void end_piece(WaveState<N>& st, DecodeShared<N, NP>&
     const int n0 = b * plan.per_seq + first_entry(plan, streaming_mask, hk);
     const int n_end = n0 + min(len, nominal_len(plan, streaming_mask, hk));
     const bool whole = n0 >= lo && n_end <= hi;
+    if constexpr (BITS != 16) lane_state_to_wave_state<N>(st, threadIdx.x % kWave);
     flush_block<T, N, NP, BITS>(st, sm, whole, H, b, hk, out, lse_out, part_o, part_ml, (size_t)blk + list);
     if (whole) return;
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // this thread's part of the piece has reached memory
