@@ -371,6 +371,42 @@ def test_selector_rebuilds_every_stale_logical_page_itself():
     assert torch.equal(got.scores, ref.scores)
 
 
+@pytest.mark.parametrize("length", [4800, 24000, 80000, 140000])
+def test_exact_ties_go_to_the_lower_page_index_in_every_ranking_path(length):
+    """All keys zero but for a handful of pages: almost every score is exactly 0, so the budget is filled from a
+    huge tie.  16-token pages at these lengths give 300, 1500, 5000 and 8750 candidate pages: one wavefront, four
+    and eight wavefronts ranking from registers, and the ranking from memory.  The selection must equal the
+    oracle's, which takes ties in index order, entry for entry."""
+    L = _lib()
+    dev = torch.device("cuda:0")
+    w = small_decode_workload(batch=2, lengths=(length, length // 2 + 5), budget_tokens=16 * 24, page_size=16,
+                              logical_page_size=16, sink_tokens=16, local_tokens=32)
+    inp = make_decode_inputs(w)
+    seq_cpu = inp.seq_lens_at(0)
+    inp.k_pool.zero_()
+    rng = np.random.default_rng(length)
+    for b in range(2):
+        n_pages = (int(seq_cpu[b]) + 15) // 16
+        for p in rng.choice(n_pages - 1, size=5, replace=False):  # a few pages that do stand out
+            inp.k_pool[inp.page_table[b, p].long()] = torch.randn((w.num_kv_heads, 16, 128)).to(inp.k_pool.dtype)
+    sess = _session(L, w, inp, dev)
+    sess.set_seq_lens(seq_cpu.to(dev))
+    sess.build_stats_full()
+    sess.select(inp.q[0].to(dev))
+    torch.cuda.synchronize()
+    stats_ref = oracle.page_stats(inp.k_pool, inp.page_table, seq_cpu, w.logical_page_size)
+    scores_ref, _ = oracle.page_scores(inp.q[0], stats_ref, inp.page_table, seq_cpu, w.page_size)
+    sel_ref, cnt_ref, _ = oracle.select_pages(scores_ref, seq_cpu, w.page_size, w.budget_tokens)
+    flags = w.streaming_flags()
+    sel, cnt = sess.sel_pages.cpu().numpy(), sess.sel_count.cpu().numpy()
+    for hk in range(w.num_kv_heads):
+        if flags[hk]:
+            continue
+        assert (scores_ref[:, hk] == 0).mean() > 0.9  # the tie is there
+        assert np.array_equal(cnt[:, hk], cnt_ref[:, hk])
+        assert np.array_equal(sel[:, hk], sel_ref[:, hk]), f"KV head {hk}"
+
+
 # ---- KV write-back with fused statistics (Sec. 3.2, Sec. 3.5.2) ---------------------------------
 
 def _append_case(L, w, dev, start, n_new, seed, k_pool, v_pool, stats, page_table):
