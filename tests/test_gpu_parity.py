@@ -407,6 +407,40 @@ def test_exact_ties_go_to_the_lower_page_index_in_every_ranking_path(length):
         assert np.array_equal(sel[:, hk], sel_ref[:, hk]), f"KV head {hk}"
 
 
+@pytest.mark.parametrize("case", [
+    dict(lengths=(1500, 300, 2100), budget_tokens=512),                                    # one list fits the budget whole
+    dict(lengths=(40000, 700), budget_tokens=512, page_size=16, logical_page_size=16),     # several wavefronts per list
+    dict(lengths=(140000, 5000), budget_tokens=512, page_size=16, logical_page_size=16),   # ranking from memory
+])
+def test_a_callers_score_array_reads_zero_past_the_last_page_and_for_streaming_heads(case):
+    """The scoring launch writes only the pages a sequence has; the zeros of the header's contract (entries at or
+    past P_b, rows of streaming heads) come from the ranking launch.  The array is poisoned first."""
+    L = _lib()
+    dev = torch.device("cuda:0")
+    w = small_decode_workload(batch=len(case["lengths"]), **case)
+    inp = make_decode_inputs(w)
+    seq_cpu = inp.seq_lens_at(0)
+    sess = _session(L, w, inp, dev)
+    sess.set_seq_lens(seq_cpu.to(dev))
+    sess.build_stats_full()
+    sess.scores.fill_(float("nan"))
+    sess.select(inp.q[0].to(dev))
+    torch.cuda.synchronize()
+    stats_ref = oracle.page_stats(inp.k_pool, inp.page_table, seq_cpu, w.logical_page_size)
+    scores_ref, _ = oracle.page_scores(inp.q[0], stats_ref, inp.page_table, seq_cpu, w.page_size)
+    got = sess.scores.cpu().numpy().astype(np.float64)
+    assert np.isfinite(got).all()
+    flags = w.streaming_flags()
+    for b in range(w.batch):
+        n_pages = (int(seq_cpu[b]) + w.page_size - 1) // w.page_size
+        for hk in range(w.num_kv_heads):
+            if flags[hk]:
+                assert not got[b, hk].any()
+            else:
+                assert not got[b, hk, n_pages:].any()
+                np.testing.assert_allclose(got[b, hk, :n_pages], scores_ref[b, hk, :n_pages], rtol=SCORE_REL_TOL, atol=1e-4)
+
+
 # ---- KV write-back with fused statistics (Sec. 3.2, Sec. 3.5.2) ---------------------------------
 
 def _append_case(L, w, dev, start, n_new, seed, k_pool, v_pool, stats, page_table):
