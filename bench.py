@@ -24,7 +24,8 @@ Extra objects in the JSON line:
   selector, whole_path            the selector run and the whole step against the same 8 TB/s
   cfg4_256k, cfg4_32k, cfg5       the other decode configurations, compact
   kv8, kv4, kv_bits_batch64       decode over quantised pages (headline shape; the same layer at batch 64)
-  prefill, append                 cfg3 prefill against the bf16 MFMA peak; KV write-back
+  prefill, append                 cfg3 prefill against the bf16 MFMA peak; KV write-back; the same prompt as eight chunks
+                                  in the order of the prefill flow (attention over cache + chunk, then write-back)
 """
 from __future__ import annotations
 
@@ -588,6 +589,24 @@ def bench_append(torch, L, dev, n_tokens, w_dec):
         paged_ms = timed(lambda: L.lserve_sparse_prefill_paged(desc, kv, qn, cu, n_tokens, n_tokens, on, None, ws_p), 2)
     except Exception as e:  # reported, never fatal
         paged_ms = repr(e)
+    # the same prompt in the order of the prefill flow: eight chunks, each attending the cache plus its own K / V
+    # (lserve_sparse_prefill_chunk) and written back afterwards (lserve_append_kv)
+    chunks, chunked_ms = 8, None
+    try:
+        ch = n_tokens // chunks
+        cu_c = torch.tensor([0, ch, 0, 0], dtype=torch.int32, device=dev)
+        lens = [torch.tensor([c * ch, 0, 0, 0], dtype=torch.int32, device=dev) for c in range(chunks + 1)]
+        kv_at = [L.PagedKV(k_pool, v_pool, stats, table, t[:1]) for t in lens]
+
+        def chunk_flow():
+            for c in range(chunks):
+                rows = slice(c * ch, (c + 1) * ch)
+                L.lserve_sparse_prefill_chunk(desc, kv_at[c], qn[rows], k_new[rows], v_new[rows], cu_c, ch, on[rows], None)
+                L.lserve_append_kv(desc, kv_at[c + 1], k_new[rows], v_new[rows], cu_c, lens[c], ch)
+
+        chunked_ms = timed(chunk_flow, 2)
+    except Exception as e:
+        chunked_ms = repr(e)
     n_sel = sum(1 for f in w.streaming_flags() if not f)
     moved = 2 * 2 * n_tokens * Hkv * D * 2 + pages * n_sel * g * 2 * D * 2  # K and V read + written, statistics written
     # the decode workload's per-step append: one token per sequence into its tail page
@@ -613,6 +632,8 @@ def bench_append(torch, L, dev, n_tokens, w_dec):
                               "frac_of_hbm_peak": moved / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS},
         "decode_append_us_per_call": us,
         "prefill_over_the_written_pages_ms": paged_ms,
+        "chunked_prefill_ms": chunked_ms,
+        "chunked_prefill": f"{chunks} chunks of {n_tokens // chunks} tokens, each attention over the cache + the chunk, then its write-back",
         "note": "not part of `value`: the decode benchmark reads a pre-written cache",
     }
 
