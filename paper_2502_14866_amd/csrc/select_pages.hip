@@ -491,6 +491,8 @@ hipError_t launch_select_pages(int dtype, const LayerParams& lp, const PagedPara
         LSERVE_TOPK_BALLOT(8, 1);
     } else if (candidates <= kWave * 8 * 4) {
         LSERVE_TOPK_BALLOT(8, 4);
+    } else if (candidates <= kWave * 8 * 8) {
+        LSERVE_TOPK_BALLOT(8, 8);
     } else if (candidates <= kWave * 16 * 8) {
         LSERVE_TOPK_BALLOT(16, 8);
     } else {  // beyond 8192 candidate pages the keys stay in memory
