@@ -18,8 +18,9 @@ Extra objects in the JSON line:
   roofline      one lserve_sparse_decode call: algorithmic KV bytes per launch / its mean duration inside the
                 timed loop (HIP events around replays of the episode graph with and without the decode calls)
                 against 8 TB/s; the calls right after a selector run and those that reuse a selection apart;
-                next to it the better of what a library reduction and a library copy of the same size reach on
-                the same box, in bytes moved per second (measured_read_ceiling_GBs; both are in measured_ceilings)
+                next to it the best of what a library reduction, a library copy of the same size and a bare read
+                of the same K / V slabs (lserve_probe_decode_read) reach on the same box, in bytes moved per
+                second (measured_read_ceiling_GBs; all three are in measured_ceilings)
   cpu_baseline  the CPU oracle on the host cores for a bounded sample of the same workload
   selector, whole_path            the selector run and the whole step against the same 8 TB/s
   cfg4_256k, cfg4_32k, cfg5       the other decode configurations, compact
@@ -290,6 +291,33 @@ def compact(loop, m):
     }
 
 
+def decode_read_probe(torch, L, loop, alg_bytes):
+    """What the memory system charges for the decode call's reads alone: lserve_probe_decode_read issues the slab
+    reads of a decode call over the current selection and discards them.  Timed the way the loop meets them: right
+    after a selector run (cold pages), and again on the same selection (as on the C - 1 steps that reuse it)."""
+    sess, inp, lt, B, C = loop.sess, loop.inp, loop.len_table, loop.B, loop.C
+    ev = lambda: torch.cuda.Event(enable_timing=True)  # noqa: E731
+    first, reuse = [], []
+    sess.set_seq_lens(lt[1, :B])
+    for rep in range(12):
+        sess.select(inp.q[rep % loop.E], stats_valid_len=lt[0, :B])
+        marks = [ev() for _ in range(C + 1)]
+        marks[0].record()
+        for k in range(C):
+            L.lserve_probe_decode_read(sess.desc, sess.kv, sess.sel_pages, sess.sel_count, sess.sel_seq_len)
+            marks[k + 1].record()
+        torch.cuda.synchronize()
+        if rep >= 2:
+            first.append(marks[0].elapsed_time(marks[1]))
+            reuse.extend(marks[k].elapsed_time(marks[k + 1]) for k in range(1, C))
+    f_ms, r_ms = _median(first), _median(reuse)
+    mix_ms = (f_ms + (C - 1) * r_ms) / C
+    return {"first_after_selection_us": f_ms * 1e3, "reusing_selection_us": r_ms * 1e3,
+            "mix_of_the_loop_us": mix_ms * 1e3, "mix_of_the_loop_GBs": alg_bytes / (mix_ms * 1e-3) / 1e9,
+            "what": "lserve_probe_decode_read: the K / V slab reads of one decode call over the current selection, "
+                    "data discarded; eager launches, HIP events"}
+
+
 def measured_read_ceiling(torch, dev):
     """What plain library kernels reach on this machine: a reduction (read only) and a copy (read + write) over the
     working-set size of one decode launch and over 4 GB, in GB/s of bytes moved."""
@@ -393,7 +421,9 @@ def main():
     if not args.no_ceiling:
         try:
             ceiling = measured_read_ceiling(torch, dev)
-            best = max(ceiling["reduction_155MB_GBs"], ceiling["copy_155MB_GBs"])
+            probe = decode_read_probe(torch, L, loop, m["decode"]["algorithmic_bytes_per_launch"])
+            ceiling["decode_read_probe"] = probe
+            best = max(ceiling["reduction_155MB_GBs"], ceiling["copy_155MB_GBs"], probe["mix_of_the_loop_GBs"])
             result["roofline"]["measured_read_ceiling_GBs"] = best
             result["roofline"]["frac_of_measured_read_ceiling"] = m["decode"]["achieved_GBs"] / best
             result["measured_ceilings"] = ceiling

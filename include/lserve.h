@@ -380,6 +380,18 @@ int lserve_sparse_decode_noalloc(const lserve_attn_desc *desc, const lserve_page
                                  void *stream);
 
 /*
+ * Measurement aid, not part of the attention path (Sec. 3.6 defines what the decode call reads): issues the reads
+ * of lserve_sparse_decode for the same arguments (the K and V slabs of every page the index tables of the batch
+ * list, through the same page tables) from one short workgroup per table entry, and discards the data.  Nothing
+ * is written.  Its duration is what the memory system charges for the decode call's access pattern alone; bench.py
+ * reports it next to the call.  Lists are read up to their nominal length plus eight pages created since the
+ * selection.  Arguments and errors as for lserve_sparse_decode, without q, out, lse_out and workspace.
+ */
+int lserve_probe_decode_read(const lserve_attn_desc *desc, const lserve_paged_kv *kv, const int32_t *sel_pages,
+                             const int32_t *sel_count, const int32_t *sel_seq_len, int32_t sel_stride,
+                             void *stream);
+
+/*
  * Bytes of device workspace a call needs (Sec. 3.6 / 3.5.2 calls keep partial results there).
  *   batch, max_pages_per_seq: as in lserve_paged_kv (ignored for prefill)
  *   sel_stride_or_budget_pages: K for select, sel_stride for decode (ignored otherwise)

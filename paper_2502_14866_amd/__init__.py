@@ -25,6 +25,7 @@ from .binding import (  # noqa: F401
     lserve_build_page_stats,
     lserve_init,
     lserve_last_hip_error,
+    lserve_probe_decode_read,
     lserve_select_pages,
     lserve_sparse_decode,
     lserve_sparse_decode_noalloc,

@@ -35,6 +35,7 @@ EXPORTED_SYMBOLS = (
     "lserve_last_hip_error",
     "lserve_init",
     "lserve_sparse_decode_noalloc",
+    "lserve_probe_decode_read",
 )
 
 
@@ -112,6 +113,8 @@ def load_library():
         lib.lserve_last_hip_error.restype = ctypes.c_int
         lib.lserve_sparse_decode_noalloc.argtypes = [dp, kp, vp, vp, vp, vp, i32, vp, vp, vp]
         lib.lserve_sparse_decode_noalloc.restype = ctypes.c_int
+        lib.lserve_probe_decode_read.argtypes = [dp, kp, vp, vp, vp, i32, vp]
+        lib.lserve_probe_decode_read.restype = ctypes.c_int
         lib.lserve_init.argtypes = []
         lib.lserve_init.restype = ctypes.c_int
         for name in ("lserve_build_page_stats", "lserve_select_pages", "lserve_sparse_prefill",
@@ -327,3 +330,10 @@ def lserve_sparse_decode_noalloc(desc: AttnDesc, kv: PagedKV, q: torch.Tensor, s
     _check(load_library().lserve_sparse_decode_noalloc(desc.c(), kv.c(), _ptr(q), _ptr(sel_pages), _ptr(sel_count),
                                                        _ptr(sel_seq_len), sel_stride, _ptr(out), _ptr(lse_out),
                                                        _stream(stream)), "lserve_sparse_decode_noalloc")
+
+
+def lserve_probe_decode_read(desc: AttnDesc, kv: PagedKV, sel_pages: Optional[torch.Tensor],
+                             sel_count: Optional[torch.Tensor], sel_seq_len: Optional[torch.Tensor], stream=None) -> None:
+    sel_stride = 0 if sel_pages is None else sel_pages.shape[-1]
+    _check(load_library().lserve_probe_decode_read(desc.c(), kv.c(), _ptr(sel_pages), _ptr(sel_count), _ptr(sel_seq_len),
+                                                   sel_stride, _stream(stream)), "lserve_probe_decode_read")

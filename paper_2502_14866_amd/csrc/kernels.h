@@ -47,6 +47,10 @@ hipError_t launch_sparse_decode(int dtype, const LayerParams& lp, const PagedPar
                                 const int* sel_pages, const int* sel_count, const int* sel_seq_len,
                                 int sel_stride, void* out, float* lse_out, void* workspace, hipStream_t stream);
 
+// measurement aid: reads what the decode call above would read and discards it
+hipError_t launch_decode_read_probe(const LayerParams& lp, const PagedParams& kv, const int* sel_pages, const int* sel_count,
+                                    const int* sel_seq_len, int sel_stride, hipStream_t stream);
+
 // Caller-side description of a general block mask for prefill (device pointers).
 struct PrefillMaskArgs {
     const int* head_mask;

@@ -362,6 +362,21 @@ int lserve_sparse_decode_noalloc(const lserve_attn_desc* desc, const lserve_page
     return e == hipSuccess ? LSERVE_OK : fail_hip(e);
 }
 
+int lserve_probe_decode_read(const lserve_attn_desc* desc, const lserve_paged_kv* kv, const int32_t* sel_pages,
+                             const int32_t* sel_count, const int32_t* sel_seq_len, int32_t sel_stride, void* stream) {
+    LayerParams lp;
+    PagedParams pp;
+    int rc = make_layer(desc, &lp);
+    if (rc) return rc;
+    rc = make_paged(kv, lp, true, true, false, true, &pp);
+    if (rc) return rc;
+    const bool any_selecting = selecting_heads(lp).count > 0;
+    if (any_selecting && (!sel_pages || !sel_count || !sel_seq_len || sel_stride <= 0)) return LSERVE_ERR_INVALID_ARG;
+    if (sel_stride < 0 || !aligned16(sel_pages) || !aligned16(sel_count) || !aligned16(sel_seq_len)) return LSERVE_ERR_INVALID_ARG;
+    hipError_t e = launch_decode_read_probe(lp, pp, sel_pages, sel_count, sel_seq_len, sel_stride, (hipStream_t)stream);
+    return e == hipSuccess ? LSERVE_OK : fail_hip(e);
+}
+
 size_t lserve_workspace_bytes(int which_call, const lserve_attn_desc* desc, int32_t batch, int32_t max_pages_per_seq,
                               int32_t sel_stride_or_budget_pages, int32_t total_tokens) {
     LayerParams lp;

@@ -1083,7 +1083,50 @@ hipError_t launch_decode(const LayerParams& lp, const PagedParams& kv, const voi
 #undef LSERVE_DECODE_N
 }
 
+// Measurement aid, not part of the attention path: reads the K and V slabs a decode call with the same arguments
+// would read, one short workgroup per index-table entry, folds the words together and throws the result away.  The
+// time of this launch is what the memory system charges for the decode call's access pattern alone.
+__global__ __launch_bounds__(kDecodeThreads) void decode_read_probe_kernel(LayerParams lp, PagedParams kv,
+                                                                           const int* __restrict__ sel_pages,
+                                                                           const int* __restrict__ sel_count,
+                                                                           const int* __restrict__ sel_seq_len,
+                                                                           int sel_stride, int slab_u4,
+                                                                           unsigned* __restrict__ sink) {
+    const int list = blockIdx.y, i = blockIdx.x;
+    const int b = list / lp.Hkv, hk = list % lp.Hkv;
+    const PageList pl = make_page_list(lp, b, hk, kv.seq_lens[b], sel_pages, sel_count, sel_seq_len, sel_stride);
+    if (i >= pl.len) return;
+    const int pos = page_of(pl, i);
+    const bool ring = in_stream_pool(lp, kv, hk);
+    const int phys = ring ? kv.ring_table[(size_t)b * kv.ring + ring_slot(lp, pos)] : kv.page_table[(size_t)b * kv.max_pages + pos];
+    const size_t o = ((size_t)phys * (ring ? kv.stream_heads : kv.pool_heads) + pool_rank(lp, kv, hk, ring)) * slab_u4;
+    const uint4* k = reinterpret_cast<const uint4*>(ring ? kv.k_stream : kv.k_pool) + o;
+    const uint4* v = reinterpret_cast<const uint4*>(ring ? kv.v_stream : kv.v_pool) + o;
+    unsigned acc = 0;
+    for (int j0 = 0; j0 < slab_u4; j0 += 4 * kDecodeThreads) {  // four 16-byte loads of K and of V in flight per thread
+        uint4 a[4], c[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const int j = min(j0 + u * kDecodeThreads + (int)threadIdx.x, slab_u4 - 1);
+            a[u] = k[j];
+            c[u] = v[j];
+        }
+#pragma unroll
+        for (int u = 0; u < 4; ++u) acc ^= a[u].x ^ a[u].y ^ a[u].z ^ a[u].w ^ c[u].x ^ c[u].y ^ c[u].z ^ c[u].w;
+    }
+    if (sink && acc == 0x9e3779b9u) *sink = acc;  // keeps the loads alive
+}
+
 }  // namespace
+
+hipError_t launch_decode_read_probe(const LayerParams& lp, const PagedParams& kv, const int* sel_pages,
+                                    const int* sel_count, const int* sel_seq_len, int sel_stride, hipStream_t stream) {
+    // entries of the longest list the launch looks at: the nominal length plus eight pages created since the selection
+    const int entries = std::max(sel_stride, lp.sink_pages + lp.local_pages) + 8;
+    hipLaunchKernelGGL(decode_read_probe_kernel, dim3(entries, kv.batch * lp.Hkv), dim3(kDecodeThreads), 0, stream, lp, kv,
+                       sel_pages, sel_count, sel_seq_len, sel_stride, (int)slab_chunks(lp.NP, kv.kv_bits), (unsigned*)nullptr);
+    return hipGetLastError();
+}
 
 long long decode_nominal_entries(const LayerParams& lp, int sel_stride) {
     long long acc = 0;

@@ -441,6 +441,27 @@ def test_a_callers_score_array_reads_zero_past_the_last_page_and_for_streaming_h
                 np.testing.assert_allclose(got[b, hk, :n_pages], scores_ref[b, hk, :n_pages], rtol=SCORE_REL_TOL, atol=1e-4)
 
 
+def test_the_read_probe_runs_over_the_same_tables_as_the_decode_call_and_changes_nothing():
+    """lserve_probe_decode_read is a measurement aid: it walks the index tables a decode call would walk and only
+    reads.  A ragged batch and a selection that is three pages old."""
+    L = _lib()
+    dev = torch.device("cuda:0")
+    w = small_decode_workload(batch=3, lengths=(1500, 300, 2100), budget_tokens=512, decode_steps=4)
+    inp = make_decode_inputs(w)
+    sess = _session(L, w, inp, dev)
+    sess.set_seq_lens(inp.seq_lens_at(0).to(dev))
+    sess.build_stats_full()
+    sess.select(inp.q[0].to(dev))
+    sess.set_seq_lens((inp.seq_lens_at(0) + 3 * w.page_size).clamp(max=inp.page_table.shape[1] * w.page_size).to(dev))
+    before = [t.clone() for t in (sess.kv.k_pool, sess.kv.v_pool, sess.sel_pages, sess.sel_count, sess.sel_seq_len)]
+    L.lserve_probe_decode_read(sess.desc, sess.kv, sess.sel_pages, sess.sel_count, sess.sel_seq_len)
+    torch.cuda.synchronize()
+    after = (sess.kv.k_pool, sess.kv.v_pool, sess.sel_pages, sess.sel_count, sess.sel_seq_len)
+    assert all(torch.equal(a, b) for a, b in zip(before, after))
+    with pytest.raises(L.LserveError):  # a selecting head needs the selection
+        L.lserve_probe_decode_read(sess.desc, sess.kv, None, None, None)
+
+
 # ---- KV write-back with fused statistics (Sec. 3.2, Sec. 3.5.2) ---------------------------------
 
 def _append_case(L, w, dev, start, n_new, seed, k_pool, v_pool, stats, page_table):
