@@ -385,7 +385,8 @@ int lserve_sparse_decode_noalloc(const lserve_attn_desc *desc, const lserve_page
  * list, through the same page tables) from one short workgroup per table entry, and discards the data.  Nothing
  * is written.  Its duration is what the memory system charges for the decode call's access pattern alone; bench.py
  * reports it next to the call.  Lists are read up to their nominal length plus eight pages created since the
- * selection.  Arguments and errors as for lserve_sparse_decode, without q, out, lse_out and workspace.
+ * selection.  Arguments and errors as for lserve_sparse_decode, without q, out, lse_out and workspace;
+ * LSERVE_ERR_UNSUPPORTED for more than 65535 (sequence, KV head) lists.
  */
 int lserve_probe_decode_read(const lserve_attn_desc *desc, const lserve_paged_kv *kv, const int32_t *sel_pages,
                              const int32_t *sel_count, const int32_t *sel_seq_len, int32_t sel_stride,

@@ -373,6 +373,7 @@ int lserve_probe_decode_read(const lserve_attn_desc* desc, const lserve_paged_kv
     const bool any_selecting = selecting_heads(lp).count > 0;
     if (any_selecting && (!sel_pages || !sel_count || !sel_seq_len || sel_stride <= 0)) return LSERVE_ERR_INVALID_ARG;
     if (sel_stride < 0 || !aligned16(sel_pages) || !aligned16(sel_count) || !aligned16(sel_seq_len)) return LSERVE_ERR_INVALID_ARG;
+    if ((long long)pp.batch * lp.Hkv > 65535) return LSERVE_ERR_UNSUPPORTED;  // one grid row per (sequence, KV head)
     hipError_t e = launch_decode_read_probe(lp, pp, sel_pages, sel_count, sel_seq_len, sel_stride, (hipStream_t)stream);
     return e == hipSuccess ? LSERVE_OK : fail_hip(e);
 }
